@@ -1,0 +1,270 @@
+/*
+ * efcp_oracle.c -- CPU oracle for one EFCP / Sparse M-FAC step.
+ *
+ * TEST INFRASTRUCTURE ONLY; see efcp_oracle.h.  Plain C, single thread, no
+ * blocking, no fusion: every function is the definition (or the paper's
+ * recursion) written out so it can be checked against the paper by eye.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
+ */
+#include "efcp_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+struct eo_state {
+    int64_t d, k;
+    int32_t m;
+    double lambda;
+    int64_t t;          /* steps done */
+    float *e;           /* error feedback xi, d */
+    int32_t **idx;      /* m row pointers, NULL until the slot is filled */
+    float **val;
+    double *S;          /* m*m Gram matrix, by slot */
+    double *q, *coef;   /* m, by slot */
+    float *a;           /* d, accumulator scratch */
+    float *dense;       /* d, newest row scattered to dense, scratch */
+};
+
+eo_state *eo_create(int64_t d, int32_t m, int64_t k, double lambda)
+{
+    if (d < 1 || d >= ((int64_t)1 << 31) || k < 1 || k > d || m < 1 ||
+        !(lambda > 0.0) || !isfinite(lambda))
+        return NULL;
+    eo_state *st = calloc(1, sizeof *st);
+    if (!st) return NULL;
+    st->d = d; st->k = k; st->m = m; st->lambda = lambda;
+    st->e = calloc((size_t)d, sizeof(float));
+    st->a = calloc((size_t)d, sizeof(float));
+    st->dense = calloc((size_t)d, sizeof(float));
+    st->idx = calloc((size_t)m, sizeof(int32_t *));
+    st->val = calloc((size_t)m, sizeof(float *));
+    st->S = calloc((size_t)m * m, sizeof(double));
+    st->q = calloc((size_t)m, sizeof(double));
+    st->coef = calloc((size_t)m, sizeof(double));
+    if (!st->e || !st->a || !st->dense || !st->idx || !st->val || !st->S ||
+        !st->q || !st->coef) {
+        eo_destroy(st);
+        return NULL;
+    }
+    return st;
+}
+
+void eo_destroy(eo_state *st)
+{
+    if (!st) return;
+    if (st->idx) for (int32_t r = 0; r < st->m; r++) free(st->idx[r]);
+    if (st->val) for (int32_t r = 0; r < st->m; r++) free(st->val[r]);
+    free(st->idx); free(st->val);
+    free(st->e); free(st->a); free(st->dense);
+    free(st->S); free(st->q); free(st->coef);
+    free(st);
+}
+
+int64_t eo_step_count(const eo_state *st) { return st->t; }
+int32_t eo_filled(const eo_state *st) { return st->t < st->m ? (int32_t)st->t : st->m; }
+const float *eo_error(const eo_state *st) { return st->e; }
+const int32_t *eo_row_idx(const eo_state *st, int32_t slot)
+{ return (slot >= 0 && slot < st->m) ? st->idx[slot] : NULL; }
+const float *eo_row_val(const eo_state *st, int32_t slot)
+{ return (slot >= 0 && slot < st->m) ? st->val[slot] : NULL; }
+const double *eo_gram(const eo_state *st) { return st->S; }
+const double *eo_q(const eo_state *st) { return st->q; }
+const double *eo_coef(const eo_state *st) { return st->coef; }
+
+/* ------------------------------------------------------------------ */
+/* Top-k (Algorithm 1 line 6 with Compress = Top-k by magnitude).      */
+/* Definition: sort all (key_j, j) by key descending, then j ascending; */
+/* the first k pairs are the selection.                                */
+
+typedef struct { uint32_t key; int32_t j; } eo_pair;
+
+static int cmp_key_desc_j_asc(const void *pa, const void *pb)
+{
+    const eo_pair *a = pa, *b = pb;
+    if (a->key != b->key) return a->key > b->key ? -1 : 1;
+    if (a->j != b->j) return a->j < b->j ? -1 : 1;
+    return 0;
+}
+
+static int cmp_j_asc(const void *pa, const void *pb)
+{
+    const eo_pair *a = pa, *b = pb;
+    return a->j < b->j ? -1 : (a->j > b->j ? 1 : 0);
+}
+
+int eo_topk(const float *a, int64_t d, int64_t k, int32_t *idx, float *val)
+{
+    eo_pair *p = malloc((size_t)d * sizeof *p);
+    if (!p) return -1;
+    for (int64_t j = 0; j < d; j++) {
+        uint32_t bits;
+        memcpy(&bits, &a[j], 4);
+        p[j].key = bits & 0x7fffffffu;      /* magnitude as an ordered integer */
+        p[j].j = (int32_t)j;
+    }
+    qsort(p, (size_t)d, sizeof *p, cmp_key_desc_j_asc);
+    qsort(p, (size_t)k, sizeof *p, cmp_j_asc);      /* stored rows are index-ascending */
+    for (int64_t s = 0; s < k; s++) {
+        idx[s] = p[s].j;
+        val[s] = a[p[s].j];
+    }
+    free(p);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Coefficients of eq. (2) by the WSM recursion.                       */
+/*                                                                     */
+/* Rows c_1..c_n in processing order.  F_0 = lambda*I,                 */
+/* F_k = F_{k-1} + (1/m) c_k c_k^T.  With v_k = F_{k-1}^{-1} c_k and   */
+/* D_k = m + c_k^T v_k the rank-one inverse update reads               */
+/*   F_k^{-1} = F_{k-1}^{-1} - v_k v_k^T / D_k,                        */
+/* hence F_n^{-1} x = x/lambda - sum_k v_k (v_k^T x) / D_k.            */
+/* Each v_k lies in span(c_1..c_k): v_k = sum_{i<=k} B[k][i] c_i, and  */
+/*   v_k = c_k/lambda - sum_{j<k} v_j (v_j^T c_k)/D_j                  */
+/* needs only S_ij = c_i^T c_j.  Collecting terms of                   */
+/*   sum_k v_k p_k / D_k,  p_k = v_k^T x = sum_i B[k][i] q_i,          */
+/* by c_i gives coef_i = sum_{k>=i} B[k][i] p_k / D_k.                 */
+
+int eo_coefficients(const double *S, const double *q, int32_t n, int32_t m,
+                    double lambda, double *coef)
+{
+    if (n == 0) return 0;
+    double *B = calloc((size_t)n * n, sizeof(double));
+    double *D = calloc((size_t)n, sizeof(double));
+    double *p = calloc((size_t)n, sizeof(double));
+    if (!B || !D || !p) { free(B); free(D); free(p); return -1; }
+
+    for (int32_t k = 0; k < n; k++) {
+        B[(size_t)k * n + k] = 1.0 / lambda;
+        for (int32_t j = 0; j < k; j++) {
+            double vjck = 0.0;                       /* v_j^T c_k */
+            for (int32_t i = 0; i <= j; i++)
+                vjck += B[(size_t)j * n + i] * S[(size_t)i * n + k];
+            double f = vjck / D[j];
+            for (int32_t i = 0; i <= j; i++)
+                B[(size_t)k * n + i] -= f * B[(size_t)j * n + i];
+        }
+        double ckvk = 0.0;                           /* c_k^T v_k */
+        for (int32_t i = 0; i <= k; i++)
+            ckvk += B[(size_t)k * n + i] * S[(size_t)i * n + k];
+        D[k] = (double)m + ckvk;
+    }
+    for (int32_t k = 0; k < n; k++) {
+        double s = 0.0;
+        for (int32_t i = 0; i <= k; i++) s += B[(size_t)k * n + i] * q[i];
+        p[k] = s;
+    }
+    for (int32_t i = 0; i < n; i++) {
+        double s = 0.0;
+        for (int32_t k = i; k < n; k++) s += B[(size_t)k * n + i] * p[k] / D[k];
+        coef[i] = s;
+    }
+    free(B); free(D); free(p);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+
+/* Place (idx,val) into the slot of step t and refresh row/column of S:
+ * S[slot][r] = S[r][slot] = <c_r, c_new> for every filled row r
+ * (Section "Scalar Products (SP)": S_{i,:} = S_{:,i} = G g). */
+static int insert_row(eo_state *st, const int32_t *idx, const float *val)
+{
+    const int64_t k = st->k;
+    const int32_t m = st->m;
+    st->t += 1;
+    const int32_t slot = (int32_t)((st->t - 1) % m);
+    if (!st->idx[slot]) {
+        st->idx[slot] = malloc((size_t)k * sizeof(int32_t));
+        st->val[slot] = malloc((size_t)k * sizeof(float));
+        if (!st->idx[slot] || !st->val[slot]) return -1;
+    }
+    memcpy(st->idx[slot], idx, (size_t)k * sizeof(int32_t));
+    memcpy(st->val[slot], val, (size_t)k * sizeof(float));
+
+    for (int64_t p = 0; p < k; p++) st->dense[idx[p]] = val[p];
+    for (int32_t r = 0; r < m; r++) {
+        if (!st->idx[r]) continue;
+        double s = 0.0;
+        for (int64_t p = 0; p < k; p++)
+            s += (double)st->val[r][p] * (double)st->dense[st->idx[r][p]];
+        st->S[(size_t)slot * m + r] = s;
+        st->S[(size_t)r * m + slot] = s;
+    }
+    for (int64_t p = 0; p < k; p++) st->dense[idx[p]] = 0.0f;
+    return 0;
+}
+
+int eo_load_row(eo_state *st, const int32_t *idx, const float *val)
+{
+    return insert_row(st, idx, val);
+}
+
+int eo_step(eo_state *st, const float *g, const float *x, double *y)
+{
+    const int64_t d = st->d, k = st->k;
+    const int32_t m = st->m;
+    if (!x) x = g;
+
+    /* Algorithm 1 line 5: a = xi + g (fp32). */
+    for (int64_t j = 0; j < d; j++) st->a[j] = st->e[j] + g[j];
+
+    /* line 6: c = TopK(a). */
+    int32_t *idx = malloc((size_t)k * sizeof(int32_t));
+    float *val = malloc((size_t)k * sizeof(float));
+    if (!idx || !val) { free(idx); free(val); return -1; }
+    if (eo_topk(st->a, d, k, idx, val) != 0) { free(idx); free(val); return -1; }
+
+    /* line 7: xi = a - c. */
+    memcpy(st->e, st->a, (size_t)d * sizeof(float));
+    for (int64_t p = 0; p < k; p++) st->e[idx[p]] = 0.0f;
+
+    /* line 8, first half: update G (ring buffer) and S. */
+    int rc = insert_row(st, idx, val);
+    free(idx); free(val);
+    if (rc != 0) return -1;
+
+    /* Scalar products with x. */
+    for (int32_t r = 0; r < m; r++) {
+        st->q[r] = 0.0;
+        st->coef[r] = 0.0;
+        if (!st->idx[r]) continue;
+        double s = 0.0;
+        for (int64_t p = 0; p < k; p++)
+            s += (double)st->val[r][p] * (double)x[st->idx[r][p]];
+        st->q[r] = s;
+    }
+
+    /* Coefficients: gather the filled rows in age order (oldest first). */
+    const int32_t n = eo_filled(st);
+    const int32_t newest = (int32_t)((st->t - 1) % m);
+    int32_t *order = malloc((size_t)n * sizeof(int32_t));
+    double *Sn = malloc((size_t)n * n * sizeof(double));
+    double *qn = malloc((size_t)n * sizeof(double));
+    double *cn = malloc((size_t)n * sizeof(double));
+    if (!order || !Sn || !qn || !cn) { free(order); free(Sn); free(qn); free(cn); return -1; }
+    for (int32_t a = 0; a < n; a++)          /* age a: 0 = oldest, n-1 = newest */
+        order[a] = (int32_t)(((int64_t)newest - (n - 1) + a + (int64_t)m * 2) % m);
+    for (int32_t a = 0; a < n; a++) {
+        qn[a] = st->q[order[a]];
+        for (int32_t b = 0; b < n; b++)
+            Sn[(size_t)a * n + b] = st->S[(size_t)order[a] * m + order[b]];
+    }
+    rc = eo_coefficients(Sn, qn, n, m, st->lambda, cn);
+    for (int32_t a = 0; a < n; a++) st->coef[order[a]] = cn[a];
+    free(order); free(Sn); free(qn); free(cn);
+    if (rc != 0) return -1;
+
+    /* eq. (2): y = x/lambda - sum_r coef_r c_r. */
+    for (int64_t j = 0; j < d; j++) y[j] = (double)x[j] / st->lambda;
+    for (int32_t r = 0; r < m; r++) {
+        if (!st->idx[r]) continue;
+        const double c = st->coef[r];
+        for (int64_t p = 0; p < k; p++)
+            y[st->idx[r][p]] -= c * (double)st->val[r][p];
+    }
+    return 0;
+}
