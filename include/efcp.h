@@ -1,0 +1,134 @@
+/*
+ * efcp.h -- C ABI of libefcp: one EFCP / Sparse M-FAC optimizer step on one
+ * AMD MI355X (gfx950).
+ *
+ * One call to efcp_step performs, for the step t = 1, 2, ... it is called on
+ * (paper: Algorithm 1, lines 5-8; Section "Efficient Full-Matrix
+ * Preconditioners", WSM recursion and eq. (2); Section "Compressing
+ * Preconditioners via Sparsity", sparse window G = (I, V), SP and LCG):
+ *
+ *   a    = e + grad                         fp32, round to nearest even
+ *   c    = TopK(a)                          the k largest |a_j|; ties at the
+ *                                           threshold go to the lower index
+ *   e    = a - c                            +0 where selected, a_j elsewhere
+ *   slot (t-1) mod m of the window <- c     stored as (int32 index, fp32 value),
+ *                                           indices ascending, oldest row replaced
+ *   S[slot][r] = S[r][slot] = <c_r, c>      fp64, every filled row r
+ *   q[r] = <c_r, grad>                      fp64 (x = grad is the vector preconditioned)
+ *   coef = (1/lambda) (m*lambda*I + S)^-1 q fp64, the coefficients of eq. (2)
+ *   out  = grad/lambda - sum_r coef[r] c_r  = F^-1 grad,
+ *          F = lambda*I + (1/m) sum_r c_r c_r^T over the filled rows
+ *          (unfilled slots are zero rows, the divisor stays m).
+ *
+ * All pointers named "device" are HIP device pointers on the device that was
+ * current when efcp_create ran; pointers named "host" are ordinary host
+ * memory.  Every function returns EFCP_OK (0) or a negative efcp_status; no
+ * function throws, aborts or prints.  A context may be used by one host
+ * thread at a time.
+ */
+#ifndef EFCP_H
+#define EFCP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct efcp_ctx efcp_ctx;
+
+typedef enum {
+    EFCP_OK = 0,
+    EFCP_EINVAL = -1,   /* bad argument (range, NULL, aliasing, alignment) */
+    EFCP_ENOMEM = -2,   /* device or host allocation failed, or workspace too small */
+    EFCP_EHIP = -3,     /* a HIP runtime call or kernel launch reported an error */
+    EFCP_ENUMERIC = -4  /* the coefficient factorisation met a non-positive pivot */
+} efcp_status;
+
+/* Bytes of device memory a context for (d, m, k) needs; 0 if the arguments
+ * are invalid.  Uses the current device's LDS size to choose the slice width. */
+size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k);
+
+/* Create a context: error feedback e = 0, empty window, S = 0, step count 0.
+ *   d       dimension,            1 <= d < 2^31
+ *   m       window slots,         1 <= m <= 1024
+ *   k       entries kept per row, 1 <= k <= d
+ *   lambda  damping, finite, > 0  (F_0 = lambda*I)
+ *   workspace        device memory of at least efcp_workspace_bytes() bytes,
+ *                    256-byte aligned, owned by the caller and kept alive
+ *                    until efcp_destroy; or NULL, then the library allocates
+ *                    (hipMalloc) and frees it in efcp_destroy.
+ * Synchronises the device once (state initialisation). */
+int efcp_create(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
+                void *workspace, size_t workspace_bytes);
+
+/* One step (see the top of this file).
+ *   grad    device, d floats, 16-byte aligned, read only
+ *   out     device, d floats, 16-byte aligned, receives F^-1 grad; must not
+ *           overlap grad
+ *   stream  hipStream_t (NULL = the default stream)
+ * Asynchronous: enqueues kernels on `stream` and returns; no host
+ * synchronisation and no allocation.  Steps of one context must be issued in
+ * order on one stream, or on streams ordered by the caller. */
+int efcp_step(efcp_ctx *ctx, const float *grad, float *out, void *stream);
+
+/* Frees the context (and its workspace if the library allocated it) after
+ * synchronising the device.  efcp_destroy(NULL) is EFCP_OK. */
+int efcp_destroy(efcp_ctx *ctx);
+
+/* ---- inspection (parity tests, checkpointing); each synchronises `stream`
+ * of the last step before copying to host memory ---- */
+
+/* Row stored in `slot` (0 <= slot < m): k ascending indices and k values.
+ * EFCP_EINVAL if the slot has not been filled yet. */
+int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, float *val_host);
+
+/* Error feedback vector e, d floats. */
+int efcp_get_error(efcp_ctx *ctx, float *e_host);
+
+/* Small state; any pointer may be NULL.
+ *   S_host     m*m doubles, row-major by slot, zero for unfilled slots
+ *   q_host     m doubles (by slot), of the last step
+ *   coef_host  m doubles (by slot), of the last step
+ *   tau        magnitude key (bits & 0x7fffffff) of the k-th largest |a_j| of the last step
+ *   step       number of steps done
+ * Returns EFCP_ENUMERIC if any step so far met a non-positive pivot. */
+int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, double *coef_host,
+                   uint32_t *tau, int64_t *step);
+
+/* Geometry chosen at creation; any pointer may be NULL.
+ *   slice      coordinates per d-slice staged in LDS by the SP and LCG kernels
+ *   n_slices   ceil(d / slice)
+ *   row_stride entries between consecutive rows of I and V (k rounded up) */
+int efcp_get_geometry(efcp_ctx *ctx, int32_t *slice, int32_t *n_slices, int64_t *row_stride);
+
+/* ---- per-kernel timing with HIP events on the step's own stream ---- */
+
+enum {
+    EFCP_K_EF_HIST = 0,   /* a = e + grad, first radix histogram            */
+    EFCP_K_SELECT = 1,    /* remaining radix passes, counts, scans           */
+    EFCP_K_COMPACT = 2,   /* ordered compaction into the ring, e write-back  */
+    EFCP_K_SP = 3,        /* q and Gram row: pass over the window            */
+    EFCP_K_COEF = 4,      /* partial-sum reduction and m x m coefficient work */
+    EFCP_K_LCG = 5,       /* out = grad/lambda - sum coef_r c_r: pass over the window */
+    EFCP_K_COUNT = 6
+};
+
+/* enable != 0: later steps bracket each kernel group with hipEvents
+ * (allocated once here, not in efcp_step).  enable == 0: stop and reset. */
+int efcp_profile_enable(efcp_ctx *ctx, int enable);
+
+/* Synchronises the stream, then accumulates the elapsed time of every step
+ * recorded since the last call (at most the most recent 256 steps).
+ *   ms_total  EFCP_K_COUNT doubles: summed milliseconds per kernel group
+ *   steps     number of steps covered */
+int efcp_profile_read(efcp_ctx *ctx, double *ms_total, int64_t *steps);
+
+/* Static description of the last error of this context (never NULL). */
+const char *efcp_last_error(efcp_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,159 @@
+"""ctypes binding of libefcp (see include/efcp.h).  Argument marshalling only:
+every step of the path runs in the library's HIP kernels.  torch is used for
+device memory and streams and nothing else; there is no CPU fallback, and a
+missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libefcp.so")
+
+EFCP_OK, EFCP_EINVAL, EFCP_ENOMEM, EFCP_EHIP, EFCP_ENUMERIC = 0, -1, -2, -3, -4
+KERNEL_GROUPS = ("ef_hist", "select", "compact", "sp", "coef", "lcg")
+
+EXPORTS = (
+    "efcp_workspace_bytes", "efcp_create", "efcp_step", "efcp_destroy", "efcp_get_row",
+    "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_profile_enable",
+    "efcp_profile_read", "efcp_last_error",
+)
+
+_lib = None
+
+
+class EfcpError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"libefcp: {what} (status {code})")
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libefcp.so built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2306_06098_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+    lib.efcp_workspace_bytes.restype = ctypes.c_size_t
+    lib.efcp_workspace_bytes.argtypes = [i64, i32, i64]
+    lib.efcp_create.restype = ctypes.c_int
+    lib.efcp_create.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, vp, ctypes.c_size_t]
+    lib.efcp_step.restype = ctypes.c_int
+    lib.efcp_step.argtypes = [vp, vp, vp, vp]
+    lib.efcp_destroy.restype = ctypes.c_int
+    lib.efcp_destroy.argtypes = [vp]
+    lib.efcp_get_row.restype = ctypes.c_int
+    lib.efcp_get_row.argtypes = [vp, i32, vp, vp]
+    lib.efcp_get_error.restype = ctypes.c_int
+    lib.efcp_get_error.argtypes = [vp, vp]
+    lib.efcp_get_small.restype = ctypes.c_int
+    lib.efcp_get_small.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.efcp_get_geometry.restype = ctypes.c_int
+    lib.efcp_get_geometry.argtypes = [vp, vp, vp, vp]
+    lib.efcp_profile_enable.restype = ctypes.c_int
+    lib.efcp_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.efcp_profile_read.restype = ctypes.c_int
+    lib.efcp_profile_read.argtypes = [vp, vp, vp]
+    lib.efcp_last_error.restype = ctypes.c_char_p
+    lib.efcp_last_error.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def efcp_workspace_bytes(d: int, m: int, k: int) -> int:
+    return int(load_library().efcp_workspace_bytes(d, m, k))
+
+
+class Efcp:
+    """One libefcp context: efcp_create / efcp_step / efcp_destroy."""
+
+    def __init__(self, d: int, m: int, k: int, lam: float, workspace=None):
+        self._lib = load_library()
+        self.d, self.m, self.k, self.lam = int(d), int(m), int(k), float(lam)
+        self._ctx = ctypes.c_void_p()
+        self._workspace = workspace          # torch tensor kept alive, or None
+        ws_ptr, ws_bytes = None, 0
+        if workspace is not None:
+            ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        rc = self._lib.efcp_create(ctypes.byref(self._ctx), self.d, self.m, self.k, self.lam,
+                                   ws_ptr, ws_bytes)
+        if rc != EFCP_OK:
+            self._ctx = ctypes.c_void_p()
+            raise EfcpError(rc, "efcp_create failed")
+
+    def _check(self, rc: int):
+        if rc != EFCP_OK:
+            raise EfcpError(rc, self._lib.efcp_last_error(self._ctx).decode())
+
+    def step_ptr(self, grad_ptr: int, out_ptr: int, stream: int = 0) -> None:
+        self._check(self._lib.efcp_step(self._ctx, grad_ptr, out_ptr, stream))
+
+    def step(self, grad, out, stream=None) -> None:
+        """grad, out: contiguous float32 CUDA tensors of d elements.  Runs on
+        `stream` (a torch.cuda.Stream) or torch's current stream."""
+        import torch
+        assert grad.is_cuda and out.is_cuda and grad.dtype == torch.float32 and out.dtype == torch.float32
+        assert grad.is_contiguous() and out.is_contiguous() and grad.numel() == self.d == out.numel()
+        s = stream if stream is not None else torch.cuda.current_stream(grad.device)
+        self.step_ptr(grad.data_ptr(), out.data_ptr(), s.cuda_stream)
+
+    def destroy(self) -> None:
+        if getattr(self, "_ctx", None) and self._ctx.value:
+            rc = self._lib.efcp_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+            self._workspace = None
+            if rc != EFCP_OK:
+                raise EfcpError(rc, "efcp_destroy failed")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # ---- inspection ----
+    def get_row(self, slot: int):
+        idx = np.empty(self.k, dtype=np.int32)
+        val = np.empty(self.k, dtype=np.float32)
+        self._check(self._lib.efcp_get_row(self._ctx, slot, idx.ctypes.data, val.ctypes.data))
+        return idx, val
+
+    def get_error(self) -> np.ndarray:
+        e = np.empty(self.d, dtype=np.float32)
+        self._check(self._lib.efcp_get_error(self._ctx, e.ctypes.data))
+        return e
+
+    def get_small(self):
+        """Returns dict(S, q, coef, tau, step)."""
+        S = np.empty((self.m, self.m), dtype=np.float64)
+        q = np.empty(self.m, dtype=np.float64)
+        coef = np.empty(self.m, dtype=np.float64)
+        tau = ctypes.c_uint32()
+        step = ctypes.c_int64()
+        self._check(self._lib.efcp_get_small(self._ctx, S.ctypes.data, q.ctypes.data, coef.ctypes.data,
+                                             ctypes.addressof(tau), ctypes.addressof(step)))
+        return dict(S=S, q=q, coef=coef, tau=int(tau.value), step=int(step.value))
+
+    def geometry(self):
+        sl, ns, rs = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
+        self._check(self._lib.efcp_get_geometry(self._ctx, ctypes.addressof(sl), ctypes.addressof(ns),
+                                                ctypes.addressof(rs)))
+        return dict(slice=sl.value, n_slices=ns.value, row_stride=rs.value)
+
+    # ---- per-kernel timing ----
+    def profile_enable(self, on: bool = True) -> None:
+        self._check(self._lib.efcp_profile_enable(self._ctx, 1 if on else 0))
+
+    def profile_read(self):
+        """Returns (dict kernel group -> total ms, steps covered)."""
+        ms = (ctypes.c_double * len(KERNEL_GROUPS))()
+        steps = ctypes.c_int64()
+        self._check(self._lib.efcp_profile_read(self._ctx, ctypes.addressof(ms), ctypes.addressof(steps)))
+        return {n: ms[i] for i, n in enumerate(KERNEL_GROUPS)}, int(steps.value)

@@ -1,0 +1,356 @@
+// efcp.hip -- host side of libefcp: the C ABI declared in include/efcp.h.
+// Validates arguments, lays the state out in one device workspace, and
+// enqueues the kernels of one step (Algorithm 1, lines 5-8) on the caller's
+// stream.  No host synchronisation and no allocation happen inside efcp_step.
+#include "../../include/efcp.h"
+#include "efcp_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace efcp;
+
+namespace {
+
+constexpr int kProfSteps = 256;
+constexpr int kProfEvents = EFCP_K_COUNT + 1;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Largest power-of-two slice whose LDS working set fits the device.
+bool make_geometry(int64_t d, int32_t m, int64_t k, Geometry &g, const char **why)
+{
+    if (d < 1 || d >= ((int64_t)1 << 31)) { *why = "d out of range [1, 2^31)"; return false; }
+    if (m < 1 || m > kMaxM) { *why = "m out of range [1, 1024]"; return false; }
+    if (k < 1 || k > d) { *why = "k out of range [1, d]"; return false; }
+    int dev = 0, lds = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) {
+        *why = "no HIP device";
+        return false;
+    }
+    g.d = d; g.k = k; g.m = m;
+    g.row_stride = (int64_t)align_up((size_t)k, 64);
+    g.ldm = (int32_t)align_up((size_t)m, 8);
+    const size_t fixed_sp = 2 * kMaxM * sizeof(int32_t);
+    const size_t fixed_lcg = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
+    int lg = 14;                                   // 16384 coordinates: 128 KiB of LDS
+    while (lg > 12 && ((size_t)8 << lg) + fixed_lcg > (size_t)lds) lg--;
+    if (((size_t)8 << lg) + fixed_lcg > (size_t)lds) { *why = "device LDS too small"; return false; }
+    g.slice_log2 = lg;
+    g.slice = 1 << lg;
+    g.n_slices = (int32_t)((d + g.slice - 1) >> lg);
+    g.n_sel_blocks = (int32_t)((d + kSelChunk - 1) / kSelChunk);
+    g.n_groups = g.n_slices < 64 ? g.n_slices : 64;
+    g.lds_sp = ((size_t)8 << lg) + fixed_sp;
+    g.lds_lcg = ((size_t)8 << lg) + fixed_lcg;
+    return true;
+}
+
+struct Layout {
+    size_t e, ring_idx, ring_val, offT, S, L, partial, partial2, q, coef, rowmax, hist, sel, cnt_gt,
+        cnt_eq, sel_off, eq_before, lcg, status, total;
+    size_t small_begin;      // everything from here on is small and zero-initialised
+};
+
+Layout make_layout(const Geometry &g)
+{
+    Layout l{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    l.ring_idx = take((size_t)g.m * g.row_stride * sizeof(int32_t));
+    l.ring_val = take((size_t)g.m * g.row_stride * sizeof(float));
+    l.partial = take((size_t)g.n_slices * g.m * sizeof(double2));
+    l.small_begin = o;
+    l.e = take((size_t)g.d * sizeof(float));
+    l.offT = take((size_t)(g.n_slices + 1) * g.m * sizeof(int32_t));
+    l.S = take((size_t)g.m * g.m * sizeof(double));
+    l.L = take((size_t)g.m * g.ldm * sizeof(double));
+    l.partial2 = take((size_t)g.n_groups * g.m * sizeof(double2));
+    l.q = take((size_t)g.m * sizeof(double));
+    l.coef = take((size_t)g.m * sizeof(double));
+    l.rowmax = take((size_t)g.m * sizeof(uint32_t));
+    l.hist = take((size_t)(kBins1 + 2 * kBins2) * sizeof(uint32_t));
+    l.sel = take(sizeof(SelState));
+    l.cnt_gt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
+    l.cnt_eq = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
+    l.sel_off = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
+    l.eq_before = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
+    l.lcg = take(sizeof(LcgParams));
+    l.status = take(256);
+    l.total = o;
+    return l;
+}
+
+}  // namespace
+
+struct efcp_ctx {
+    Geometry g;
+    DevicePtrs p;
+    double lambda;
+    int device;
+    void *ws;
+    size_t ws_bytes;
+    bool own_ws;
+    int64_t t;
+    hipStream_t last_stream;
+    const char *err;
+    // profiling
+    bool prof_on;
+    std::vector<hipEvent_t> ev;      // kProfSteps * kProfEvents
+    int prof_count;                  // steps recorded since the last read
+};
+
+static int fail(efcp_ctx *ctx, int code, const char *msg)
+{
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+extern "C" size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k)
+{
+    Geometry g;
+    const char *why = "";
+    if (!make_geometry(d, m, k, g, &why)) return 0;
+    return make_layout(g).total;
+}
+
+extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
+                           void *workspace, size_t workspace_bytes)
+{
+    if (!out) return EFCP_EINVAL;
+    *out = nullptr;
+    if (!(lambda > 0.0) || !std::isfinite(lambda)) return EFCP_EINVAL;
+    Geometry g;
+    const char *why = "";
+    if (!make_geometry(d, m, k, g, &why)) return EFCP_EINVAL;
+    const Layout l = make_layout(g);
+
+    efcp_ctx *ctx = new (std::nothrow) efcp_ctx();
+    if (!ctx) return EFCP_ENOMEM;
+    ctx->g = g;
+    ctx->lambda = lambda;
+    ctx->t = 0;
+    ctx->last_stream = nullptr;
+    ctx->err = "no error";
+    ctx->prof_on = false;
+    ctx->prof_count = 0;
+    if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return EFCP_EHIP; }
+
+    if (workspace) {
+        if (workspace_bytes < l.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) {
+            delete ctx;
+            return workspace_bytes < l.total ? EFCP_ENOMEM : EFCP_EINVAL;
+        }
+        ctx->ws = workspace;
+        ctx->own_ws = false;
+    } else {
+        if (hipMalloc(&ctx->ws, l.total) != hipSuccess) {
+            (void)hipGetLastError();
+            delete ctx;
+            return EFCP_ENOMEM;
+        }
+        ctx->own_ws = true;
+    }
+    ctx->ws_bytes = l.total;
+
+    unsigned char *b = static_cast<unsigned char *>(ctx->ws);
+    DevicePtrs &p = ctx->p;
+    p.e = reinterpret_cast<float *>(b + l.e);
+    p.ring_idx = reinterpret_cast<int32_t *>(b + l.ring_idx);
+    p.ring_val = reinterpret_cast<float *>(b + l.ring_val);
+    p.offT = reinterpret_cast<int32_t *>(b + l.offT);
+    p.S = reinterpret_cast<double *>(b + l.S);
+    p.L = reinterpret_cast<double *>(b + l.L);
+    p.partial = reinterpret_cast<double2 *>(b + l.partial);
+    p.partial2 = reinterpret_cast<double2 *>(b + l.partial2);
+    p.q = reinterpret_cast<double *>(b + l.q);
+    p.coef = reinterpret_cast<double *>(b + l.coef);
+    p.rowmax = reinterpret_cast<uint32_t *>(b + l.rowmax);
+    p.hist1 = reinterpret_cast<uint32_t *>(b + l.hist);
+    p.hist2 = p.hist1 + kBins1;
+    p.hist3 = p.hist2 + kBins2;
+    p.sel = reinterpret_cast<SelState *>(b + l.sel);
+    p.cnt_gt = reinterpret_cast<uint32_t *>(b + l.cnt_gt);
+    p.cnt_eq = reinterpret_cast<uint32_t *>(b + l.cnt_eq);
+    p.sel_off = reinterpret_cast<uint32_t *>(b + l.sel_off);
+    p.eq_before = reinterpret_cast<uint32_t *>(b + l.eq_before);
+    p.lcg = reinterpret_cast<LcgParams *>(b + l.lcg);
+    p.status = reinterpret_cast<uint32_t *>(b + l.status);
+
+    // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.
+    // The ring rows and the per-slice partial sums are written before they are read.
+    hipError_t rc = hipMemset(b + l.small_begin, 0, l.total - l.small_begin);
+    if (rc == hipSuccess) rc = configure_sp(g);
+    if (rc == hipSuccess) rc = configure_lcg(g);
+    if (rc == hipSuccess) rc = hipDeviceSynchronize();
+    if (rc != hipSuccess) {
+        (void)hipGetLastError();
+        if (ctx->own_ws) (void)hipFree(ctx->ws);
+        delete ctx;
+        return EFCP_EHIP;
+    }
+    *out = ctx;
+    return EFCP_OK;
+}
+
+extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *stream_v)
+{
+    if (!ctx) return EFCP_EINVAL;
+    if (!grad || !outp) return fail(ctx, EFCP_EINVAL, "grad/out is NULL");
+    const uintptr_t ga = reinterpret_cast<uintptr_t>(grad), oa = reinterpret_cast<uintptr_t>(outp);
+    if ((ga & 15) || (oa & 15)) return fail(ctx, EFCP_EINVAL, "grad/out not 16-byte aligned");
+    const size_t bytes = (size_t)ctx->g.d * sizeof(float);
+    if (ga < oa + bytes && oa < ga + bytes) return fail(ctx, EFCP_EINVAL, "grad and out overlap");
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const Geometry &g = ctx->g;
+    const DevicePtrs &p = ctx->p;
+    const int64_t t = ctx->t + 1;
+    const int32_t slot = (int32_t)((t - 1) % g.m);
+    const int32_t n_filled = (int32_t)(t < g.m ? t : g.m);
+    const int32_t evict = t > g.m ? 1 : 0;
+
+    hipEvent_t *ev = nullptr;
+    if (ctx->prof_on) ev = &ctx->ev[(size_t)(ctx->prof_count % kProfSteps) * kProfEvents];
+    hipError_t rc = hipSuccess;
+    auto mark = [&](int i) { if (ev && rc == hipSuccess) rc = hipEventRecord(ev[i], stream); };
+
+    mark(0);
+    if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
+    mark(1);
+    if (rc == hipSuccess) rc = launch_select(g, p, slot, stream);
+    mark(2);
+    if (rc == hipSuccess) rc = launch_compact(g, p, slot, stream);
+    mark(3);
+    if (rc == hipSuccess) rc = launch_sp(g, p, grad, n_filled, slot, stream);
+    mark(4);
+    if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
+    if (rc == hipSuccess) rc = launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
+    mark(5);
+    if (rc == hipSuccess) rc = launch_lcg(g, p, grad, outp, n_filled, ctx->lambda, stream);
+    mark(6);
+
+    ctx->t = t;
+    ctx->last_stream = stream;
+    if (ctx->prof_on) ctx->prof_count++;
+    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
+    return EFCP_OK;
+}
+
+extern "C" int efcp_destroy(efcp_ctx *ctx)
+{
+    if (!ctx) return EFCP_OK;
+    int rcode = EFCP_OK;
+    if (hipDeviceSynchronize() != hipSuccess) rcode = EFCP_EHIP;
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    if (ctx->own_ws && hipFree(ctx->ws) != hipSuccess) rcode = EFCP_EHIP;
+    delete ctx;
+    return rcode;
+}
+
+static int sync_last(efcp_ctx *ctx)
+{
+    if (hipStreamSynchronize(ctx->last_stream) != hipSuccess)
+        return fail(ctx, EFCP_EHIP, "stream synchronisation failed");
+    return EFCP_OK;
+}
+
+extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, float *val_host)
+{
+    if (!ctx || !idx_host || !val_host) return EFCP_EINVAL;
+    const Geometry &g = ctx->g;
+    const int64_t filled = ctx->t < g.m ? ctx->t : g.m;
+    if (slot < 0 || slot >= filled) return fail(ctx, EFCP_EINVAL, "slot not filled");
+    if (int rc = sync_last(ctx)) return rc;
+    const size_t off = (size_t)slot * g.row_stride;
+    if (hipMemcpy(idx_host, ctx->p.ring_idx + off, (size_t)g.k * 4, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(val_host, ctx->p.ring_val + off, (size_t)g.k * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(ctx, EFCP_EHIP, "copy to host failed");
+    return EFCP_OK;
+}
+
+extern "C" int efcp_get_error(efcp_ctx *ctx, float *e_host)
+{
+    if (!ctx || !e_host) return EFCP_EINVAL;
+    if (int rc = sync_last(ctx)) return rc;
+    if (hipMemcpy(e_host, ctx->p.e, (size_t)ctx->g.d * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(ctx, EFCP_EHIP, "copy to host failed");
+    return EFCP_OK;
+}
+
+extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, double *coef_host,
+                              uint32_t *tau, int64_t *step)
+{
+    if (!ctx) return EFCP_EINVAL;
+    if (int rc = sync_last(ctx)) return rc;
+    const Geometry &g = ctx->g;
+    hipError_t rc = hipSuccess;
+    if (S_host) rc = hipMemcpy(S_host, ctx->p.S, (size_t)g.m * g.m * 8, hipMemcpyDeviceToHost);
+    if (rc == hipSuccess && q_host) rc = hipMemcpy(q_host, ctx->p.q, (size_t)g.m * 8, hipMemcpyDeviceToHost);
+    if (rc == hipSuccess && coef_host)
+        rc = hipMemcpy(coef_host, ctx->p.coef, (size_t)g.m * 8, hipMemcpyDeviceToHost);
+    SelState st;
+    uint32_t status = 0;
+    if (rc == hipSuccess) rc = hipMemcpy(&st, ctx->p.sel, sizeof st, hipMemcpyDeviceToHost);
+    if (rc == hipSuccess) rc = hipMemcpy(&status, ctx->p.status, 4, hipMemcpyDeviceToHost);
+    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to host failed");
+    if (tau) *tau = st.tau;
+    if (step) *step = ctx->t;
+    if (status & kStatusCount) return fail(ctx, EFCP_EHIP, "selection wrote a row whose length is not k");
+    if (status & kStatusRange) return fail(ctx, EFCP_ENUMERIC, "coefficients are not finite");
+    if (status & kStatusPivot) return fail(ctx, EFCP_ENUMERIC, "non-positive pivot in the factor update");
+    return EFCP_OK;
+}
+
+extern "C" int efcp_get_geometry(efcp_ctx *ctx, int32_t *slice, int32_t *n_slices, int64_t *row_stride)
+{
+    if (!ctx) return EFCP_EINVAL;
+    if (slice) *slice = ctx->g.slice;
+    if (n_slices) *n_slices = ctx->g.n_slices;
+    if (row_stride) *row_stride = ctx->g.row_stride;
+    return EFCP_OK;
+}
+
+extern "C" int efcp_profile_enable(efcp_ctx *ctx, int enable)
+{
+    if (!ctx) return EFCP_EINVAL;
+    ctx->prof_count = 0;
+    if (!enable) { ctx->prof_on = false; return EFCP_OK; }
+    if (ctx->ev.empty()) {
+        ctx->ev.reserve((size_t)kProfSteps * kProfEvents);
+        for (int i = 0; i < kProfSteps * kProfEvents; i++) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return fail(ctx, EFCP_EHIP, "hipEventCreate failed");
+            ctx->ev.push_back(e);
+        }
+    }
+    ctx->prof_on = true;
+    return EFCP_OK;
+}
+
+extern "C" int efcp_profile_read(efcp_ctx *ctx, double *ms_total, int64_t *steps)
+{
+    if (!ctx || !ms_total || !steps) return EFCP_EINVAL;
+    for (int i = 0; i < EFCP_K_COUNT; i++) ms_total[i] = 0.0;
+    *steps = 0;
+    if (!ctx->prof_on) return fail(ctx, EFCP_EINVAL, "profiling is not enabled");
+    if (int rc = sync_last(ctx)) return rc;
+    const int n = ctx->prof_count < kProfSteps ? ctx->prof_count : kProfSteps;
+    for (int s = 0; s < n; s++) {
+        hipEvent_t *ev = &ctx->ev[(size_t)s * kProfEvents];
+        for (int i = 0; i < EFCP_K_COUNT; i++) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess)
+                return fail(ctx, EFCP_EHIP, "hipEventElapsedTime failed");
+            ms_total[i] += ms;
+        }
+    }
+    *steps = n;
+    ctx->prof_count = 0;
+    return EFCP_OK;
+}
+
+extern "C" const char *efcp_last_error(efcp_ctx *ctx) { return ctx ? ctx->err : "null context"; }

@@ -1,0 +1,131 @@
+// efcp_internal.h -- shared declarations of the libefcp HIP sources (gfx950 only).
+//
+// Data layout in device memory (one context):
+//   e         float  [d]                 error feedback xi (Algorithm 1)
+//   ring_idx  int32  [m][row_stride]     window indices I, ascending inside a row
+//   ring_val  float  [m][row_stride]     window values  V
+//   offT      int32  [n_slices+1][m]     offT[s][r] = first entry of row r whose
+//                                        index is >= s*slice (slice-major so one
+//                                        workgroup reads its m offsets contiguously)
+//   S         double [m][m]              Gram matrix by slot
+//   L         double [m cols][ldm rows]  Cholesky factor of m*lambda*I + S in age
+//                                        order, stored column-major by slot:
+//                                        L(i,k) at L[k*ldm + i], defined for age(i) >= age(k)
+//   partial   double2[n_slices][m]       per-slice (q, Gram) partial sums
+//   partial2  double2[n_groups][m]       per-slice-group partial sums
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace efcp {
+
+constexpr int kSelChunk = 4096;      // coordinates per compaction block
+constexpr int kSelThreads = 256;     // threads per select/compaction block
+constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
+constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
+constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
+constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
+
+// Device-resident state of the radix select of the current step.
+struct SelState {
+    uint32_t prefix;     // key bits fixed so far
+    uint32_t kr;         // how many of the remaining candidates are still to take
+    uint32_t tau;        // final threshold key (k-th largest magnitude key)
+    uint32_t quota;      // how many keys == tau are selected (lowest indices first)
+    uint32_t n_gt;       // number of keys > tau
+    uint32_t total;      // entries written to the new row (must equal k)
+    uint32_t pad[2];
+};
+
+// Fixed-point scale of the LCG accumulator, written by the coefficient kernel.
+struct LcgParams {
+    double magic;        // 1.5 * 2^52 * unit: adding it aligns a product to `unit`
+    double unit;         // value of one accumulator count
+};
+
+enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
+
+struct Geometry {
+    int64_t d, k, row_stride;
+    int32_t m, ldm;
+    int32_t slice, slice_log2, n_slices;
+    int32_t n_sel_blocks;
+    int32_t n_groups;
+    size_t lds_sp, lds_lcg;
+};
+
+struct DevicePtrs {
+    float *e;
+    int32_t *ring_idx;
+    float *ring_val;
+    int32_t *offT;
+    double *S, *L;
+    double2 *partial, *partial2;
+    double *q, *coef;
+    uint32_t *rowmax;
+    uint32_t *hist1, *hist2, *hist3;
+    SelState *sel;
+    uint32_t *cnt_gt, *cnt_eq, *sel_off, *eq_before;
+    LcgParams *lcg;
+    uint32_t *status;
+};
+
+// Launchers (each enqueues on `stream` and returns hipGetLastError()).
+hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
+hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
+hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
+hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
+                     int32_t slot, hipStream_t stream);
+hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
+hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
+                       int32_t evict, double lambda, hipStream_t stream);
+hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
+                      int32_t n_filled, double lambda, hipStream_t stream);
+hipError_t configure_sp(const Geometry &g);
+hipError_t configure_lcg(const Geometry &g);
+
+// ---- small device helpers shared by the kernels ----
+
+__device__ __forceinline__ uint32_t mag_key(float a) { return __float_as_uint(a) & 0x7fffffffu; }
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t n = __shfl_up(v, o, 64);
+        if (lane >= o) v += n;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Exclusive prefix sum over the threads of a block (blockDim.x multiple of 64,
+// at most 1024).  `tmp` needs 33 uint32 of LDS.  Every thread must call it.
+__device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t *tmp, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const uint32_t incl = wave_incl_scan_u32(v);
+    if (lane == 63) tmp[w] = incl;
+    __syncthreads();
+    if (w == 0) {
+        const uint32_t s = lane < nw ? tmp[lane] : 0u;
+        const uint32_t si = wave_incl_scan_u32(s);
+        if (lane < nw) tmp[lane] = si - s;
+        if (lane == 63) tmp[32] = si;
+    }
+    __syncthreads();
+    const uint32_t res = tmp[w] + incl - v;
+    *total = tmp[32];
+    __syncthreads();
+    return res;
+}
+
+}  // namespace efcp

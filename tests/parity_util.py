@@ -1,0 +1,79 @@
+"""Step-by-step comparison of libefcp (GPU) with the CPU oracle on the same
+float32 gradient bytes.  Bars (from the benchmark definition):
+  * Top-k indices, stored values and the error-feedback buffer: bit-exact at
+    every step;
+  * F^-1 x: relative L2 error <= 1e-3 at every step (fp32 output against the
+    oracle's fp64; observed errors are ~1e-7);
+  * S, q: fp64 sums of exact products in a different order: 1e-10 relative to
+    the largest magnitude involved;  coef is reported, not gated, because it is
+    conditioning-dependent and the bar is on the output.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+OUT_TOL = 1e-3
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
+    den = np.linalg.norm(ref)
+    num = np.linalg.norm(np.asarray(a, dtype=np.float64) - ref)
+    return float(num / den) if den > 0 else float(num)
+
+
+def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
+               check_small=True, verbose=False):
+    """grads: iterable of float32 numpy arrays.  Returns dict of worst errors."""
+    dev = torch.device("cuda:0")
+    o = oracle_mod.Oracle(d, m, k, lam)
+    g_gpu = binding.Efcp(d, m, k, lam)
+    grad_d = torch.empty(d, dtype=torch.float32, device=dev)
+    out_d = torch.empty(d, dtype=torch.float32, device=dev)
+    worst = dict(out=0.0, S=0.0, q=0.0, coef=0.0)
+    t = 0
+    try:
+        for g in grads:
+            t += 1
+            g = np.ascontiguousarray(g, dtype=np.float32)
+            y = o.step(g)
+            grad_d.copy_(torch.from_numpy(g))
+            g_gpu.step(grad_d, out_d)
+            torch.cuda.synchronize()
+            slot = (t - 1) % m
+            idx, val = g_gpu.get_row(slot)
+            oi, ov = o.row(slot)
+            assert np.array_equal(idx, oi), f"step {t}: Top-k indices differ"
+            assert np.array_equal(bits(val), bits(ov)), f"step {t}: stored values differ"
+            if check_error_every and (t % check_error_every == 0 or t == 1):
+                assert np.array_equal(bits(g_gpu.get_error()), bits(o.error)), \
+                    f"step {t}: error feedback differs"
+            out = out_d.cpu().numpy()
+            assert np.isfinite(out).all(), f"step {t}: non-finite output"
+            err = rel_l2(out, y)
+            worst["out"] = max(worst["out"], err)
+            assert err <= OUT_TOL, f"step {t}: rel L2 of F^-1 x = {err:.3e}"
+            if check_small:
+                sm = g_gpu.get_small()
+                assert sm["step"] == t
+                S_ref, q_ref = o.gram, o.q
+                sS = np.abs(sm["S"] - S_ref).max() / max(np.abs(S_ref).max(), 1e-300)
+                sq = np.abs(sm["q"] - q_ref).max() / max(np.abs(q_ref).max(), 1e-300)
+                sc = np.abs(sm["coef"] - o.coef).max() / max(np.abs(o.coef).max(), 1e-300)
+                worst["S"] = max(worst["S"], sS)
+                worst["q"] = max(worst["q"], sq)
+                worst["coef"] = max(worst["coef"], sc)
+                assert sS <= 1e-10, f"step {t}: Gram matrix off by {sS:.3e}"
+                assert sq <= 1e-10, f"step {t}: q off by {sq:.3e}"
+                sel_key = bits(ov) & np.uint32(0x7FFFFFFF)
+                assert sm["tau"] == int(sel_key.min()), f"step {t}: threshold key differs"
+            if verbose:
+                print(f"  step {t}: out {err:.2e}", flush=True)
+    finally:
+        g_gpu.destroy()
+        o.close()
+    worst["steps"] = t
+    return worst

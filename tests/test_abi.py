@@ -1,0 +1,42 @@
+"""The C-ABI library loads and exports every symbol include/efcp.h declares.
+No compute call is made here (no GPU in this tier)."""
+import ctypes
+import os
+import re
+
+from paper_2306_06098_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "efcp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(efcp_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_documented_entry_points():
+    syms = _declared_symbols()
+    for must in ("efcp_create", "efcp_step", "efcp_destroy", "efcp_workspace_bytes"):
+        assert must in syms
+    assert set(syms) == set(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(binding.LIB_PATH), "build libefcp.so first (python -m paper_2306_06098_amd.build)"
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for s in _declared_symbols():
+        assert hasattr(lib, s), f"libefcp.so does not export {s}"
+
+
+def test_binding_signatures_cover_all_exports():
+    lib = binding.load_library()
+    for s in binding.EXPORTS:
+        assert getattr(lib, s).argtypes is not None
+
+
+def test_null_context_is_rejected_without_a_gpu():
+    lib = binding.load_library()
+    assert lib.efcp_destroy(None) == binding.EFCP_OK
+    assert lib.efcp_step(None, None, None, None) == binding.EFCP_EINVAL
+    assert lib.efcp_last_error(None) == b"null context"
