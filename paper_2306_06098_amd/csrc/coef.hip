@@ -2,218 +2,268 @@
 //   coef = (1/lambda) (m*lambda*I + S)^-1 q,
 // which is what the WSM recursion of Section "Efficient Full-Matrix
 // Preconditioners" produces (Woodbury identity applied to
-// F = lambda*I + (1/m) sum_r c_r c_r^T).
+// F = lambda*I + (1/m) sum_r c_r c_r^T).  fp64 throughout, O(m^2) per step.
 //
-// One workgroup of 1024 threads, fp64 throughout, O(m^2) work per step:
-// thread p owns window slot p.  The Cholesky factor L of A = m*lambda*I + S
-// is kept in age order (oldest row first) and stored by slot, so sliding the
-// window never moves data:
-//   * evicting the oldest row deletes the first row/column of A; the factor
-//     of what remains is the rank-one *update* chol(L22 L22^T + l l^T) with
-//     l the deleted column (an update, never a downdate: unconditionally
-//     stable);
-//   * appending the newest row is one forward substitution L z = s with the
-//     new Gram column s, and a new diagonal sqrt(A_nn - z^T z);
-//   * coef needs L w = q (forward, done in the same sweep) and L^T c = w
-//     (backward).
-// The update rotations and both forward substitutions share one sweep over
-// the columns in age order (one barrier per column); the backward sweep
-// walks each thread's own column downwards in 64-byte pieces.
+// State: W = L^-1, the inverse of the Cholesky factor of A = m*lambda*I + S
+// with rows in age order (oldest first), so A^-1 = W^T W.  W is stored
+// row-major by window slot (W(i,j) at W[i*ldm + j]); entries above the
+// diagonal *in age order*, and rows/columns of unfilled slots, are kept at
+// exactly zero, so every product below may run over full rows and columns.
+// Keeping the inverse factor instead of the factor turns the two triangular
+// solves of a step (a chain of m dependent column steps each) into plain
+// matrix-vector products that many workgroups share:
+//
+//   k_evict   (window already full)  delete the oldest row/column of A.
+//             If A = [[a11, a^T], [a, A22]], L = [[l11, 0], [l, L22]] then
+//             A22 = L22 (I + p p^T) L22^T with p = L22^-1 l, and with the
+//             Cholesky factor K of I + p p^T (closed form, below) the new
+//             inverse factor is K^-1 W22.  K is "diagonal plus rank-one
+//             below the diagonal", so K^-1 W22 is one running sum per column:
+//             columns are independent and need no barrier.  p comes from the
+//             first column of W itself: p = -W(:,old) / W(old,old).
+//   k_fwd     z = W s and w = W q for the new Gram column s and for q.
+//   k_bwd     new diagonal l = sqrt(a_nn - z^T z), w_n = (q_n - z^T w)/l,
+//             coef = (1/lambda) [W^T (w - z w_n/l) ; w_n/l], and the new last
+//             row of W: [-(W^T z)/l , 1/l].
+//
+// All reductions have a fixed shape, so results do not depend on scheduling.
 #include "efcp_internal.h"
 
 namespace efcp {
 
-struct ColMsg {      // published by the thread that owns the diagonal of a column
-    double ic, s, c;     // rotation: inverse cosine-like factor, sine-like factor, c
-    double z, w;         // forward-substitution results for the two right-hand sides
-};
-
-__device__ __forceinline__ double block_sum_fixed(double v, double *buf /*1024*/)
+__device__ __forceinline__ double wave_sum_f64(double v)
 {
-    // Fixed-shape tree over 1024 slots: same order every run.
-    buf[threadIdx.x] = v;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Sum over the 1024 threads of a block in a fixed order.  buf: 16 doubles.
+__device__ __forceinline__ double block_sum_f64_1024(double v, double *buf)
+{
+    v = wave_sum_f64(v);
+    if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
     __syncthreads();
-    for (int o = 512; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) buf[threadIdx.x] += buf[threadIdx.x + o];
-        __syncthreads();
-    }
-    const double r = buf[0];
+    double r = 0.0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) r += buf[i];
     __syncthreads();
     return r;
 }
 
-__global__ __launch_bounds__(1024) void k_coef(int32_t m, int32_t ldm, int32_t n, int32_t slot,
-                                               int32_t evict, double lambda,
-                                               const double2 *__restrict__ partial2, int32_t n_groups,
-                                               double *__restrict__ S, double *__restrict__ L,
-                                               double *__restrict__ q_out, double *__restrict__ coef_out,
-                                               const uint32_t *__restrict__ rowmax,
-                                               LcgParams *__restrict__ lcg, uint32_t *__restrict__ status)
+// ------------------------------------------------------------------
+// Delete the oldest row (slot `old`) from the inverse factor.
+// Ages a = 0..m-2 of the surviving rows map to slots (old + 1 + a) mod m.
+// With sigma_a = 1 + sum_{b<a} p_b^2:
+//   K_aa = sqrt(sigma_{a+1}/sigma_a),  K_ab = p_a p_b / sqrt(sigma_b sigma_{b+1})  (a > b)
+// and Y = K^-1 W22 row by row:  Y_a = (W_a - p_a R_a) / K_aa,
+//   R_{a+1} = R_a + p_a / sqrt(sigma_a sigma_{a+1}) * Y_a,  R_0 = 0.
+// The recurrence is affine in R: R_{a+1} = (sigma_a/sigma_{a+1}) R_a + (...) W_a,
+// so a block splits the rows into 16 chunks of 64 ages, one per wave: every
+// wave first runs its chunk from R = 0 (all its loads independent of the other
+// chunks), the chunk results are chained through LDS with the closed-form
+// factor sigma_start/sigma_end, and a second sweep recomputes the chunk from
+// the right starting value and stores it.  Block b owns columns [64b, 64b+64);
+// column `old` is left alone (k_bwd clears it).
+__global__ __launch_bounds__(1024) void k_evict(int32_t m, int32_t ldm, int32_t old,
+                                                double *__restrict__ W)
 {
-    __shared__ ColMsg msg[2];
-    __shared__ double red[1024];
-    __shared__ double bc[2];
+    __shared__ double s_p[kMaxM], s_ik[kMaxM], s_g[kMaxM], s_sig[kMaxM + 1];
+    __shared__ double s_wave[16];
+    __shared__ double s_B[16][64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform
+    const int n = m - 1;                      // surviving rows
+    const double w00 = W[(int64_t)old * ldm + old];
 
-    const int p = threadIdx.x;
-    // Rows present besides the new one: every other slot when the window was
-    // already full (evict), else slots 0..slot-1.
-    const bool is_new = (p == slot);
-    const bool is_old = (p < m) && !is_new && (evict ? true : (p < slot));
-    // Age among the old rows after the eviction: 0 = oldest.
-    const int age = evict ? ((p - slot - 1 + m) % m) : p;
+    // thread a: p_a, then sigma by an exclusive scan of p^2 in age order
+    double p = 0.0;
+    if (tid < n) p = -W[(int64_t)((old + 1 + tid) % m) * ldm + old] / w00;
+    const double p2 = p * p;
+    double incl = p2;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) s_wave[wv] = incl;
+    __syncthreads();
+    double before = 1.0;                      // sigma_0 = 1
+    for (int i = 0; i < wv; i++) before += s_wave[i];
+    const double sigma = before + (incl - p2);
+    const double nxt = sigma + p2;
+    s_p[tid] = p;
+    s_ik[tid] = sqrt(sigma / nxt);
+    s_g[tid] = p / sqrt(sigma * nxt);
+    s_sig[tid] = sigma;
+    if (tid == 1023) s_sig[1024] = nxt;
+    __syncthreads();
 
-    // ---- finish the fixed-order reduction over slice groups ----
-    double qv = 0.0, sv = 0.0;
-    if (p < m && (is_old || is_new)) {
-        for (int g = 0; g < n_groups; g++) {
-            const double2 t = partial2[(int64_t)g * m + p];
-            qv += t.x;
-            sv += t.y;
+    const int col = blockIdx.x * 64 + lane;
+    const bool live = (col < m) && (col != old);
+    const int colc = min(col, m - 1);         // loads are unconditional (clamped), values masked:
+    const int a_lo = wv * 64;                 // conditional loads would be waited for one by one
+
+    // sweep 1: this wave's 64 ages starting from R = 0
+    double R = 0.0;
+    for (int a0 = a_lo; a0 < a_lo + 64; a0 += 16) {
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int a = a0 + u;
+            const double t = W[(int64_t)((old + 1 + min(a, n)) % m) * ldm + colc];
+            v[u] = (live && a < n) ? t : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int a = a0 + u;
+            const double y = (v[u] - s_p[a] * R) * s_ik[a];
+            R = fma(s_g[a], y, R);
         }
     }
-    if (p < m) {
-        q_out[p] = qv;
-        if (is_old || is_new) {
-            S[(int64_t)slot * m + p] = sv;
-            S[(int64_t)p * m + slot] = sv;
+    s_B[wv][lane] = R;
+    __syncthreads();
+    // chain the chunks before this one: R_in = sum_c B_c * sigma_end(c)/sigma_start(this)
+    R = 0.0;
+    for (int c = 0; c < wv; c++)
+        R = R * (s_sig[c * 64] / s_sig[c * 64 + 64]) + s_B[c][lane];
+
+    // sweep 2: recompute with the right start and store
+    for (int a0 = a_lo; a0 < a_lo + 64; a0 += 16) {
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int a = a0 + u;
+            const double t = W[(int64_t)((old + 1 + min(a, n)) % m) * ldm + colc];
+            v[u] = (live && a < n) ? t : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; u++) {
+            const int a = a0 + u;
+            const double y = (v[u] - s_p[a] * R) * s_ik[a];
+            R = fma(s_g[a], y, R);
+            if (live && a < n) W[(int64_t)((old + 1 + a) % m) * ldm + col] = y;
         }
     }
+}
+
+// ------------------------------------------------------------------
+// z = W s, w = W q.  One wave per row; sq[j] = (q_j, s_j).  The entry of the
+// slot being (re)written is excluded on both sides.
+__global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, int32_t slot,
+                                             const double *__restrict__ W,
+                                             const double2 *__restrict__ sq,
+                                             double2 *__restrict__ zw)
+{
+    __shared__ double2 s_sq[kMaxM];
+    for (int j = threadIdx.x; j < kMaxM; j += 256)
+        s_sq[j] = (j < m && j != slot) ? sq[j] : make_double2(0.0, 0.0);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (row >= m) return;
+    double az = 0.0, aw = 0.0;
+    if (row != slot) {
+        const double *wr = W + (int64_t)row * ldm;
+        for (int j = lane; j < m; j += 64) {
+            const double v = wr[j];
+            const double2 t = s_sq[j];
+            aw = fma(v, t.x, aw);
+            az = fma(v, t.y, az);
+        }
+    }
+    az = wave_sum_f64(az);
+    aw = wave_sum_f64(aw);
+    if (lane == 0) zw[row] = make_double2(az, aw);
+}
+
+// ------------------------------------------------------------------
+// Block b owns columns [64b, 64b+64); its 16 waves split the rows.
+__global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t slot, double lambda,
+                                              double *__restrict__ W,
+                                              const double2 *__restrict__ sq,
+                                              const double2 *__restrict__ zw,
+                                              double *__restrict__ S, double *__restrict__ q_out,
+                                              double *__restrict__ coef_out,
+                                              uint32_t *__restrict__ status)
+{
+    __shared__ double s_z[kMaxM], s_r[kMaxM];
+    __shared__ double buf[16];
+    __shared__ double2 red[16][64];
+
+    const int tid = threadIdx.x;
+    double z = 0.0, w = 0.0;
+    if (tid < m && tid != slot) {
+        const double2 t = zw[tid];
+        z = t.x;
+        w = t.y;
+    }
+    const double zz = block_sum_f64_1024(z * z, buf);
+    const double zwd = block_sum_f64_1024(z * w, buf);
+    const double2 sqn = sq[slot];                    // (q_n, s_nn)
     const double mlam = (double)m * lambda;
-    const double a_nn = sv + mlam;       // meaningful on the thread that owns the new row
-    const double q_nn = qv;
-
-    // ---- sweep over the old columns in age order ----
-    // w_upd: the deleted column l (only when evicting); rhs_s / rhs_q: right-hand sides.
-    double w_upd = (evict && is_old) ? L[(int64_t)slot * ldm + p] : 0.0;
-    double rhs_s = sv, rhs_q = qv;
-    double z_own = 0.0, w_own = 0.0, diag = 1.0;
-
-    int step = 0;
-    // two physical segments in ascending age: [slot+1, m-1] (only when evicting), then [0, slot-1]
-    for (int seg = evict ? 0 : 1; seg < 2; seg++) {
-        const int lo = seg == 0 ? slot + 1 : 0;
-        const int hi = seg == 0 ? m - 1 : slot - 1;
-        for (int kb = lo & ~7; kb <= hi; kb += 8) {
-            double v[8];
-#pragma unroll
-            for (int r = 0; r < 8; r++) {
-                const int kp = kb + r;
-                const int ak = evict ? ((kp - slot - 1 + m) % m) : kp;
-                v[r] = (kp >= lo && kp <= hi && is_old && age >= ak) ? L[(int64_t)kp * ldm + p] : 0.0;
-            }
-#pragma unroll
-            for (int r = 0; r < 8; r++) {
-                const int kp = kb + r;
-                if (kp < lo || kp > hi) continue;          // uniform
-                const int ak = evict ? ((kp - slot - 1 + m) % m) : kp;
-                ColMsg *mm = &msg[step & 1];
-                if (p == kp) {
-                    double lkk = v[r];
-                    double ic = 1.0, sn = 0.0, cs = 1.0;
-                    if (evict) {
-                        const double rr = sqrt(lkk * lkk + w_upd * w_upd);
-                        cs = rr / lkk;
-                        sn = w_upd / lkk;
-                        ic = lkk / rr;
-                        lkk = rr;
-                        L[(int64_t)kp * ldm + p] = lkk;
-                    }
-                    diag = lkk;
-                    z_own = rhs_s / lkk;
-                    w_own = rhs_q / lkk;
-                    mm->ic = ic; mm->s = sn; mm->c = cs; mm->z = z_own; mm->w = w_own;
-                    L[(int64_t)kp * ldm + slot] = z_own;       // new row of the factor
-                }
-                __syncthreads();
-                if (is_old && age > ak) {
-                    double lv = v[r];
-                    if (evict) {
-                        lv = (lv + mm->s * w_upd) * mm->ic;
-                        w_upd = mm->c * w_upd - mm->s * lv;
-                        L[(int64_t)kp * ldm + p] = lv;
-                    }
-                    rhs_s -= lv * mm->z;
-                    rhs_q -= lv * mm->w;
-                }
-                step++;
-            }
-        }
+    double piv = sqn.y + mlam - zz;
+    if (!(piv >= mlam)) {                            // the exact Schur complement is >= m*lambda
+        piv = mlam;
+        if (blockIdx.x == 0 && tid == 0) atomicOr(status, kStatusPivot);
     }
+    const double l = sqrt(piv);
+    const double wn = (sqn.x - zwd) / l;
+    const double f = wn / l;
+    s_z[tid] = z;
+    s_r[tid] = (tid < m && tid != slot) ? (w - z * f) : 0.0;
     __syncthreads();
 
-    // ---- diagonal of the new row and its forward-substitution entry ----
-    const double zz = block_sum_fixed(is_old ? z_own * z_own : 0.0, red);
-    const double zw = block_sum_fixed(is_old ? z_own * w_own : 0.0, red);
-    if (is_new) {
-        double piv = a_nn - zz;
-        if (!(piv >= mlam)) {        // the exact Schur complement is >= m*lambda
-            piv = mlam;
-            atomicOr(status, kStatusPivot);
-        }
-        diag = sqrt(piv);
-        w_own = (q_nn - zw) / diag;
-        L[(int64_t)slot * ldm + slot] = diag;
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = blockIdx.x * 64 + lane;
+    const int colc = min(col, m - 1);
+    double ac = 0.0, ay = 0.0;
+    // row `slot` needs no skip: s_r[slot] = s_z[slot] = 0 and the row holds finite values
+    for (int i = wv; i < m; i += 16) {
+        const double v = W[(int64_t)i * ldm + colc];
+        ac = fma(v, s_r[i], ac);
+        ay = fma(v, s_z[i], ay);
     }
-
-    // ---- backward substitution L^T c = w, newest row first ----
-    double csol = 0.0;       // this thread's solution entry once its turn has come
-    if (is_new) { csol = w_own / diag; bc[0] = csol; }
+    red[wv][lane] = make_double2(ac, ay);
     __syncthreads();
-    if (is_old) w_own -= z_own * bc[0];      // row `slot` of L is z
-    step = 1;
-    // descending age: [slot-1 .. 0], then [m-1 .. slot+1] (only when evicting)
-    for (int seg = 0; seg < (evict ? 2 : 1); seg++) {
-        const int lo = seg == 0 ? 0 : slot + 1;
-        const int hi = seg == 0 ? slot - 1 : m - 1;
-        if (hi < lo) continue;
-        for (int kb = hi & ~7; kb >= (lo & ~7); kb -= 8) {
-            double v[8];
-            // rows kb..kb+7 of this thread's own column: one 64-byte piece
-            const bool any = is_old;
-#pragma unroll
-            for (int r = 0; r < 8; r++) {
-                const int kp = kb + r;
-                const int ak = evict ? ((kp - slot - 1 + m) % m) : kp;
-                v[r] = (any && kp >= lo && kp <= hi && ak > age) ? L[(int64_t)p * ldm + kp] : 0.0;
-            }
-#pragma unroll
-            for (int r = 7; r >= 0; r--) {
-                const int kp = kb + r;
-                if (kp < lo || kp > hi) continue;          // uniform
-                const int ak = evict ? ((kp - slot - 1 + m) % m) : kp;
-                if (p == kp) { csol = w_own / diag; bc[step & 1] = csol; }
-                __syncthreads();
-                if (is_old && age < ak) w_own -= v[r] * bc[step & 1];
-                step++;
-            }
-        }
+    if (col < m && col == slot) {
+        // column of the slot that was rewritten: nothing older may refer to it
+        for (int i = wv; i < m; i += 16)
+            if (i != slot) W[(int64_t)i * ldm + col] = 0.0;
     }
-    __syncthreads();
-
-    const double coef = (is_old || is_new) ? csol / lambda : 0.0;
-    if (p < m) coef_out[p] = coef;
-
-    // ---- fixed-point scale for the LCG accumulator ----
-    const double vmax = (p < m && (is_old || is_new)) ? (double)__uint_as_float(rowmax[p]) : 0.0;
-    const double bound = block_sum_fixed(fabs(coef) * vmax, red);
-    if (p == 0) {
-        int ex = 0;
-        if (bound > 0.0 && bound < 1.0e300) {
-            ex = ilogb(bound) + 1;
-            ex = ex < -900 ? -900 : (ex > 900 ? 900 : ex);
-        } else if (bound != 0.0) {
-            atomicOr(status, kStatusRange);
+    if (wv == 0 && col < m) {
+        double c = 0.0, y = 0.0;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            c += red[i][lane].x;
+            y += red[i][lane].y;
         }
-        lcg->unit = ldexp(1.0, ex - 50);
-        lcg->magic = ldexp(1.5, ex + 2);      // 1.5 * 2^52 * unit
+        const double2 sqc = sq[col];
+        double coef;
+        if (col == slot) {
+            coef = f / lambda;
+            W[(int64_t)slot * ldm + slot] = 1.0 / l;
+        } else {
+            coef = c / lambda;
+            W[(int64_t)slot * ldm + col] = -y / l;
+        }
+        coef_out[col] = coef;
+        q_out[col] = sqc.x;
+        S[(int64_t)slot * m + col] = sqc.y;
+        S[(int64_t)col * m + slot] = sqc.y;
     }
 }
 
 hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
                        int32_t evict, double lambda, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_coef, dim3(1), dim3(1024), 0, stream, g.m, g.ldm, n_filled, slot, evict, lambda,
-                       p.partial2, g.n_groups, p.S, p.L, p.q, p.coef, p.rowmax, p.lcg, p.status);
+    if (evict)
+        hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, p.W);
+    hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, slot, p.W, p.sq,
+                       p.zw);
+    hipLaunchKernelGGL(k_bwd, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, lambda,
+                       p.W, p.sq, p.zw, p.S, p.q, p.coef, p.status);
     return hipGetLastError();
 }
 

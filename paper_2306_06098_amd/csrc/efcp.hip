@@ -34,24 +34,29 @@ bool make_geometry(int64_t d, int32_t m, int64_t k, Geometry &g, const char **wh
     g.d = d; g.k = k; g.m = m;
     g.row_stride = (int64_t)align_up((size_t)k, 64);
     g.ldm = (int32_t)align_up((size_t)m, 8);
-    const size_t fixed_sp = 2 * kMaxM * sizeof(int32_t);
+    const size_t fixed_sp = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2);
     const size_t fixed_lcg = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
-    int lg = 14;                                   // 16384 coordinates: 128 KiB of LDS
-    while (lg > 12 && ((size_t)8 << lg) + fixed_lcg > (size_t)lds) lg--;
-    if (((size_t)8 << lg) + fixed_lcg > (size_t)lds) { *why = "device LDS too small"; return false; }
+    const int lg = 14;                             // 16384 coordinates: 128 KiB of the 160 KiB LDS
+    if (((size_t)8 << lg) + fixed_sp > (size_t)lds || ((size_t)8 << lg) + fixed_lcg > (size_t)lds) {
+        *why = "device LDS too small (needs the 160 KiB of gfx950)";
+        return false;
+    }
     g.slice_log2 = lg;
     g.slice = 1 << lg;
     g.n_slices = (int32_t)((d + g.slice - 1) >> lg);
-    g.n_sel_blocks = (int32_t)((d + kSelChunk - 1) / kSelChunk);
-    g.n_groups = g.n_slices < 64 ? g.n_slices : 64;
+    g.n_sel_blocks = (int32_t)((d + kCandBlock - 1) / kCandBlock);
+    {
+        const int32_t per = (g.n_slices + 7) / 8;
+        g.sp_grid = 8 * (per < 32 ? per : 32);
+    }
     g.lds_sp = ((size_t)8 << lg) + fixed_sp;
     g.lds_lcg = ((size_t)8 << lg) + fixed_lcg;
     return true;
 }
 
 struct Layout {
-    size_t e, ring_idx, ring_val, offT, S, L, partial, partial2, q, coef, rowmax, hist, sel, cnt_gt,
-        cnt_eq, sel_off, eq_before, lcg, status, total;
+    size_t e, ring_idx, ring_val, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
+        cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, total;
     size_t small_begin;      // everything from here on is small and zero-initialised
 };
 
@@ -62,13 +67,16 @@ Layout make_layout(const Geometry &g)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     l.ring_idx = take((size_t)g.m * g.row_stride * sizeof(int32_t));
     l.ring_val = take((size_t)g.m * g.row_stride * sizeof(float));
-    l.partial = take((size_t)g.n_slices * g.m * sizeof(double2));
+    l.partial = take((size_t)g.sp_grid * g.m * sizeof(double2));
+    l.cand_idx = take((size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
+    l.cand_val = take((size_t)g.n_sel_blocks * kCandBlock * sizeof(float));
     l.small_begin = o;
     l.e = take((size_t)g.d * sizeof(float));
     l.offT = take((size_t)(g.n_slices + 1) * g.m * sizeof(int32_t));
     l.S = take((size_t)g.m * g.m * sizeof(double));
-    l.L = take((size_t)g.m * g.ldm * sizeof(double));
-    l.partial2 = take((size_t)g.n_groups * g.m * sizeof(double2));
+    l.W = take((size_t)g.m * g.ldm * sizeof(double));
+    l.sq = take((size_t)g.m * sizeof(double2));
+    l.zw = take((size_t)g.m * sizeof(double2));
     l.q = take((size_t)g.m * sizeof(double));
     l.coef = take((size_t)g.m * sizeof(double));
     l.rowmax = take((size_t)g.m * sizeof(uint32_t));
@@ -78,7 +86,7 @@ Layout make_layout(const Geometry &g)
     l.cnt_eq = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.sel_off = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.eq_before = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
-    l.lcg = take(sizeof(LcgParams));
+    l.cand_cnt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.status = take(256);
     l.total = o;
     return l;
@@ -163,9 +171,10 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
     p.ring_val = reinterpret_cast<float *>(b + l.ring_val);
     p.offT = reinterpret_cast<int32_t *>(b + l.offT);
     p.S = reinterpret_cast<double *>(b + l.S);
-    p.L = reinterpret_cast<double *>(b + l.L);
+    p.W = reinterpret_cast<double *>(b + l.W);
     p.partial = reinterpret_cast<double2 *>(b + l.partial);
-    p.partial2 = reinterpret_cast<double2 *>(b + l.partial2);
+    p.sq = reinterpret_cast<double2 *>(b + l.sq);
+    p.zw = reinterpret_cast<double2 *>(b + l.zw);
     p.q = reinterpret_cast<double *>(b + l.q);
     p.coef = reinterpret_cast<double *>(b + l.coef);
     p.rowmax = reinterpret_cast<uint32_t *>(b + l.rowmax);
@@ -177,7 +186,9 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
     p.cnt_eq = reinterpret_cast<uint32_t *>(b + l.cnt_eq);
     p.sel_off = reinterpret_cast<uint32_t *>(b + l.sel_off);
     p.eq_before = reinterpret_cast<uint32_t *>(b + l.eq_before);
-    p.lcg = reinterpret_cast<LcgParams *>(b + l.lcg);
+    p.cand_idx = reinterpret_cast<int32_t *>(b + l.cand_idx);
+    p.cand_val = reinterpret_cast<float *>(b + l.cand_val);
+    p.cand_cnt = reinterpret_cast<uint32_t *>(b + l.cand_cnt);
     p.status = reinterpret_cast<uint32_t *>(b + l.status);
 
     // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.

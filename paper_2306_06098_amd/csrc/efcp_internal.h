@@ -8,11 +8,15 @@
 //                                        index is >= s*slice (slice-major so one
 //                                        workgroup reads its m offsets contiguously)
 //   S         double [m][m]              Gram matrix by slot
-//   L         double [m cols][ldm rows]  Cholesky factor of m*lambda*I + S in age
-//                                        order, stored column-major by slot:
-//                                        L(i,k) at L[k*ldm + i], defined for age(i) >= age(k)
-//   partial   double2[n_slices][m]       per-slice (q, Gram) partial sums
-//   partial2  double2[n_groups][m]       per-slice-group partial sums
+//   W         double [m rows][ldm]       inverse of the Cholesky factor of
+//                                        m*lambda*I + S (rows in age order), stored
+//                                        row-major by slot; zero above the diagonal
+//                                        in age order and for unfilled slots
+//   cand_*    [ceil(d/16384)][16384]      Top-k candidates of the current step, one
+//                                        segment per block of 16,384 coordinates
+//   partial   double2[sp_grid][m]        per-workgroup (q, Gram) partial sums
+//   sq        double2[m]                 (q_r, S[slot][r]) of the current step
+//   zw        double2[m]                 (W s, W q) of the current step
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -20,7 +24,8 @@
 
 namespace efcp {
 
-constexpr int kSelChunk = 4096;      // coordinates per compaction block
+constexpr int kSelChunk = 4096;      // coordinates a 256-thread block streams at a time
+constexpr int kCandBlock = 16384;    // coordinates per candidate segment (== slice width)
 constexpr int kSelThreads = 256;     // threads per select/compaction block
 constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
 constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
@@ -35,13 +40,8 @@ struct SelState {
     uint32_t quota;      // how many keys == tau are selected (lowest indices first)
     uint32_t n_gt;       // number of keys > tau
     uint32_t total;      // entries written to the new row (must equal k)
-    uint32_t pad[2];
-};
-
-// Fixed-point scale of the LCG accumulator, written by the coefficient kernel.
-struct LcgParams {
-    double magic;        // 1.5 * 2^52 * unit: adding it aligns a product to `unit`
-    double unit;         // value of one accumulator count
+    uint32_t t_lo;       // keys >= t_lo are copied to the candidate list by the first pass
+    uint32_t redo;       // 1: the threshold bin lies below t_lo, candidates must be rebuilt
 };
 
 enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
@@ -51,7 +51,7 @@ struct Geometry {
     int32_t m, ldm;
     int32_t slice, slice_log2, n_slices;
     int32_t n_sel_blocks;
-    int32_t n_groups;
+    int32_t sp_grid;         // persistent SP workgroups: 8 * (workgroups per XCD)
     size_t lds_sp, lds_lcg;
 };
 
@@ -60,14 +60,16 @@ struct DevicePtrs {
     int32_t *ring_idx;
     float *ring_val;
     int32_t *offT;
-    double *S, *L;
-    double2 *partial, *partial2;
+    double *S, *W;
+    double2 *partial, *sq, *zw;
     double *q, *coef;
     uint32_t *rowmax;
     uint32_t *hist1, *hist2, *hist3;
     SelState *sel;
     uint32_t *cnt_gt, *cnt_eq, *sel_off, *eq_before;
-    LcgParams *lcg;
+    int32_t *cand_idx;       // [n_sel_blocks][kCandBlock] candidate indices, ascending per segment
+    float *cand_val;         // [n_sel_blocks][kCandBlock] candidate values
+    uint32_t *cand_cnt;      // [n_sel_blocks] entries used per segment
     uint32_t *status;
 };
 

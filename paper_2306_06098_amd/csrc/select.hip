@@ -3,88 +3,191 @@
 //
 // The magnitude of a float is ordered by the integer key = bits & 0x7fffffff.
 // A three-digit radix select (11 + 10 + 10 bits, most significant first)
-// finds the key tau of the k-th largest magnitude with LDS histograms merged
-// by integer atomics (order independent, hence deterministic).  The selected
-// set is {key > tau} plus the first `quota` elements with key == tau in index
-// order.  An ordered compaction (per-block counts -> exclusive scan ->
-// ballot-free wave prefix sums) writes the row with ascending indices and
-// zeroes the selected entries of the error buffer.
+// finds the key tau of the k-th largest magnitude; the selected set is
+// {key > tau} plus the first `quota` elements with key == tau in index order.
 //
-// All kernels are bound by HBM traffic; none uses floating-point arithmetic
-// beyond the one fp32 addition a = e + g per element.
+// Only the first pass touches the whole vector.  While it forms a = e + g and
+// the histogram of the first digit, it also copies every element whose key is
+// at least t_lo -- a bin edge two bins below the previous step's threshold --
+// to a candidate list, in index order, one segment per block of 16,384
+// coordinates.  All later passes (two digit histograms, per-block counts, the
+// ordered compaction into the ring and the zeroing of the selected entries of
+// e) read the candidates only: a few percent of d.  The first-digit histogram
+// is exact, so it tells whether the threshold bin lies at or above t_lo; if it
+// does not (the threshold dropped by more than two bins in one step), one
+// extra pass over a rebuilds the candidates from the now known bin.  The
+// result is exact either way; the prediction only saves traffic.
+//
+// Histograms are merged with integer atomics (order independent), candidates
+// and rows are written at positions computed by prefix sums, so every output
+// is deterministic.
 #include "efcp_internal.h"
 
 namespace efcp {
 
-// ------------------------------------------------------------------
-// a = e + g (written over e) and histogram of key bits 30..20.
+// Streaming layout of a d-sized pass: a block owns kCandBlock = 16,384
+// consecutive coordinates, walked as 4 chunks of 4,096; inside a chunk wave w
+// owns 1,024 consecutive coordinates and lane l holds, for it = 0..3, the four
+// coordinates wave_first + it*256 + l*4 + (0..3), loaded as one 16-byte load.
+// All four loads of a lane are issued before any is used.
+
+// Appends this wave's flagged elements of one chunk to the block's candidate
+// segment, in index order.  `flags`: bit it*4+c.  `base`: entries of the
+// segment already used by earlier chunks and by lower waves of this chunk.
+__device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t flags, int64_t wave_base,
+                                                uint32_t base, int32_t *__restrict__ seg_idx,
+                                                float *__restrict__ seg_val)
+{
+    uint32_t run = base;
+#pragma unroll
+    for (int it = 0; it < 4; it++) {
+        const uint32_t m4 = (flags >> (it * 4)) & 15u;
+        const uint32_t cnt = __popc(m4);
+        const uint32_t incl = wave_incl_scan_u32(cnt);
+        uint32_t pos = run + incl - cnt;
+        if (m4) {
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                if ((m4 >> c) & 1u) {
+                    seg_idx[pos] = (int32_t)(wave_base + it * 256 + c);
+                    seg_val[pos] = v[it][c];
+                    pos++;
+                }
+            }
+        }
+        run += __shfl(incl, 63, 64);
+    }
+}
+
+// a = e + g (written over e), histogram of key bits 30..20, candidates.
+// REDO = true: the pass that rebuilds the candidates from a (already in e)
+// with the threshold bin found by the first digit; it exits at once unless
+// the select state asks for it.
+template <bool REDO>
 __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict__ g,
                                                          float *__restrict__ e, int64_t d,
-                                                         uint32_t *__restrict__ hist)
+                                                         uint32_t *__restrict__ hist,
+                                                         const SelState *__restrict__ sel,
+                                                         int32_t *__restrict__ cand_idx,
+                                                         float *__restrict__ cand_val,
+                                                         uint32_t *__restrict__ cand_cnt)
 {
-    __shared__ uint32_t lh[kBins1];
-    for (int i = threadIdx.x; i < kBins1; i += kSelThreads) lh[i] = 0;
-    __syncthreads();
+    __shared__ uint32_t lh[REDO ? 1 : kBins1];
+    __shared__ uint32_t s_cnt[2][4];
+    uint32_t t_lo;
+    if (REDO) {
+        if (!sel->redo) return;
+        t_lo = sel->prefix << 20;
+    } else {
+        t_lo = sel->t_lo;
+        for (int i = threadIdx.x; i < kBins1; i += kSelThreads) lh[i] = 0;
+        __syncthreads();
+    }
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t block_first = (int64_t)blockIdx.x * kCandBlock;
+    int32_t *seg_idx = cand_idx + block_first;
+    float *seg_val = cand_val + block_first;
+    uint32_t used = 0;                                    // entries of the segment written so far
 
-    const int64_t n4 = d >> 2;
-    const float4 *g4 = reinterpret_cast<const float4 *>(g);
-    float4 *e4 = reinterpret_cast<float4 *>(e);
-    const int64_t stride = (int64_t)gridDim.x * kSelThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; i < n4; i += stride) {
-        const float4 gv = g4[i];
-        const float4 ev = e4[i];
-        float4 a;
-        a.x = ev.x + gv.x;
-        a.y = ev.y + gv.y;
-        a.z = ev.z + gv.z;
-        a.w = ev.w + gv.w;
-        e4[i] = a;
-        atomicAdd(&lh[mag_key(a.x) >> 20], 1u);
-        atomicAdd(&lh[mag_key(a.y) >> 20], 1u);
-        atomicAdd(&lh[mag_key(a.z) >> 20], 1u);
-        atomicAdd(&lh[mag_key(a.w) >> 20], 1u);
+    for (int cch = 0; cch < kCandBlock / kSelChunk; cch++) {
+        const int64_t wave_first = block_first + cch * kSelChunk + w * 1024;
+        const int64_t wave_base = wave_first + lane * 4;
+        const bool full = wave_first + 1024 <= d;        // scalar: whole wave inside the vector
+        float a[4][4];
+        if (full) {
+            float4 ev[4], gv[4];
+#pragma unroll
+            for (int it = 0; it < 4; it++) {
+                ev[it] = *reinterpret_cast<const float4 *>(e + wave_base + it * 256);
+                if (!REDO) gv[it] = *reinterpret_cast<const float4 *>(g + wave_base + it * 256);
+            }
+#pragma unroll
+            for (int it = 0; it < 4; it++) {
+                if (REDO) {
+                    a[it][0] = ev[it].x; a[it][1] = ev[it].y; a[it][2] = ev[it].z; a[it][3] = ev[it].w;
+                } else {
+                    a[it][0] = ev[it].x + gv[it].x;
+                    a[it][1] = ev[it].y + gv[it].y;
+                    a[it][2] = ev[it].z + gv[it].z;
+                    a[it][3] = ev[it].w + gv[it].w;
+                    *reinterpret_cast<float4 *>(e + wave_base + it * 256) =
+                        make_float4(a[it][0], a[it][1], a[it][2], a[it][3]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < 4; it++) {
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    const int64_t j = wave_base + it * 256 + c;
+                    float t = 0.0f;
+                    if (j < d) {
+                        t = REDO ? e[j] : e[j] + g[j];
+                        if (!REDO) e[j] = t;
+                    }
+                    a[it][c] = t;
+                }
+            }
+        }
+        uint32_t flags = 0;
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                const uint32_t key = mag_key(a[it][c]);
+                const bool in = full || (wave_base + it * 256 + c < d);
+                if (in) {
+                    if (!REDO) atomicAdd(&lh[key >> 20], 1u);
+                    if (key >= t_lo) flags |= 1u << (it * 4 + c);
+                }
+            }
+        }
+        const uint32_t wave_cnt = wave_sum_u32(__popc(flags));
+        if (lane == 0) s_cnt[cch & 1][w] = wave_cnt;
+        __syncthreads();
+        uint32_t base = used, total = 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const uint32_t c = s_cnt[cch & 1][i];
+            if (i < w) base += c;
+            total += c;
+        }
+        if (wave_cnt) emit_candidates(a, flags, wave_base, base, seg_idx, seg_val);
+        used += total;
     }
-    if (blockIdx.x == 0 && threadIdx.x < (d & 3)) {
-        const int64_t j = (n4 << 2) + threadIdx.x;
-        const float a = e[j] + g[j];
-        e[j] = a;
-        atomicAdd(&lh[mag_key(a) >> 20], 1u);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < kBins1; i += kSelThreads) {
-        const uint32_t c = lh[i];
-        if (c) atomicAdd(&hist[i], c);
+    if (threadIdx.x == 0) cand_cnt[blockIdx.x] = used;
+    if (!REDO) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < kBins1; i += kSelThreads) {
+            const uint32_t c = lh[i];
+            if (c) atomicAdd(&hist[i], c);
+        }
     }
 }
 
 // ------------------------------------------------------------------
-// Histogram of the next 10-bit digit over the elements whose higher key bits
-// equal the prefix found so far.  shift_hi: bits to drop to compare with the
-// prefix; shift_lo: position of the digit.
-__global__ __launch_bounds__(kSelThreads) void k_hist_digit(const float *__restrict__ a, int64_t d,
-                                                            const SelState *__restrict__ sel,
-                                                            uint32_t *__restrict__ hist,
-                                                            int shift_hi, int shift_lo)
+// Histogram of the next 10-bit digit over the candidates whose higher key
+// bits equal the prefix found so far.  One workgroup walks kHistSegs segments.
+constexpr int kHistSegs = 2;
+
+__global__ __launch_bounds__(kSelThreads) void k_cand_hist(const float *__restrict__ cand_val,
+                                                           const uint32_t *__restrict__ cand_cnt,
+                                                           int32_t nb, const SelState *__restrict__ sel,
+                                                           uint32_t *__restrict__ hist, int shift_hi,
+                                                           int shift_lo)
 {
     __shared__ uint32_t lh[kBins2];
     for (int i = threadIdx.x; i < kBins2; i += kSelThreads) lh[i] = 0;
     __syncthreads();
     const uint32_t prefix = sel->prefix;
-
-    const int64_t n4 = d >> 2;
-    const float4 *a4 = reinterpret_cast<const float4 *>(a);
-    const int64_t stride = (int64_t)gridDim.x * kSelThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; i < n4; i += stride) {
-        const float4 v = a4[i];
-        const uint32_t k0 = mag_key(v.x), k1 = mag_key(v.y), k2 = mag_key(v.z), k3 = mag_key(v.w);
-        if ((k0 >> shift_hi) == prefix) atomicAdd(&lh[(k0 >> shift_lo) & (kBins2 - 1)], 1u);
-        if ((k1 >> shift_hi) == prefix) atomicAdd(&lh[(k1 >> shift_lo) & (kBins2 - 1)], 1u);
-        if ((k2 >> shift_hi) == prefix) atomicAdd(&lh[(k2 >> shift_lo) & (kBins2 - 1)], 1u);
-        if ((k3 >> shift_hi) == prefix) atomicAdd(&lh[(k3 >> shift_lo) & (kBins2 - 1)], 1u);
-    }
-    if (blockIdx.x == 0 && threadIdx.x < (d & 3)) {
-        const uint32_t kk = mag_key(a[(n4 << 2) + threadIdx.x]);
-        if ((kk >> shift_hi) == prefix) atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
+    const int32_t b0 = blockIdx.x * kHistSegs, b1 = min(nb, b0 + kHistSegs);
+    for (int32_t b = b0; b < b1; b++) {
+        const uint32_t cnt = cand_cnt[b];
+        const float *seg = cand_val + (int64_t)b * kCandBlock;
+        for (uint32_t i = threadIdx.x; i < cnt; i += kSelThreads) {
+            const uint32_t kk = mag_key(seg[i]);
+            if ((kk >> shift_hi) == prefix) atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kBins2; i += kSelThreads) {
@@ -100,12 +203,16 @@ __global__ __launch_bounds__(kSelThreads) void k_hist_digit(const float *__restr
 template <int NB>
 __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist,
                                                      SelState *__restrict__ sel, int pass,
-                                                     uint32_t k)
+                                                     uint32_t k, uint32_t *__restrict__ rowmax_slot)
 {
     __shared__ uint32_t tmp[33];
+    __shared__ int top_bin;
+    if (threadIdx.x == 0) top_bin = 0;
+    __syncthreads();
     constexpr int PER = NB / 1024;
     const uint32_t kr = (pass == 0) ? k : sel->kr;
     const uint32_t prefix = (pass == 0) ? 0u : sel->prefix;
+    const uint32_t t_lo = sel->t_lo;
 
     // Walk the bins from the largest digit down: rb = NB-1-bin.
     uint32_t c[PER];
@@ -116,6 +223,7 @@ __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist
         c[i] = hist[bin];
         hist[bin] = 0;
         local += c[i];
+        if (pass == 0 && c[i]) atomicMax(&top_bin, bin);
     }
     uint32_t total;
     uint32_t above = block_excl_scan_u32(local, tmp, &total);   // count in larger digits
@@ -126,78 +234,58 @@ __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist
             const uint32_t np = (pass == 0) ? (uint32_t)bin : ((prefix << 10) | (uint32_t)bin);
             sel->prefix = np;
             sel->kr = kr - above;
+            if (pass == 0) {
+                // candidates hold every key >= t_lo: enough iff the threshold bin starts at or above t_lo
+                sel->redo = ((uint32_t)bin << 20) < t_lo ? 1u : 0u;
+            }
             if (pass == 2) {
                 sel->tau = np;
                 sel->quota = kr - above;
                 sel->n_gt = k - (kr - above);
+                const uint32_t tb = np >> 20;             // next step collects from two bins below
+                sel->t_lo = (tb >= 2 ? tb - 2 : 0u) << 20;
             }
         }
         above += c[i];
     }
-}
-
-// ------------------------------------------------------------------
-// Block b owns coordinates [b*kSelChunk, (b+1)*kSelChunk).  Wave w of the
-// block owns 1024 consecutive coordinates, read as 4 float4 per lane:
-// element (it, lane, c) is coordinate wave_base + it*256 + lane*4 + c.  The
-// count kernel and the compaction kernel use this same order.
-struct Chunk16 {
-    float v[4][4];
-    uint32_t gt, eq;      // 16-bit masks, bit it*4+c
-};
-
-__device__ __forceinline__ void load_chunk(const float *__restrict__ a, int64_t d, int64_t wave_base,
-                                           uint32_t tau, Chunk16 &ch)
-{
-    const int lane = threadIdx.x & 63;
-    ch.gt = 0;
-    ch.eq = 0;
-#pragma unroll
-    for (int it = 0; it < 4; it++) {
-        const int64_t j0 = wave_base + it * 256 + lane * 4;
-        if (j0 + 3 < d) {
-            const float4 t = *reinterpret_cast<const float4 *>(a + j0);
-            ch.v[it][0] = t.x; ch.v[it][1] = t.y; ch.v[it][2] = t.z; ch.v[it][3] = t.w;
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; c++) ch.v[it][c] = (j0 + c < d) ? a[j0 + c] : 0.0f;
-        }
-#pragma unroll
-        for (int c = 0; c < 4; c++) {
-            if (j0 + c < d) {
-                const uint32_t key = mag_key(ch.v[it][c]);
-                if (key > tau) ch.gt |= 1u << (it * 4 + c);
-                else if (key == tau) ch.eq |= 1u << (it * 4 + c);
-            }
-        }
+    if (pass == 0 && threadIdx.x == 0) {
+        // every |a_j| of this step is below the upper edge of the highest occupied bin:
+        // an upper bound on the largest stored magnitude, enough to scale the LCG sum
+        const uint32_t edge = ((uint32_t)top_bin + 1u) << 20;
+        *rowmax_slot = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
     }
 }
 
-__global__ __launch_bounds__(kSelThreads) void k_count(const float *__restrict__ a, int64_t d,
-                                                       const SelState *__restrict__ sel,
-                                                       uint32_t *__restrict__ cnt_gt,
-                                                       uint32_t *__restrict__ cnt_eq)
+// ------------------------------------------------------------------
+// Per candidate segment: how many keys are > tau and == tau.  One wave per segment.
+__global__ __launch_bounds__(kSelThreads) void k_cand_count(const float *__restrict__ cand_val,
+                                                            const uint32_t *__restrict__ cand_cnt,
+                                                            int32_t nb, const SelState *__restrict__ sel,
+                                                            uint32_t *__restrict__ cnt_gt,
+                                                            uint32_t *__restrict__ cnt_eq)
 {
-    __shared__ uint32_t s_gt[4], s_eq[4];
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int32_t b = blockIdx.x * 4 + w;
+    if (b >= nb) return;
     const uint32_t tau = sel->tau;
-    Chunk16 ch;
-    load_chunk(a, d, (int64_t)blockIdx.x * kSelChunk + w * 1024, tau, ch);
-    const uint32_t g = wave_sum_u32(__popc(ch.gt));
-    const uint32_t q = wave_sum_u32(__popc(ch.eq));
-    if (lane == 0) { s_gt[w] = g; s_eq[w] = q; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        cnt_gt[blockIdx.x] = s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3];
-        cnt_eq[blockIdx.x] = s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3];
+    const uint32_t cnt = cand_cnt[b];
+    const float *seg = cand_val + (int64_t)b * kCandBlock;
+    uint32_t g = 0, q = 0;
+    for (uint32_t i = lane; i < cnt; i += 64) {
+        const uint32_t key = mag_key(seg[i]);
+        g += key > tau;
+        q += key == tau;
     }
+    g = wave_sum_u32(g);
+    q = wave_sum_u32(q);
+    if (lane == 0) { cnt_gt[b] = g; cnt_eq[b] = q; }
 }
 
 // ------------------------------------------------------------------
-// One workgroup: exclusive scans over the compaction blocks.
-//   eq_before[b] = number of keys == tau in blocks before b
-//   sel_off[b]   = number of selected entries in blocks before b
-// and the slice offsets of the new row: offT[s][slot] = sel_off[first block of slice s].
+// One workgroup: exclusive scans over the candidate segments.
+//   eq_before[b] = number of keys == tau in segments before b
+//   sel_off[b]   = number of selected entries in segments before b
+// and the slice offsets of the new row: offT[s][slot] = sel_off[first segment of slice s].
 __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict__ cnt_gt,
                                                       const uint32_t *__restrict__ cnt_eq,
                                                       uint32_t *__restrict__ sel_off,
@@ -205,173 +293,139 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
                                                       SelState *__restrict__ sel, int32_t nb,
                                                       int32_t blocks_per_slice, int32_t n_slices,
                                                       int32_t m, int32_t slot,
-                                                      int32_t *__restrict__ offT,
-                                                      uint32_t *__restrict__ rowmax, uint32_t k,
+                                                      int32_t *__restrict__ offT, uint32_t k,
                                                       uint32_t *__restrict__ status)
 {
     __shared__ uint32_t tmp[33];
-    const int32_t per = (nb + 1023) / 1024;
-    const int32_t b0 = min(nb, (int32_t)threadIdx.x * per), b1 = min(nb, b0 + per);
     const uint32_t quota = sel->quota;
-
-    uint32_t local = 0;
-    for (int32_t b = b0; b < b1; b++) local += cnt_eq[b];
-    uint32_t total;
-    uint32_t run = block_excl_scan_u32(local, tmp, &total);
-    uint32_t lsel = 0;
-    for (int32_t b = b0; b < b1; b++) {
-        const uint32_t ce = cnt_eq[b];
-        eq_before[b] = run;
-        const uint32_t take = run >= quota ? 0u : min(quota - run, ce);
-        const uint32_t sc = cnt_gt[b] + take;
-        sel_off[b] = sc;            // count for now, offset after the second scan
-        lsel += sc;
-        run += ce;
-    }
-    run = block_excl_scan_u32(lsel, tmp, &total);
-    for (int32_t b = b0; b < b1; b++) {
-        const uint32_t sc = sel_off[b];
-        sel_off[b] = run;
-        if (b % blocks_per_slice == 0) offT[(int64_t)(b / blocks_per_slice) * m + slot] = (int32_t)run;
-        run += sc;
+    uint32_t carry_eq = 0, carry_sel = 0;
+    for (int32_t tile = 0; tile < nb; tile += 4096) {
+        const int32_t b = tile + (int32_t)threadIdx.x * 4;
+        uint32_t ce[4] = {0, 0, 0, 0}, cg[4] = {0, 0, 0, 0};
+        if (b + 3 < nb) {
+            const uint4 t0 = *reinterpret_cast<const uint4 *>(cnt_eq + b);
+            const uint4 t1 = *reinterpret_cast<const uint4 *>(cnt_gt + b);
+            ce[0] = t0.x; ce[1] = t0.y; ce[2] = t0.z; ce[3] = t0.w;
+            cg[0] = t1.x; cg[1] = t1.y; cg[2] = t1.z; cg[3] = t1.w;
+        } else {
+            for (int i = 0; i < 4; i++)
+                if (b + i < nb) { ce[i] = cnt_eq[b + i]; cg[i] = cnt_gt[b + i]; }
+        }
+        uint32_t total_eq, total_sel;
+        uint32_t run = carry_eq + block_excl_scan_u32(ce[0] + ce[1] + ce[2] + ce[3], tmp, &total_eq);
+        uint32_t sc[4], eb[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            eb[i] = run;
+            const uint32_t take = run >= quota ? 0u : min(quota - run, ce[i]);
+            sc[i] = cg[i] + take;
+            run += ce[i];
+        }
+        uint32_t run2 = carry_sel + block_excl_scan_u32(sc[0] + sc[1] + sc[2] + sc[3], tmp, &total_sel);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            if (b + i < nb) {
+                eq_before[b + i] = eb[i];
+                sel_off[b + i] = run2;
+                if ((b + i) % blocks_per_slice == 0)
+                    offT[(int64_t)((b + i) / blocks_per_slice) * m + slot] = (int32_t)run2;
+            }
+            run2 += sc[i];
+        }
+        carry_eq += total_eq;
+        carry_sel += total_sel;
     }
     if (threadIdx.x == 0) {
-        offT[(int64_t)n_slices * m + slot] = (int32_t)total;
-        sel->total = total;
-        rowmax[slot] = 0;
-        if (total != k) atomicOr(status, kStatusCount);
+        offT[(int64_t)n_slices * m + slot] = (int32_t)carry_sel;
+        sel->total = carry_sel;
+        if (carry_sel != k) atomicOr(status, kStatusCount);
     }
 }
 
 // ------------------------------------------------------------------
-// Ordered compaction of the selected entries of block b into the ring row,
-// and e = a - c: selected entries of the error buffer become +0.
-__global__ __launch_bounds__(kSelThreads) void k_compact(float *__restrict__ e, int64_t d,
-                                                         const SelState *__restrict__ sel,
-                                                         const uint32_t *__restrict__ sel_off,
-                                                         const uint32_t *__restrict__ eq_before,
-                                                         int32_t *__restrict__ row_idx,
-                                                         float *__restrict__ row_val,
-                                                         uint32_t *__restrict__ rowmax_slot)
+// Ordered compaction of the selected candidates of segment b into the ring
+// row, and e = a - c: selected entries of the error buffer become +0.
+// One wave per segment; candidates are already in index order.
+__global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__restrict__ cand_idx,
+                                                              const float *__restrict__ cand_val,
+                                                              const uint32_t *__restrict__ cand_cnt,
+                                                              int32_t nb, float *__restrict__ e,
+                                                              const SelState *__restrict__ sel,
+                                                              const uint32_t *__restrict__ sel_off,
+                                                              const uint32_t *__restrict__ eq_before,
+                                                              int32_t *__restrict__ row_idx,
+                                                              float *__restrict__ row_val)
 {
-    __shared__ uint32_t s_eq[4], s_sel[4];
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int32_t b = blockIdx.x * 4 + w;
+    if (b >= nb) return;
     const uint32_t tau = sel->tau, quota = sel->quota;
-    const int64_t wave_base = (int64_t)blockIdx.x * kSelChunk + w * 1024;
-    Chunk16 ch;
-    load_chunk(e, d, wave_base, tau, ch);
-
-    const uint32_t wave_eq = wave_sum_u32(__popc(ch.eq));
-    if (lane == 0) s_eq[w] = wave_eq;
-    __syncthreads();
-
-    uint32_t selm = ch.gt;
-    if (wave_eq != 0) {          // uniform over the wave
-        uint32_t run = eq_before[blockIdx.x];
-        for (int i = 0; i < w; i++) run += s_eq[i];
-        if (run < quota) {       // uniform: some ties of this wave may still be taken
-#pragma unroll
-            for (int it = 0; it < 4; it++) {
-                const uint32_t m4 = (ch.eq >> (it * 4)) & 15u;
-                const uint32_t cnt = __popc(m4);
-                const uint32_t incl = wave_incl_scan_u32(cnt);
-                uint32_t rank = run + incl - cnt;
-#pragma unroll
-                for (int c = 0; c < 4; c++) {
-                    if ((m4 >> c) & 1u) {
-                        if (rank < quota) selm |= 1u << (it * 4 + c);
-                        rank++;
-                    }
-                }
-                run += __shfl(incl, 63, 64);
-            }
+    const uint32_t cnt = cand_cnt[b];
+    const int32_t *sidx = cand_idx + (int64_t)b * kCandBlock;
+    const float *sval = cand_val + (int64_t)b * kCandBlock;
+    uint32_t eq_run = eq_before[b];
+    uint32_t out_run = sel_off[b];
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {
+        const uint32_t i = i0 + lane;
+        const bool in = i < cnt;
+        const float v = in ? sval[i] : 0.0f;
+        const int32_t j = in ? sidx[i] : 0;
+        const uint32_t key = mag_key(v);
+        const bool is_eq = in && key == tau;
+        const uint64_t eq_mask = __ballot(is_eq);
+        const uint32_t eq_rank = eq_run + __popcll(eq_mask & ((1ull << lane) - 1ull));
+        const bool take = in && (key > tau || (is_eq && eq_rank < quota));
+        const uint64_t take_mask = __ballot(take);
+        if (take) {
+            const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
+            row_idx[pos] = j;
+            row_val[pos] = v;
+            e[j] = 0.0f;
         }
+        eq_run += __popcll(eq_mask);
+        out_run += __popcll(take_mask);
     }
-
-    const uint32_t wave_sel = wave_sum_u32(__popc(selm));
-    if (lane == 0) s_sel[w] = wave_sel;
-    __syncthreads();
-    if (wave_sel == 0) return;   // uniform over the wave; no barrier follows
-
-    uint32_t run = sel_off[blockIdx.x];
-    for (int i = 0; i < w; i++) run += s_sel[i];
-    uint32_t kmax = 0;
-#pragma unroll
-    for (int it = 0; it < 4; it++) {
-        const uint32_t m4 = (selm >> (it * 4)) & 15u;
-        const uint32_t cnt = __popc(m4);
-        const uint32_t incl = wave_incl_scan_u32(cnt);
-        uint32_t pos = run + incl - cnt;
-        const int64_t j0 = wave_base + it * 256 + lane * 4;
-        if (m4) {
-#pragma unroll
-            for (int c = 0; c < 4; c++) {
-                if ((m4 >> c) & 1u) {
-                    row_idx[pos] = (int32_t)(j0 + c);
-                    row_val[pos] = ch.v[it][c];
-                    kmax = max(kmax, mag_key(ch.v[it][c]));
-                    ch.v[it][c] = 0.0f;
-                    pos++;
-                }
-            }
-            if (j0 + 3 < d) {
-                *reinterpret_cast<float4 *>(e + j0) =
-                    make_float4(ch.v[it][0], ch.v[it][1], ch.v[it][2], ch.v[it][3]);
-            } else {
-#pragma unroll
-                for (int c = 0; c < 4; c++)
-                    if ((m4 >> c) & 1u) e[j0 + c] = 0.0f;
-            }
-        }
-        run += __shfl(incl, 63, 64);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) kmax = max(kmax, (uint32_t)__shfl_xor(kmax, o, 64));
-    if (lane == 0) atomicMax(rowmax_slot, kmax);
 }
 
 // ------------------------------------------------------------------
-
-static int select_grid(int64_t d)
-{
-    const int64_t n4 = (d >> 2) + 1;
-    const int64_t want = (n4 + kSelThreads - 1) / kSelThreads;
-    return (int)(want < 2048 ? want : 2048);
-}
 
 hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ef_hist, dim3(select_grid(g.d)), dim3(kSelThreads), 0, stream, grad, p.e, g.d,
-                       p.hist1);
+    hipLaunchKernelGGL(k_ef_hist<false>, dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
+                       g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt);
     return hipGetLastError();
 }
 
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
-    const int grid = select_grid(g.d);
+    const int32_t nb = g.n_sel_blocks;
+    const int hist_grid = (nb + kHistSegs - 1) / kHistSegs;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
-                       (uint32_t)g.k);
-    hipLaunchKernelGGL(k_hist_digit, dim3(grid), dim3(kSelThreads), 0, stream, p.e, g.d, p.sel, p.hist2,
-                       20, 10);
+                       (uint32_t)g.k, p.rowmax + slot);
+    hipLaunchKernelGGL(k_ef_hist<true>, dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
+                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt);
+    hipLaunchKernelGGL(k_cand_hist, dim3(hist_grid), dim3(kSelThreads), 0, stream, p.cand_val, p.cand_cnt,
+                       nb, p.sel, p.hist2, 20, 10);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
-                       (uint32_t)g.k);
-    hipLaunchKernelGGL(k_hist_digit, dim3(grid), dim3(kSelThreads), 0, stream, p.e, g.d, p.sel, p.hist3,
-                       10, 0);
+                       (uint32_t)g.k, p.rowmax + slot);
+    hipLaunchKernelGGL(k_cand_hist, dim3(hist_grid), dim3(kSelThreads), 0, stream, p.cand_val, p.cand_cnt,
+                       nb, p.sel, p.hist3, 10, 0);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist3, p.sel, 2,
-                       (uint32_t)g.k);
-    hipLaunchKernelGGL(k_count, dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, p.e, g.d, p.sel,
-                       p.cnt_gt, p.cnt_eq);
+                       (uint32_t)g.k, p.rowmax + slot);
+    hipLaunchKernelGGL(k_cand_count, dim3((nb + 3) / 4), dim3(kSelThreads), 0, stream, p.cand_val,
+                       p.cand_cnt, nb, p.sel, p.cnt_gt, p.cnt_eq);
     hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, stream, p.cnt_gt, p.cnt_eq, p.sel_off,
-                       p.eq_before, p.sel, g.n_sel_blocks, g.slice / kSelChunk, g.n_slices, g.m, slot,
-                       p.offT, p.rowmax, (uint32_t)g.k, p.status);
+                       p.eq_before, p.sel, nb, g.slice / kCandBlock, g.n_slices, g.m, slot, p.offT,
+                       (uint32_t)g.k, p.status);
     return hipGetLastError();
 }
 
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_compact, dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, p.e, g.d, p.sel,
-                       p.sel_off, p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
-                       p.ring_val + (int64_t)slot * g.row_stride, p.rowmax + slot);
+    hipLaunchKernelGGL(k_cand_compact, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0, stream,
+                       p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
+                       p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
+                       p.ring_val + (int64_t)slot * g.row_stride);
     return hipGetLastError();
 }
 

@@ -2,33 +2,76 @@
 // with the newest row: q_r = <c_r, x> and the Gram row S[slot][r] = <c_r, c_new>
 // (Section "Scalar Products (SP)", Section "Sparse Scalar Products").
 //
-// Traversal is by d-slice, not by row: one workgroup stages x[slice] and the
+// Traversal is by d-slice, not by row: a workgroup stages x[slice] and the
 // newest row scattered to dense in LDS (interleaved float2, one 8-byte LDS
 // gather serves both products), then streams the index/value runs of all
 // filled rows that fall in the slice.  x is read from HBM once and every
 // gather is an LDS access.  A 16-lane group owns one row at a time and reads
-// its run with 16-byte loads; products of two fp32 values are exact in fp64
-// and are accumulated in fp64.  Per-(slice,row) partial sums go to a scratch
-// array and are added in a fixed order by k_sp_reduce, so the result does not
-// depend on scheduling.
+// its run with 16-byte loads, three chunks of the current row and three of
+// the next row in flight at once; products of two fp32 values are exact in
+// fp64 and are accumulated in fp64.
+//
+// Workgroups are persistent: each walks a fixed list of slices and keeps one
+// (q, Gram) accumulator per row in LDS, so the partial sums that reach memory
+// are one per (workgroup, row); k_sp_reduce adds them in a fixed order.  The
+// slice lists are static, which makes the sums independent of scheduling.
 #include "efcp_internal.h"
 
 namespace efcp {
 
-// Slice handled by a workgroup: consecutive slices share an XCD (workgroups
-// are dealt to the 8 XCDs round-robin), so the cache line that straddles two
-// neighbouring runs of a row is fetched into one L2 only.
-__device__ __forceinline__ int32_t slice_of_block(int32_t nsl)
+constexpr int kChunksAhead = 3;      // 16-byte loads per array a lane keeps in flight per row
+
+struct RunBatch {
+    int4 iv[kChunksAhead];
+    float4 vv[kChunksAhead];
+    int32_t p0, p1;
+};
+
+// Issue the loads of the first kChunksAhead chunks of a run.  Lane gl of the
+// 16-lane group reads entries [pc, pc+4), pc = (p0 & ~3) + 4*gl + 64*c.
+__device__ __forceinline__ void issue_run(const int32_t *__restrict__ idx_row,
+                                          const float *__restrict__ val_row, int32_t p0, int32_t p1,
+                                          int gl, RunBatch &b)
 {
-    const int32_t per = (nsl + 7) >> 3;
-    const int32_t xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
-    const int32_t s = xcd * per + i;
-    return (i < per && s < nsl) ? s : -1;
+    b.p0 = p0;
+    b.p1 = p1;
+#pragma unroll
+    for (int c = 0; c < kChunksAhead; c++) {
+        // always load (from the row start when the chunk lies past the run) so that the
+        // number of loads in flight is known and later waits need not drain the prefetch
+        const int32_t pc = (p0 & ~3) + gl * 4 + c * 64;
+        const int32_t pcs = pc < p1 ? pc : 0;
+        b.iv[c] = *reinterpret_cast<const int4 *>(idx_row + pcs);
+        b.vv[c] = *reinterpret_cast<const float4 *>(val_row + pcs);
+    }
 }
 
+__device__ __forceinline__ void sp_accumulate(const int4 &iv, const float4 &vv, int32_t pc, int32_t p0,
+                                              int32_t p1, int32_t base, int32_t mask,
+                                              const float2 *__restrict__ xc, double &aq, double &ag)
+{
+    const int32_t ii[4] = {iv.x, iv.y, iv.z, iv.w};
+    const float fv[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const int32_t p = pc + c;
+        const bool ok = (p >= p0) && (p < p1);
+        const int32_t li = ok ? ((ii[c] - base) & mask) : 0;
+        const double v = ok ? (double)fv[c] : 0.0;
+        const float2 t = xc[li];
+        aq = fma(v, (double)t.x, aq);
+        ag = fma(v, (double)t.y, ag);
+    }
+}
+
+// Workgroup b sits on XCD b%8 (workgroups are dealt to the 8 XCDs round-robin)
+// and is the (b/8)-th of `cpx` workgroups there.  XCD x owns the contiguous
+// slice range [x*per, (x+1)*per); at any time its workgroups work on
+// neighbouring slices, so a cache line straddling two runs of a row is
+// wanted by two CUs of the same L2 at about the same time.
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              int32_t n_filled, int32_t slot, int64_t row_stride,
-                                             int32_t slice_log2, int32_t nsl,
+                                             int32_t slice_log2, int32_t nsl, int32_t cpx,
                                              const int32_t *__restrict__ ring_idx,
                                              const float *__restrict__ ring_val,
                                              const int32_t *__restrict__ offT,
@@ -37,120 +80,143 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t slice = 1 << slice_log2;
     float2 *xc = reinterpret_cast<float2 *>(smem);                 // [slice]: (x_j, c_new_j)
-    int32_t *off0 = reinterpret_cast<int32_t *>(xc + slice);       // [1024]
+    double2 *racc = reinterpret_cast<double2 *>(xc + slice);       // [1024] per-row sums
+    int32_t *off0 = reinterpret_cast<int32_t *>(racc + kMaxM);     // [1024]
     int32_t *off1 = off0 + kMaxM;                                  // [1024]
 
-    const int32_t s = slice_of_block(nsl);
-    if (s < 0) return;
-    const int64_t base = (int64_t)s << slice_log2;
-    const int32_t len = (int32_t)min((int64_t)slice, d - base);
     const int tid = threadIdx.x;
-
-    for (int32_t i = tid * 4; i < slice; i += 4096) {
-        float4 xv;
-        if (i + 3 < len) {
-            xv = *reinterpret_cast<const float4 *>(x + base + i);
-        } else {
-            xv.x = (i + 0 < len) ? x[base + i + 0] : 0.0f;
-            xv.y = (i + 1 < len) ? x[base + i + 1] : 0.0f;
-            xv.z = (i + 2 < len) ? x[base + i + 2] : 0.0f;
-            xv.w = (i + 3 < len) ? x[base + i + 3] : 0.0f;
-        }
-        xc[i + 0] = make_float2(xv.x, 0.0f);
-        xc[i + 1] = make_float2(xv.y, 0.0f);
-        xc[i + 2] = make_float2(xv.z, 0.0f);
-        xc[i + 3] = make_float2(xv.w, 0.0f);
-    }
-    for (int32_t r = tid; r < m; r += 1024) {
-        off0[r] = offT[(int64_t)s * m + r];
-        off1[r] = offT[(int64_t)(s + 1) * m + r];
-    }
-    __syncthreads();
-    {   // scatter the newest row's entries of this slice next to x
-        const int64_t rb = (int64_t)slot * row_stride;
-        const int32_t p1 = off1[slot];
-        for (int32_t p = off0[slot] + tid; p < p1; p += 1024) {
-            const int32_t li = (ring_idx[rb + p] - (int32_t)base) & (slice - 1);
-            xc[li].y = ring_val[rb + p];
-        }
-    }
-    __syncthreads();
-
     const int grp = tid >> 4, gl = tid & 15;
-    for (int32_t r = grp; r < n_filled; r += kRowGroups) {
-        const int64_t rb = (int64_t)r * row_stride;
-        const int32_t p0 = off0[r], p1 = off1[r];
-        double aq = 0.0, ag = 0.0;
-        for (int32_t pc = (p0 & ~3) + gl * 4; pc < p1; pc += 64) {
-            const int4 iv = *reinterpret_cast<const int4 *>(ring_idx + rb + pc);
-            const float4 vv = *reinterpret_cast<const float4 *>(ring_val + rb + pc);
-            const int32_t ii[4] = {iv.x, iv.y, iv.z, iv.w};
-            const float fv[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-            for (int c = 0; c < 4; c++) {
-                const int32_t p = pc + c;
-                const bool ok = (p >= p0) && (p < p1);
-                const int32_t li = ok ? ((ii[c] - (int32_t)base) & (slice - 1)) : 0;
-                const double v = ok ? (double)fv[c] : 0.0;
-                const float2 t = xc[li];
-                aq = fma(v, (double)t.x, aq);
-                ag = fma(v, (double)t.y, ag);
+    const int32_t per = (nsl + 7) >> 3;
+    const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
+    const int32_t s_end = min(nsl, (xcd + 1) * per);
+    const int32_t mask = slice - 1;
+
+    racc[tid] = make_double2(0.0, 0.0);
+
+    for (int32_t s = xcd * per + cu; s < s_end; s += cpx) {
+        const int64_t base64 = (int64_t)s << slice_log2;
+        const int32_t base = (int32_t)base64;
+        const int32_t len = (int32_t)min((int64_t)slice, d - base64);
+        __syncthreads();            // previous slice fully consumed (and racc zeroed on entry)
+        for (int32_t i = tid * 4; i < slice; i += 4096) {
+            float4 xv;
+            if (i + 3 < len) {
+                xv = *reinterpret_cast<const float4 *>(x + base64 + i);
+            } else {
+                xv.x = (i + 0 < len) ? x[base64 + i + 0] : 0.0f;
+                xv.y = (i + 1 < len) ? x[base64 + i + 1] : 0.0f;
+                xv.z = (i + 2 < len) ? x[base64 + i + 2] : 0.0f;
+                xv.w = (i + 3 < len) ? x[base64 + i + 3] : 0.0f;
+            }
+            xc[i + 0] = make_float2(xv.x, 0.0f);
+            xc[i + 1] = make_float2(xv.y, 0.0f);
+            xc[i + 2] = make_float2(xv.z, 0.0f);
+            xc[i + 3] = make_float2(xv.w, 0.0f);
+        }
+        if (tid < m) {
+            off0[tid] = offT[(int64_t)s * m + tid];
+            off1[tid] = offT[(int64_t)(s + 1) * m + tid];
+        }
+        __syncthreads();
+        {   // scatter the newest row's entries of this slice next to x
+            const int64_t rb = (int64_t)slot * row_stride;
+            const int32_t p1 = off1[slot];
+            for (int32_t p = off0[slot] + tid; p < p1; p += 1024) {
+                const int32_t li = (ring_idx[rb + p] - base) & mask;
+                xc[li].y = ring_val[rb + p];
             }
         }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {
-            aq += __shfl_xor(aq, o, 16);
-            ag += __shfl_xor(ag, o, 16);
+        __syncthreads();
+
+        int32_t r = grp;
+        RunBatch cur, nxt;
+        {
+            const int32_t rc = min(r, n_filled - 1);
+            issue_run(ring_idx + (int64_t)rc * row_stride, ring_val + (int64_t)rc * row_stride,
+                      off0[rc], off1[rc], gl, cur);
         }
-        if (gl == 0) partial[(int64_t)s * m + r] = make_double2(aq, ag);
+        while (r < n_filled) {
+            const int32_t rn = r + kRowGroups;
+            {   // prefetch the next row of this group (a harmless repeat of the last row at the end)
+                const int32_t rc = min(rn, n_filled - 1);
+                issue_run(ring_idx + (int64_t)rc * row_stride, ring_val + (int64_t)rc * row_stride,
+                          off0[rc], off1[rc], gl, nxt);
+            }
+            double aq = 0.0, ag = 0.0;
+            const int32_t pc0 = (cur.p0 & ~3) + gl * 4;
+#pragma unroll
+            for (int c = 0; c < kChunksAhead; c++)
+                sp_accumulate(cur.iv[c], cur.vv[c], pc0 + c * 64, cur.p0, cur.p1, base, mask, xc, aq, ag);
+            // runs longer than the prefetched chunks (dense slices): plain loop
+            for (int32_t pc = pc0 + kChunksAhead * 64; pc < cur.p1; pc += 64) {
+                const int64_t rb = (int64_t)r * row_stride;
+                const int4 iv = *reinterpret_cast<const int4 *>(ring_idx + rb + pc);
+                const float4 vv = *reinterpret_cast<const float4 *>(ring_val + rb + pc);
+                sp_accumulate(iv, vv, pc, cur.p0, cur.p1, base, mask, xc, aq, ag);
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) {
+                aq += __shfl_xor(aq, o, 16);
+                ag += __shfl_xor(ag, o, 16);
+            }
+            if (gl == 0) {          // row r belongs to this group only: no race on racc[r]
+                double2 t = racc[r];
+                t.x += aq;
+                t.y += ag;
+                racc[r] = t;
+            }
+            cur = nxt;
+            r = rn;
+        }
     }
+    __syncthreads();
+    if (tid < m)
+        partial[(int64_t)blockIdx.x * m + tid] = tid < n_filled ? racc[tid] : make_double2(0.0, 0.0);
 }
 
-// First level of the fixed-order reduction over slices: block (bx, by) adds
-// the partial sums of 64 rows over slice group by.
+// sq[r] = sum over workgroups of partial[b][r], in a fixed order: block bx
+// owns 64 rows; thread (bl, rl) adds workgroups bl, bl+16, ...; the 16
+// partial sums are then added in order.  Unfilled rows give exactly 0.
 __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ partial, int32_t m,
-                                                    int32_t n_filled, int32_t nsl, int32_t per_group,
-                                                    double2 *__restrict__ partial2)
+                                                    int32_t nwg, double2 *__restrict__ sq)
 {
     __shared__ double2 sh[16][64];
-    const int rl = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    const int rl = threadIdx.x & 63, bl = threadIdx.x >> 6;
     const int32_t r = blockIdx.x * 64 + rl;
-    const int32_t s0 = blockIdx.y * per_group, s1 = min(nsl, s0 + per_group);
     double ax = 0.0, ay = 0.0;
-    if (r < n_filled) {
-        for (int32_t s = s0 + sl; s < s1; s += 16) {
-            const double2 t = partial[(int64_t)s * m + r];
+    if (r < m) {
+        for (int32_t b = bl; b < nwg; b += 16) {
+            const double2 t = partial[(int64_t)b * m + r];
             ax += t.x;
             ay += t.y;
         }
     }
-    sh[sl][rl] = make_double2(ax, ay);
+    sh[bl][rl] = make_double2(ax, ay);
     __syncthreads();
-    if (sl == 0 && r < m) {
+    if (bl == 0 && r < m) {
         double sx = 0.0, sy = 0.0;
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             sx += sh[i][rl].x;
             sy += sh[i][rl].y;
         }
-        partial2[(int64_t)blockIdx.y * m + r] = make_double2(sx, sy);
+        sq[r] = make_double2(sx, sy);
     }
 }
 
 hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
                      int32_t slot, hipStream_t stream)
 {
-    const int32_t per = (g.n_slices + 7) / 8;
-    hipLaunchKernelGGL(k_sp, dim3(per * 8), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled, slot,
-                       g.row_stride, g.slice_log2, g.n_slices, p.ring_idx, p.ring_val, p.offT, p.partial);
+    hipLaunchKernelGGL(k_sp, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled, slot,
+                       g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8, p.ring_idx, p.ring_val,
+                       p.offT, p.partial);
     return hipGetLastError();
 }
 
 hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream)
 {
-    const int32_t per_group = (g.n_slices + g.n_groups - 1) / g.n_groups;
-    hipLaunchKernelGGL(k_sp_reduce, dim3((g.m + 63) / 64, g.n_groups), dim3(1024), 0, stream, p.partial,
-                       g.m, n_filled, g.n_slices, per_group, p.partial2);
+    hipLaunchKernelGGL(k_sp_reduce, dim3((g.m + 63) / 64), dim3(1024), 0, stream, p.partial, g.m,
+                       g.sp_grid, p.sq);
     return hipGetLastError();
 }
 

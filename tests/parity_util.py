@@ -26,7 +26,7 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 
 
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
-               check_small=True, verbose=False):
+               check_small=True, verbose=False, out_tol=OUT_TOL):
     """grads: iterable of float32 numpy arrays.  Returns dict of worst errors."""
     dev = torch.device("cuda:0")
     o = oracle_mod.Oracle(d, m, k, lam)
@@ -55,7 +55,8 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
             assert np.isfinite(out).all(), f"step {t}: non-finite output"
             err = rel_l2(out, y)
             worst["out"] = max(worst["out"], err)
-            assert err <= OUT_TOL, f"step {t}: rel L2 of F^-1 x = {err:.3e}"
+            if out_tol is not None:
+                assert err <= out_tol, f"step {t}: rel L2 of F^-1 x = {err:.3e}"
             if check_small:
                 sm = g_gpu.get_small()
                 assert sm["step"] == t
