@@ -255,11 +255,15 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t sl
     }
 }
 
+hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, p.W);
+    return hipGetLastError();
+}
+
 hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
                        int32_t evict, double lambda, hipStream_t stream)
 {
-    if (evict)
-        hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, p.W);
     hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, slot, p.W, p.sq,
                        p.zw);
     hipLaunchKernelGGL(k_bwd, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, lambda,

@@ -35,7 +35,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k, Geometry &g, const char **wh
     g.row_stride = (int64_t)align_up((size_t)k, 64);
     g.ldm = (int32_t)align_up((size_t)m, 8);
     const size_t fixed_sp = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2);
-    const size_t fixed_lcg = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
+    const size_t fixed_lcg = 4 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
     const int lg = 14;                             // 16384 coordinates: 128 KiB of the 160 KiB LDS
     if (((size_t)8 << lg) + fixed_sp > (size_t)lds || ((size_t)8 << lg) + fixed_lcg > (size_t)lds) {
         *why = "device LDS too small (needs the 160 KiB of gfx950)";
@@ -80,7 +80,7 @@ Layout make_layout(const Geometry &g)
     l.q = take((size_t)g.m * sizeof(double));
     l.coef = take((size_t)g.m * sizeof(double));
     l.rowmax = take((size_t)g.m * sizeof(uint32_t));
-    l.hist = take((size_t)(kBins1 + 2 * kBins2) * sizeof(uint32_t));
+    l.hist = take((size_t)(kBins1 + 2 * kHistPriv * kBins2) * sizeof(uint32_t));
     l.sel = take(sizeof(SelState));
     l.cnt_gt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.cnt_eq = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
@@ -104,6 +104,10 @@ struct efcp_ctx {
     bool own_ws;
     int64_t t;
     hipStream_t last_stream;
+    // The eviction update of the inverse factor depends on the previous step only; it runs on
+    // this stream next to the d-sized passes of the step and is joined before k_fwd.
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_join;
     const char *err;
     // profiling
     bool prof_on;
@@ -180,7 +184,7 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
     p.rowmax = reinterpret_cast<uint32_t *>(b + l.rowmax);
     p.hist1 = reinterpret_cast<uint32_t *>(b + l.hist);
     p.hist2 = p.hist1 + kBins1;
-    p.hist3 = p.hist2 + kBins2;
+    p.hist3 = p.hist2 + kHistPriv * kBins2;
     p.sel = reinterpret_cast<SelState *>(b + l.sel);
     p.cnt_gt = reinterpret_cast<uint32_t *>(b + l.cnt_gt);
     p.cnt_eq = reinterpret_cast<uint32_t *>(b + l.cnt_eq);
@@ -194,11 +198,19 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
     // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.
     // The ring rows and the per-slice partial sums are written before they are read.
     hipError_t rc = hipMemset(b + l.small_begin, 0, l.total - l.small_begin);
+    ctx->side = nullptr;
+    ctx->ev_fork = ctx->ev_join = nullptr;
+    if (rc == hipSuccess) rc = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+    if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
     if (rc == hipSuccess) rc = configure_sp(g);
     if (rc == hipSuccess) rc = configure_lcg(g);
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) {
         (void)hipGetLastError();
+        if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+        if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+        if (ctx->side) (void)hipStreamDestroy(ctx->side);
         if (ctx->own_ws) (void)hipFree(ctx->ws);
         delete ctx;
         return EFCP_EHIP;
@@ -229,6 +241,12 @@ extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *st
     hipError_t rc = hipSuccess;
     auto mark = [&](int i) { if (ev && rc == hipSuccess) rc = hipEventRecord(ev[i], stream); };
 
+    if (evict) {        // fork: delete the oldest row from the inverse factor while the d-sized passes run
+        if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_fork, stream);
+        if (rc == hipSuccess) rc = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
+        if (rc == hipSuccess) rc = launch_evict(g, p, slot, ctx->side);
+        if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_join, ctx->side);
+    }
     mark(0);
     if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
     mark(1);
@@ -239,6 +257,7 @@ extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *st
     if (rc == hipSuccess) rc = launch_sp(g, p, grad, n_filled, slot, stream);
     mark(4);
     if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
+    if (evict && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);      // join
     if (rc == hipSuccess) rc = launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
     mark(5);
     if (rc == hipSuccess) rc = launch_lcg(g, p, grad, outp, n_filled, ctx->lambda, stream);
@@ -257,6 +276,9 @@ extern "C" int efcp_destroy(efcp_ctx *ctx)
     int rcode = EFCP_OK;
     if (hipDeviceSynchronize() != hipSuccess) rcode = EFCP_EHIP;
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    (void)hipEventDestroy(ctx->ev_fork);
+    (void)hipEventDestroy(ctx->ev_join);
+    (void)hipStreamDestroy(ctx->side);
     if (ctx->own_ws && hipFree(ctx->ws) != hipSuccess) rcode = EFCP_EHIP;
     delete ctx;
     return rcode;

@@ -31,6 +31,7 @@ constexpr int kMaxM = 1024;          // window slots == threads of the m x m ker
 constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
 constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
+constexpr int kHistPriv = 128;       // private histograms of the candidate passes
 
 // Device-resident state of the radix select of the current step.
 struct SelState {
@@ -80,6 +81,7 @@ hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, 
 hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
                      int32_t slot, hipStream_t stream);
 hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
+hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
                        int32_t evict, double lambda, hipStream_t stream);
 hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,

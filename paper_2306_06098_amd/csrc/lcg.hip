@@ -14,42 +14,23 @@
 // sum) is far finer than the fp32 output.
 #include "efcp_internal.h"
 
-namespace efcp {
+#include <type_traits>
 
-__device__ __forceinline__ int32_t lcg_slice_of_block(int32_t nsl)
-{
-    const int32_t per = (nsl + 7) >> 3;
-    const int32_t xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
-    const int32_t s = xcd * per + i;
-    return (i < per && s < nsl) ? s : -1;
-}
+namespace efcp {
 
 constexpr int kLcgChunksAhead = 3;
 
+// One batch = up to kLcgChunksAhead chunks of 64 entries of one row's run in the slice.  A run
+// longer than a batch is continued by the next batch (same row, pcs advanced), so the row
+// loop has a single shape and the number of loads in flight is always known.
 struct LcgBatch {
     int4 iv[kLcgChunksAhead];
     float4 vv[kLcgChunksAhead];
-    int32_t p0, p1;
+    int32_t r;          // row (may be >= n_filled: then nothing is valid)
+    int32_t pcs;        // position of chunk 0, lane 0 (multiple of 4)
+    int32_t p0, p1;     // the row's run in this slice
     double c;
 };
-
-__device__ __forceinline__ void lcg_issue(const int32_t *__restrict__ idx_row,
-                                          const float *__restrict__ val_row, int32_t p0, int32_t p1,
-                                          double c, int gl, LcgBatch &b)
-{
-    b.p0 = p0;
-    b.p1 = p1;
-    b.c = c;
-#pragma unroll
-    for (int q = 0; q < kLcgChunksAhead; q++) {
-        // always load (from the row start when the chunk lies past the run) so that the
-        // number of loads in flight is known and later waits need not drain the prefetch
-        const int32_t pc = (p0 & ~3) + gl * 4 + q * 64;
-        const int32_t pcs = pc < p1 ? pc : 0;
-        b.iv[q] = *reinterpret_cast<const int4 *>(idx_row + pcs);
-        b.vv[q] = *reinterpret_cast<const float4 *>(val_row + pcs);
-    }
-}
 
 // round(c*v / unit) as an integer: the magic constant puts the product's
 // units digit at the last mantissa bit; integer LDS atomics add it.
@@ -72,9 +53,13 @@ __device__ __forceinline__ void lcg_scatter(const int4 &iv, const float4 &vv, in
     }
 }
 
+// Persistent: workgroup b sits on XCD b%8 and is the (b/8)-th of `cpx` workgroups there; XCD x owns the
+// contiguous slice range [x*per, (x+1)*per) and its workgroups work on neighbouring slices at any
+// moment (same mapping as the SP pass).  While a slice's rows stream, the x values of its epilogue and
+// the row offsets of the workgroup's next slice are already on their way in registers.
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
                                               int64_t d, int32_t m, int32_t n_filled, int64_t row_stride,
-                                              int32_t slice_log2, int32_t nsl,
+                                              int32_t slice_log2, int32_t nsl, int32_t cpx,
                                               const int32_t *__restrict__ ring_idx,
                                               const float *__restrict__ ring_val,
                                               const int32_t *__restrict__ offT,
@@ -86,23 +71,24 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const int32_t slice = 1 << slice_log2;
     unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem);   // [slice]
     double *cf = reinterpret_cast<double *>(acc + slice);                     // [1024]
-    int32_t *off0 = reinterpret_cast<int32_t *>(cf + kMaxM);                  // [1024]
-    int32_t *off1 = off0 + kMaxM;                                             // [1024]
+    int32_t *offs = reinterpret_cast<int32_t *>(cf + kMaxM);                  // [2 buffers][2][1024]
     __shared__ double wsum[16];
 
-    const int32_t s = lcg_slice_of_block(nsl);
-    if (s < 0) return;
-    const int64_t base64 = (int64_t)s << slice_log2;
-    const int32_t base = (int32_t)base64;
-    const int32_t len = (int32_t)min((int64_t)slice, d - base64);
-    const int32_t mask = slice - 1;
     const int tid = threadIdx.x;
+    const int grp = tid >> 4, gl = tid & 15;
+    const int32_t per = (nsl + 7) >> 3;
+    const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
+    const int32_t s_end = min(nsl, (xcd + 1) * per);
+    const int32_t mask = slice - 1;
+    int32_t s = xcd * per + cu;
+    if (s >= s_end) return;                   // uniform: this workgroup has no slice
+    const int32_t trow = min(tid, m - 1);     // row whose offsets this thread fetches
 
     for (int32_t i = tid; i < slice; i += 1024) acc[i] = 0ull;
     double cabs = 0.0;
-    if (tid < m) {
-        off0[tid] = offT[(int64_t)s * m + tid];
-        off1[tid] = offT[(int64_t)(s + 1) * m + tid];
+    {
+        offs[tid] = offT[(int64_t)s * m + trow];
+        offs[kMaxM + tid] = offT[(int64_t)(s + 1) * m + trow];
         const double c = tid < n_filled ? coef[tid] : 0.0;
         cf[tid] = c;
         // |coef_r| * (upper bound of the largest |value| of row r)
@@ -128,70 +114,142 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const double magic = ldexp(1.5, ex + 2);          // 1.5 * 2^52 * unit
     const long long magic_bits = __double_as_longlong(magic);
 
-    const int grp = tid >> 4, gl = tid & 15;
-    int32_t r = grp;
-    LcgBatch cur, nxt;
-    {
-        const int32_t rc = min(r, n_filled - 1);
-        lcg_issue(ring_idx + (int64_t)rc * row_stride, ring_val + (int64_t)rc * row_stride, off0[rc],
-                  off1[rc], cf[rc], gl, cur);
-    }
-    while (r < n_filled) {
-        const int32_t rn = r + kRowGroups;
-        {   // prefetch the next row of this group (a harmless repeat of the last row at the end)
-            const int32_t rc = min(rn, n_filled - 1);
-            lcg_issue(ring_idx + (int64_t)rc * row_stride, ring_val + (int64_t)rc * row_stride,
-                      off0[rc], off1[rc], cf[rc], gl, nxt);
-        }
-        const int32_t pc0 = (cur.p0 & ~3) + gl * 4;
+    // Batches: two register sets used alternately (no copies between them): while one batch
+    // is scattered, the loads of the group's next batch are in flight.
+    const int32_t *off0 = offs, *off1 = offs + kMaxM;             // offsets of the current slice
+    auto first = [&](LcgBatch &b) {
+        b.r = grp;
+        const int32_t rc = min(b.r, n_filled - 1);
+        b.p0 = off0[rc]; b.p1 = off1[rc]; b.c = cf[rc];
+        b.pcs = b.p0 & ~3;
+    };
+    auto advance = [&](const LcgBatch &a, LcgBatch &b) {          // b = the batch after a
+        const int32_t cont = a.pcs + kLcgChunksAhead * 64;
+        const bool same = cont < a.p1;
+        b.r = same ? a.r : a.r + kRowGroups;
+        const int32_t rc = min(b.r, n_filled - 1);                // past the end: repeat of the last row
+        const int32_t q0 = off0[rc], q1 = off1[rc];
+        b.p0 = same ? a.p0 : q0;
+        b.p1 = same ? a.p1 : q1;
+        b.c = cf[rc];
+        b.pcs = same ? cont : (q0 & ~3);
+    };
+    auto load = [&](LcgBatch &b) {
+        const int32_t rc = min(b.r, n_filled - 1);
+        const int32_t *ir = ring_idx + (int64_t)rc * row_stride;
+        const float *vr = ring_val + (int64_t)rc * row_stride;
 #pragma unroll
-        for (int q = 0; q < kLcgChunksAhead; q++)
-            lcg_scatter(cur.iv[q], cur.vv[q], pc0 + q * 64, cur.p0, cur.p1, base, mask, cur.c, magic,
-                        magic_bits, acc);
-        for (int32_t pc = pc0 + kLcgChunksAhead * 64; pc < cur.p1; pc += 64) {
-            const int64_t rb = (int64_t)r * row_stride;
-            const int4 iv = *reinterpret_cast<const int4 *>(ring_idx + rb + pc);
-            const float4 vv = *reinterpret_cast<const float4 *>(ring_val + rb + pc);
-            lcg_scatter(iv, vv, pc, cur.p0, cur.p1, base, mask, cur.c, magic, magic_bits, acc);
+        for (int q = 0; q < kLcgChunksAhead; q++) {
+            // always load (from the row start when the chunk lies past the run)
+            const int32_t pc = b.pcs + gl * 4 + q * 64;
+            const int32_t pcl = pc < b.p1 ? pc : 0;
+            b.iv[q] = *reinterpret_cast<const int4 *>(ir + pcl);
+            b.vv[q] = *reinterpret_cast<const float4 *>(vr + pcl);
         }
-        cur = nxt;
-        r = rn;
-    }
-    __syncthreads();
+    };
 
-    for (int32_t i = tid * 4; i < slice; i += 4096) {
-        if (i >= len) break;
-        float o[4];
-        float xv[4];
-        if (i + 3 < len) {
-            const float4 t = *reinterpret_cast<const float4 *>(x + base64 + i);
-            xv[0] = t.x; xv[1] = t.y; xv[2] = t.z; xv[3] = t.w;
-        } else {
+    LcgBatch ba, bb;
+    first(ba);
+    load(ba);                                 // first batch of the first slice
+    int buf = 0;
+    // One slice.  FULL: all 16384 coordinates exist, so x and out move as unconditional 16-byte
+    // accesses and the compiler can keep exact counts of the loads in flight.  The ragged last
+    // slice of the vector (at most one, and the last one of its workgroup) takes the guarded path.
+    auto do_slice = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const int64_t base64 = (int64_t)s << slice_log2;
+        const int32_t base = (int32_t)base64;
+        const int32_t len = FULL ? slice : (int32_t)(d - base64);
+        const int32_t sn = s + cpx;
+        const int32_t sl = sn < s_end ? sn : s;
+        auto consume = [&](const LcgBatch &b) {
+            const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
 #pragma unroll
-            for (int q = 0; q < 4; q++) xv[q] = (i + q < len) ? x[base64 + i + q] : 0.0f;
-        }
+            for (int q = 0; q < kLcgChunksAhead; q++)
+                lcg_scatter(b.iv[q], b.vv[q], b.pcs + gl * 4 + q * 64, b.p0, hi, base, mask, b.c, magic,
+                            magic_bits, acc);
+        };
+
+        // on their way while the rows stream: x of this slice (for the epilogue) and the row
+        // offsets of this workgroup's next slice
+        float4 xr[4];
+        if (FULL) {
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const double sum = (double)(long long)acc[i + q] * unit;
-            o[q] = (float)((double)xv[q] * inv_lambda - sum);
+            for (int u = 0; u < 4; u++)
+                xr[u] = *reinterpret_cast<const float4 *>(x + base64 + tid * 4 + u * 4096);
         }
-        if (i + 3 < len) {
-            *reinterpret_cast<float4 *>(out + base64 + i) = make_float4(o[0], o[1], o[2], o[3]);
-        } else {
+        const int32_t o0 = offT[(int64_t)sl * m + trow];
+        const int32_t o1 = offT[(int64_t)(sl + 1) * m + trow];
+        int32_t *offn = offs + (buf ^ 1) * 2 * kMaxM;
+
+        bool stored = false;
+        while (__any(ba.r < n_filled)) {
+            advance(ba, bb);
+            load(bb);
+            consume(ba);
+            const bool more = __any(bb.r < n_filled);
+            if (more) {
+                advance(bb, ba);
+                load(ba);
+                consume(bb);
+            }
+            if (!stored) {                    // offsets of the next slice into the other LDS buffer
+                offn[tid] = o0;
+                offn[kMaxM + tid] = o1;
+                stored = true;
+            }
+            if (!more) break;
+        }
+        __syncthreads();            // all rows of this slice are in the accumulators; offn visible
+
+        off0 = offn;
+        off1 = offn + kMaxM;
+        buf ^= 1;
+        // first batch of the next slice: in flight during the epilogue (after the last slice
+        // this re-reads the current one: unconditional, so the waits below can leave it in flight)
+        first(ba);
+        load(ba);
+
+        // out = x/lambda - sum; accumulators back to zero for the next slice
 #pragma unroll
-            for (int q = 0; q < 4; q++)
-                if (i + q < len) out[base64 + i + q] = o[q];
+        for (int u = 0; u < 4; u++) {
+            const int32_t i = tid * 4 + u * 4096;
+            float o[4];
+            if (FULL) {
+                const float xv[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const double sum = (double)(long long)acc[i + q] * unit;
+                    o[q] = (float)((double)xv[q] * inv_lambda - sum);
+                }
+                *reinterpret_cast<float4 *>(out + base64 + i) = make_float4(o[0], o[1], o[2], o[3]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    if (i + q < len) {
+                        const double sum = (double)(long long)acc[i + q] * unit;
+                        out[base64 + i + q] = (float)((double)x[base64 + i + q] * inv_lambda - sum);
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; q++) acc[i + q] = 0ull;
         }
-    }
+        __syncthreads();            // accumulators are zero before the next slice scatters
+    };
+
+    const int32_t n_full = (int32_t)(d >> slice_log2);            // slices with all coordinates
+    const int32_t s_full_end = min(s_end, n_full);
+    for (; s < s_full_end; s += cpx) do_slice(std::true_type{});
+    if (s < s_end) do_slice(std::false_type{});                   // uniform
 }
 
 hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
                       int32_t n_filled, double lambda, hipStream_t stream)
 {
-    const int32_t per = (g.n_slices + 7) / 8;
-    hipLaunchKernelGGL(k_lcg, dim3(per * 8), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m, n_filled,
-                       g.row_stride, g.slice_log2, g.n_slices, p.ring_idx, p.ring_val, p.offT, p.coef,
-                       p.rowmax, p.status, 1.0 / lambda);
+    hipLaunchKernelGGL(k_lcg, dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m, n_filled,
+                       g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8, p.ring_idx, p.ring_val,
+                       p.offT, p.coef, p.rowmax, p.status, 1.0 / lambda);
     return hipGetLastError();
 }
 

@@ -167,38 +167,52 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
 
 // ------------------------------------------------------------------
 // Histogram of the next 10-bit digit over the candidates whose higher key
-// bits equal the prefix found so far.  One workgroup walks kHistSegs segments.
-constexpr int kHistSegs = 2;
+// bits equal the prefix found so far.  kHistGroups workgroups of 16 waves; a
+// wave takes one candidate segment at a time.  Every workgroup stores its own
+// 1024-bin histogram (no global atomics: device-scope atomics on a few hot
+// addresses from thousands of waves serialise); k_pick_digit adds them up.
+constexpr int kHistGroups = kHistPriv;
 
-__global__ __launch_bounds__(kSelThreads) void k_cand_hist(const float *__restrict__ cand_val,
-                                                           const uint32_t *__restrict__ cand_cnt,
-                                                           int32_t nb, const SelState *__restrict__ sel,
-                                                           uint32_t *__restrict__ hist, int shift_hi,
-                                                           int shift_lo)
+__global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ cand_val,
+                                                    const uint32_t *__restrict__ cand_cnt, int32_t nb,
+                                                    const SelState *__restrict__ sel,
+                                                    uint32_t *__restrict__ hist_priv, int shift_hi,
+                                                    int shift_lo)
 {
     __shared__ uint32_t lh[kBins2];
-    for (int i = threadIdx.x; i < kBins2; i += kSelThreads) lh[i] = 0;
+    lh[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t prefix = sel->prefix;
-    const int32_t b0 = blockIdx.x * kHistSegs, b1 = min(nb, b0 + kHistSegs);
-    for (int32_t b = b0; b < b1; b++) {
-        const uint32_t cnt = cand_cnt[b];
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    // The count of the wave's next segment is fetched while the current one is processed, and
+    // eight loads per lane are issued before any is used (unconditional, clamped addresses).
+    int32_t b = blockIdx.x * 16 + w;
+    uint32_t cnt = b < nb ? cand_cnt[b] : 0u;
+    while (b < nb) {
+        const int32_t bn = b + kHistGroups * 16;
+        const uint32_t cnt_next = cand_cnt[min(bn, nb - 1)];
         const float *seg = cand_val + (int64_t)b * kCandBlock;
-        for (uint32_t i = threadIdx.x; i < cnt; i += kSelThreads) {
-            const uint32_t kk = mag_key(seg[i]);
-            if ((kk >> shift_hi) == prefix) atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
+        for (uint32_t i0 = 0; i0 < cnt; i0 += 512) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) v[u] = seg[min(i0 + u * 64 + lane, cnt - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const uint32_t kk = mag_key(v[u]);
+                if (i0 + u * 64 + lane < cnt && (kk >> shift_hi) == prefix)
+                    atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
+            }
         }
+        b = bn;
+        cnt = cnt_next;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kBins2; i += kSelThreads) {
-        const uint32_t c = lh[i];
-        if (c) atomicAdd(&hist[i], c);
-    }
+    hist_priv[(int64_t)blockIdx.x * kBins2 + threadIdx.x] = lh[threadIdx.x];
 }
 
 // ------------------------------------------------------------------
 // One workgroup: locate the digit in which the kr-th largest remaining key
-// falls, update the select state, and clear the histogram for the next step.
+// falls and update the select state.
 // pass 0: 2048 bins (bits 30..20); pass 1, 2: 1024 bins.
 template <int NB>
 __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist,
@@ -215,15 +229,23 @@ __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist
     const uint32_t t_lo = sel->t_lo;
 
     // Walk the bins from the largest digit down: rb = NB-1-bin.
+    // pass 0: `hist` is one histogram filled by atomics (cleared here for the next step);
+    // passes 1, 2: `hist` holds kHistGroups private histograms to add up.
     uint32_t c[PER];
     uint32_t local = 0;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int bin = NB - 1 - (threadIdx.x * PER + i);
-        c[i] = hist[bin];
-        hist[bin] = 0;
+        if (pass == 0) {
+            c[i] = hist[bin];
+            hist[bin] = 0;
+            if (c[i]) atomicMax(&top_bin, bin);
+        } else {
+            uint32_t t = 0;
+            for (int g = 0; g < kHistGroups; g++) t += hist[(int64_t)g * NB + bin];
+            c[i] = t;
+        }
         local += c[i];
-        if (pass == 0 && c[i]) atomicMax(&top_bin, bin);
     }
     uint32_t total;
     uint32_t above = block_excl_scan_u32(local, tmp, &total);   // count in larger digits
@@ -271,10 +293,17 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_count(const float *__restr
     const uint32_t cnt = cand_cnt[b];
     const float *seg = cand_val + (int64_t)b * kCandBlock;
     uint32_t g = 0, q = 0;
-    for (uint32_t i = lane; i < cnt; i += 64) {
-        const uint32_t key = mag_key(seg[i]);
-        g += key > tau;
-        q += key == tau;
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 512) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = seg[min(i0 + u * 64 + lane, cnt - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const uint32_t key = mag_key(v[u]);
+            const bool in = i0 + u * 64 + lane < cnt;
+            g += in && key > tau;
+            q += in && key == tau;
+        }
     }
     g = wave_sum_u32(g);
     q = wave_sum_u32(q);
@@ -365,25 +394,35 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
     const float *sval = cand_val + (int64_t)b * kCandBlock;
     uint32_t eq_run = eq_before[b];
     uint32_t out_run = sel_off[b];
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {
-        const uint32_t i = i0 + lane;
-        const bool in = i < cnt;
-        const float v = in ? sval[i] : 0.0f;
-        const int32_t j = in ? sidx[i] : 0;
-        const uint32_t key = mag_key(v);
-        const bool is_eq = in && key == tau;
-        const uint64_t eq_mask = __ballot(is_eq);
-        const uint32_t eq_rank = eq_run + __popcll(eq_mask & ((1ull << lane) - 1ull));
-        const bool take = in && (key > tau || (is_eq && eq_rank < quota));
-        const uint64_t take_mask = __ballot(take);
-        if (take) {
-            const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
-            row_idx[pos] = j;
-            row_val[pos] = v;
-            e[j] = 0.0f;
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 256) {
+        float vv[4];
+        int32_t jj[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {          // unconditional loads, clamped addresses
+            const uint32_t ic = min(i0 + u * 64 + lane, cnt - 1);
+            vv[u] = sval[ic];
+            jj[u] = sidx[ic];
         }
-        eq_run += __popcll(eq_mask);
-        out_run += __popcll(take_mask);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const bool in = i0 + u * 64 + lane < cnt;
+            const float v = vv[u];
+            const int32_t j = jj[u];
+            const uint32_t key = mag_key(v);
+            const bool is_eq = in && key == tau;
+            const uint64_t eq_mask = __ballot(is_eq);
+            const uint32_t eq_rank = eq_run + __popcll(eq_mask & ((1ull << lane) - 1ull));
+            const bool take = in && (key > tau || (is_eq && eq_rank < quota));
+            const uint64_t take_mask = __ballot(take);
+            if (take) {
+                const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
+                row_idx[pos] = j;
+                row_val[pos] = v;
+                e[j] = 0.0f;
+            }
+            eq_run += __popcll(eq_mask);
+            out_run += __popcll(take_mask);
+        }
     }
 }
 
@@ -399,17 +438,16 @@ hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *g
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
     const int32_t nb = g.n_sel_blocks;
-    const int hist_grid = (nb + kHistSegs - 1) / kHistSegs;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
                        (uint32_t)g.k, p.rowmax + slot);
     hipLaunchKernelGGL(k_ef_hist<true>, dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
                        p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt);
-    hipLaunchKernelGGL(k_cand_hist, dim3(hist_grid), dim3(kSelThreads), 0, stream, p.cand_val, p.cand_cnt,
-                       nb, p.sel, p.hist2, 20, 10);
+    hipLaunchKernelGGL(k_cand_hist, dim3(kHistGroups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
+                       p.sel, p.hist2, 20, 10);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
                        (uint32_t)g.k, p.rowmax + slot);
-    hipLaunchKernelGGL(k_cand_hist, dim3(hist_grid), dim3(kSelThreads), 0, stream, p.cand_val, p.cand_cnt,
-                       nb, p.sel, p.hist3, 10, 0);
+    hipLaunchKernelGGL(k_cand_hist, dim3(kHistGroups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
+                       p.sel, p.hist3, 10, 0);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist3, p.sel, 2,
                        (uint32_t)g.k, p.rowmax + slot);
     hipLaunchKernelGGL(k_cand_count, dim3((nb + 3) / 4), dim3(kSelThreads), 0, stream, p.cand_val,

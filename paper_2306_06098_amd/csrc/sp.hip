@@ -19,32 +19,19 @@
 
 namespace efcp {
 
-constexpr int kChunksAhead = 3;      // 16-byte loads per array a lane keeps in flight per row
+constexpr int kChunksAhead = 3;      // 16-byte loads per array a lane keeps in flight per batch
 
+// One batch = up to kChunksAhead chunks of 64 entries of one row's run in the slice: lane gl of
+// the 16-lane group reads entries [pc, pc+4), pc = pcs + 4*gl + 64*c.  A run longer than a batch
+// is continued by the next batch (same row, pcs advanced), so the row loop has a single shape
+// and the number of loads in flight is always known.
 struct RunBatch {
     int4 iv[kChunksAhead];
     float4 vv[kChunksAhead];
-    int32_t p0, p1;
+    int32_t r;          // row (may be >= n_filled: then nothing is valid)
+    int32_t pcs;        // position of chunk 0, lane 0 (multiple of 4)
+    int32_t p0, p1;     // the row's run in this slice
 };
-
-// Issue the loads of the first kChunksAhead chunks of a run.  Lane gl of the
-// 16-lane group reads entries [pc, pc+4), pc = (p0 & ~3) + 4*gl + 64*c.
-__device__ __forceinline__ void issue_run(const int32_t *__restrict__ idx_row,
-                                          const float *__restrict__ val_row, int32_t p0, int32_t p1,
-                                          int gl, RunBatch &b)
-{
-    b.p0 = p0;
-    b.p1 = p1;
-#pragma unroll
-    for (int c = 0; c < kChunksAhead; c++) {
-        // always load (from the row start when the chunk lies past the run) so that the
-        // number of loads in flight is known and later waits need not drain the prefetch
-        const int32_t pc = (p0 & ~3) + gl * 4 + c * 64;
-        const int32_t pcs = pc < p1 ? pc : 0;
-        b.iv[c] = *reinterpret_cast<const int4 *>(idx_row + pcs);
-        b.vv[c] = *reinterpret_cast<const float4 *>(val_row + pcs);
-    }
-}
 
 __device__ __forceinline__ void sp_accumulate(const int4 &iv, const float4 &vv, int32_t pc, int32_t p0,
                                               int32_t p1, int32_t base, int32_t mask,
@@ -128,45 +115,66 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         }
         __syncthreads();
 
-        int32_t r = grp;
-        RunBatch cur, nxt;
-        {
-            const int32_t rc = min(r, n_filled - 1);
-            issue_run(ring_idx + (int64_t)rc * row_stride, ring_val + (int64_t)rc * row_stride,
-                      off0[rc], off1[rc], gl, cur);
-        }
-        while (r < n_filled) {
-            const int32_t rn = r + kRowGroups;
-            {   // prefetch the next row of this group (a harmless repeat of the last row at the end)
-                const int32_t rc = min(rn, n_filled - 1);
-                issue_run(ring_idx + (int64_t)rc * row_stride, ring_val + (int64_t)rc * row_stride,
-                          off0[rc], off1[rc], gl, nxt);
+        // Two register batches used alternately (no copies between them): while one batch is
+        // accumulated, the loads of the group's next batch are in flight.
+        auto first = [&](RunBatch &b) {
+            b.r = grp;
+            const int32_t rc = min(b.r, n_filled - 1);
+            b.p0 = off0[rc]; b.p1 = off1[rc];
+            b.pcs = b.p0 & ~3;
+        };
+        auto advance = [&](const RunBatch &a, RunBatch &b) {      // b = the batch after a
+            const int32_t cont = a.pcs + kChunksAhead * 64;
+            const bool same = cont < a.p1;
+            b.r = same ? a.r : a.r + kRowGroups;
+            const int32_t rc = min(b.r, n_filled - 1);            // past the end: repeat of the last row
+            const int32_t q0 = off0[rc], q1 = off1[rc];
+            b.p0 = same ? a.p0 : q0;
+            b.p1 = same ? a.p1 : q1;
+            b.pcs = same ? cont : (q0 & ~3);
+        };
+        auto load = [&](RunBatch &b) {
+            const int32_t rc = min(b.r, n_filled - 1);
+            const int32_t *ir = ring_idx + (int64_t)rc * row_stride;
+            const float *vr = ring_val + (int64_t)rc * row_stride;
+#pragma unroll
+            for (int c = 0; c < kChunksAhead; c++) {
+                // always load (from the row start when the chunk lies past the run)
+                const int32_t pc = b.pcs + gl * 4 + c * 64;
+                const int32_t pcl = pc < b.p1 ? pc : 0;
+                b.iv[c] = *reinterpret_cast<const int4 *>(ir + pcl);
+                b.vv[c] = *reinterpret_cast<const float4 *>(vr + pcl);
             }
+        };
+        auto consume = [&](const RunBatch &b) {
             double aq = 0.0, ag = 0.0;
-            const int32_t pc0 = (cur.p0 & ~3) + gl * 4;
+            const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
 #pragma unroll
             for (int c = 0; c < kChunksAhead; c++)
-                sp_accumulate(cur.iv[c], cur.vv[c], pc0 + c * 64, cur.p0, cur.p1, base, mask, xc, aq, ag);
-            // runs longer than the prefetched chunks (dense slices): plain loop
-            for (int32_t pc = pc0 + kChunksAhead * 64; pc < cur.p1; pc += 64) {
-                const int64_t rb = (int64_t)r * row_stride;
-                const int4 iv = *reinterpret_cast<const int4 *>(ring_idx + rb + pc);
-                const float4 vv = *reinterpret_cast<const float4 *>(ring_val + rb + pc);
-                sp_accumulate(iv, vv, pc, cur.p0, cur.p1, base, mask, xc, aq, ag);
-            }
+                sp_accumulate(b.iv[c], b.vv[c], b.pcs + gl * 4 + c * 64, b.p0, hi, base, mask, xc, aq, ag);
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) {
                 aq += __shfl_xor(aq, o, 16);
                 ag += __shfl_xor(ag, o, 16);
             }
-            if (gl == 0) {          // row r belongs to this group only: no race on racc[r]
-                double2 t = racc[r];
+            if (gl == 0 && b.r < n_filled) {   // row r belongs to this group only: no race on racc[r]
+                double2 t = racc[b.r];
                 t.x += aq;
                 t.y += ag;
-                racc[r] = t;
+                racc[b.r] = t;
             }
-            cur = nxt;
-            r = rn;
+        };
+        RunBatch ba, bb;
+        first(ba);
+        load(ba);
+        while (__any(ba.r < n_filled)) {
+            advance(ba, bb);
+            load(bb);
+            consume(ba);
+            if (!__any(bb.r < n_filled)) break;
+            advance(bb, ba);
+            load(ba);
+            consume(bb);
         }
     }
     __syncthreads();
