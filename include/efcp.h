@@ -66,7 +66,9 @@ int efcp_create(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
 /* One step (see the top of this file).
  *   grad    device, d floats, 16-byte aligned, read only
  *   out     device, d floats, 16-byte aligned, receives F^-1 grad; must not
- *           overlap grad
+ *           overlap grad.  NULL: the state (e, window, S, the coefficient
+ *           factor, q, coef) is updated exactly as usual but F^-1 grad is not
+ *           formed (the LCG pass is skipped), e.g. to fill the window
  *   stream  hipStream_t (NULL = the default stream)
  * Asynchronous: enqueues kernels on `stream` and returns; no host
  * synchronisation and no allocation.  Steps of one context must be issued in

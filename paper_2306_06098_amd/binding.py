@@ -96,13 +96,15 @@ class Efcp:
         self._check(self._lib.efcp_step(self._ctx, grad_ptr, out_ptr, stream))
 
     def step(self, grad, out, stream=None) -> None:
-        """grad, out: contiguous float32 CUDA tensors of d elements.  Runs on
-        `stream` (a torch.cuda.Stream) or torch's current stream."""
+        """grad, out: contiguous float32 CUDA tensors of d elements; out may be
+        None (state updated, F^-1 grad not formed).  Runs on `stream` (a
+        torch.cuda.Stream) or torch's current stream."""
         import torch
-        assert grad.is_cuda and out.is_cuda and grad.dtype == torch.float32 and out.dtype == torch.float32
-        assert grad.is_contiguous() and out.is_contiguous() and grad.numel() == self.d == out.numel()
+        assert grad.is_cuda and grad.dtype == torch.float32 and grad.is_contiguous() and grad.numel() == self.d
+        if out is not None:
+            assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == self.d
         s = stream if stream is not None else torch.cuda.current_stream(grad.device)
-        self.step_ptr(grad.data_ptr(), out.data_ptr(), s.cuda_stream)
+        self.step_ptr(grad.data_ptr(), out.data_ptr() if out is not None else None, s.cuda_stream)
 
     def destroy(self) -> None:
         if getattr(self, "_ctx", None) and self._ctx.value:

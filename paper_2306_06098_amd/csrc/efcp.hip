@@ -222,11 +222,11 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
 extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *stream_v)
 {
     if (!ctx) return EFCP_EINVAL;
-    if (!grad || !outp) return fail(ctx, EFCP_EINVAL, "grad/out is NULL");
+    if (!grad) return fail(ctx, EFCP_EINVAL, "grad is NULL");
     const uintptr_t ga = reinterpret_cast<uintptr_t>(grad), oa = reinterpret_cast<uintptr_t>(outp);
     if ((ga & 15) || (oa & 15)) return fail(ctx, EFCP_EINVAL, "grad/out not 16-byte aligned");
     const size_t bytes = (size_t)ctx->g.d * sizeof(float);
-    if (ga < oa + bytes && oa < ga + bytes) return fail(ctx, EFCP_EINVAL, "grad and out overlap");
+    if (outp && ga < oa + bytes && oa < ga + bytes) return fail(ctx, EFCP_EINVAL, "grad and out overlap");
 
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const Geometry &g = ctx->g;
@@ -260,7 +260,7 @@ extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *st
     if (evict && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);      // join
     if (rc == hipSuccess) rc = launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
     mark(5);
-    if (rc == hipSuccess) rc = launch_lcg(g, p, grad, outp, n_filled, ctx->lambda, stream);
+    if (rc == hipSuccess && outp) rc = launch_lcg(g, p, grad, outp, n_filled, ctx->lambda, stream);
     mark(6);
 
     ctx->t = t;

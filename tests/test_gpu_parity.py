@@ -190,6 +190,34 @@ def test_inverse_factor_does_not_drift(env):
     ctx.destroy()
 
 
+def test_steps_without_output_update_the_same_state(env):
+    """out = NULL skips only the LCG pass: window, e, S, q, coef and every later
+    output are bit-identical to a run that asked for the output on each step."""
+    torch, _, binding = env
+    d, m, k, lam = 50_000, 6, 500, 1e-3
+    grads = list(_stream(synth.Workload("x", d, m, k, lam, 14, 0.9, 5), 14))
+    res = []
+    for skip in (False, True):
+        ctx = binding.Efcp(d, m, k, lam)
+        g = torch.empty(d, dtype=torch.float32, device="cuda:0")
+        out = torch.full((d,), 7.0, dtype=torch.float32, device="cuda:0")
+        for t, x in enumerate(grads):
+            g.copy_(torch.from_numpy(x))
+            ctx.step(g, None if (skip and t < 10) else out)
+            if skip and t == 9:
+                assert bool((out == 7.0).all())          # never written so far
+        sm = ctx.get_small()
+        res.append((out.cpu().numpy().copy(), ctx.get_error(), sm["S"], sm["q"], sm["coef"],
+                    [ctx.get_row(r) for r in range(m)]))
+        ctx.destroy()
+    a, b = res
+    assert np.array_equal(bits(a[0]), bits(b[0])) and np.array_equal(bits(a[1]), bits(b[1]))
+    for i in (2, 3, 4):
+        assert np.array_equal(a[i], b[i])
+    for (i0, v0), (i1, v1) in zip(a[5], b[5]):
+        assert np.array_equal(i0, i1) and np.array_equal(bits(v0), bits(v1))
+
+
 def test_argument_checks(env):
     torch, _, binding = env
     for bad in [(0, 4, 1, 1e-3), (100, 0, 10, 1e-3), (100, 1025, 10, 1e-3), (100, 4, 101, 1e-3),
