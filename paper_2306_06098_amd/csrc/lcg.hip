@@ -176,7 +176,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         if (FULL) {
 #pragma unroll
             for (int u = 0; u < 4; u++)
-                xr[u] = *reinterpret_cast<const float4 *>(x + base64 + tid * 4 + u * 4096);
+                xr[u] = load_stream_f4(x + base64 + tid * 4 + u * 4096);
         }
         const int32_t o0 = offT[(int64_t)sl * m + trow];
         const int32_t o1 = offT[(int64_t)(sl + 1) * m + trow];
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
                     const double sum = (double)(long long)acc[i + q] * unit;
                     o[q] = (float)((double)xv[q] * inv_lambda - sum);
                 }
-                *reinterpret_cast<float4 *>(out + base64 + i) = make_float4(o[0], o[1], o[2], o[3]);
+                store_stream_f4(out + base64 + i, make_float4(o[0], o[1], o[2], o[3]));
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {

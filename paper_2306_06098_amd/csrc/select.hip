@@ -98,8 +98,8 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
             float4 ev[4], gv[4];
 #pragma unroll
             for (int it = 0; it < 4; it++) {
-                ev[it] = *reinterpret_cast<const float4 *>(e + wave_base + it * 256);
-                if (!REDO) gv[it] = *reinterpret_cast<const float4 *>(g + wave_base + it * 256);
+                ev[it] = load_stream_f4(e + wave_base + it * 256);
+                if (!REDO) gv[it] = load_stream_f4(g + wave_base + it * 256);
             }
 #pragma unroll
             for (int it = 0; it < 4; it++) {
@@ -110,8 +110,8 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                     a[it][1] = ev[it].y + gv[it].y;
                     a[it][2] = ev[it].z + gv[it].z;
                     a[it][3] = ev[it].w + gv[it].w;
-                    *reinterpret_cast<float4 *>(e + wave_base + it * 256) =
-                        make_float4(a[it][0], a[it][1], a[it][2], a[it][3]);
+                    store_stream_f4(e + wave_base + it * 256,
+                                    make_float4(a[it][0], a[it][1], a[it][2], a[it][3]));
                 }
             }
         } else {

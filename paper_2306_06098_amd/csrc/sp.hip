@@ -88,7 +88,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         for (int32_t i = tid * 4; i < slice; i += 4096) {
             float4 xv;
             if (i + 3 < len) {
-                xv = *reinterpret_cast<const float4 *>(x + base64 + i);
+                xv = load_stream_f4(x + base64 + i);
             } else {
                 xv.x = (i + 0 < len) ? x[base64 + i + 0] : 0.0f;
                 xv.y = (i + 1 < len) ? x[base64 + i + 1] : 0.0f;
