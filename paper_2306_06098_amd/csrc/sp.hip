@@ -17,6 +17,8 @@
 // slice lists are static, which makes the sums independent of scheduling.
 #include "efcp_internal.h"
 
+#include <type_traits>
+
 namespace efcp {
 
 constexpr int kChunksAhead = 3;      // 16-byte loads per array a lane keeps in flight per batch
@@ -51,14 +53,22 @@ __device__ __forceinline__ void sp_accumulate(const int4 &iv, const float4 &vv, 
     }
 }
 
+constexpr int kMaxSlicesPerWg = 512;     // ceil(2^31 / 16384 / 8 / 32)
+
 // Workgroup b sits on XCD b%8 (workgroups are dealt to the 8 XCDs round-robin)
 // and is the (b/8)-th of `cpx` workgroups there.  XCD x owns the contiguous
 // slice range [x*per, (x+1)*per); at any time its workgroups work on
 // neighbouring slices, so a cache line straddling two runs of a row is
 // wanted by two CUs of the same L2 at about the same time.
+//
+// While the rows of one slice stream, everything the next slice needs first is
+// already on its way in registers: its x values, its row offsets and the
+// newest row's entries that fall into it.  The switch between slices is then
+// three barriers and LDS traffic, with the first batch of ring loads of the
+// new slice issued before the last two.
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              int32_t n_filled, int32_t slot, int64_t row_stride,
-                                             int32_t slice_log2, int32_t nsl, int32_t cpx,
+                                             int64_t k, int32_t slice_log2, int32_t nsl, int32_t cpx,
                                              const int32_t *__restrict__ ring_idx,
                                              const float *__restrict__ ring_val,
                                              const int32_t *__restrict__ offT,
@@ -70,82 +80,129 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     double2 *racc = reinterpret_cast<double2 *>(xc + slice);       // [1024] per-row sums
     int32_t *off0 = reinterpret_cast<int32_t *>(racc + kMaxM);     // [1024]
     int32_t *off1 = off0 + kMaxM;                                  // [1024]
+    int32_t *np0 = off1 + kMaxM;                                   // [kMaxSlicesPerWg] newest row's run
+    int32_t *np1 = np0 + kMaxSlicesPerWg;                          //   in each slice of this workgroup
 
     const int tid = threadIdx.x;
     const int grp = tid >> 4, gl = tid & 15;
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
     const int32_t s_end = min(nsl, (xcd + 1) * per);
+    const int32_t s_first = xcd * per + cu;
     const int32_t mask = slice - 1;
+    const int32_t trow = min(tid, m - 1);
+    const int32_t *nidx = ring_idx + (int64_t)slot * row_stride;   // newest row
+    const float *nval = ring_val + (int64_t)slot * row_stride;
+    const int32_t klast = (int32_t)(k - 1);
 
     racc[tid] = make_double2(0.0, 0.0);
+    if (s_first >= s_end) {                   // uniform: no slice for this workgroup
+        if (tid < m) partial[(int64_t)blockIdx.x * m + tid] = make_double2(0.0, 0.0);
+        return;
+    }
+    for (int32_t i = tid; s_first + i * cpx < s_end && i < kMaxSlicesPerWg; i += 1024) {
+        const int32_t si = s_first + i * cpx;
+        np0[i] = offT[(int64_t)si * m + slot];
+        np1[i] = offT[(int64_t)(si + 1) * m + slot];
+    }
 
-    for (int32_t s = xcd * per + cu; s < s_end; s += cpx) {
-        const int64_t base64 = (int64_t)s << slice_log2;
-        const int32_t base = (int32_t)base64;
-        const int32_t len = (int32_t)min((int64_t)slice, d - base64);
-        __syncthreads();            // previous slice fully consumed (and racc zeroed on entry)
-        for (int32_t i = tid * 4; i < slice; i += 4096) {
-            float4 xv;
-            if (i + 3 < len) {
-                xv = load_stream_f4(x + base64 + i);
-            } else {
-                xv.x = (i + 0 < len) ? x[base64 + i + 0] : 0.0f;
-                xv.y = (i + 1 < len) ? x[base64 + i + 1] : 0.0f;
-                xv.z = (i + 2 < len) ? x[base64 + i + 2] : 0.0f;
-                xv.w = (i + 3 < len) ? x[base64 + i + 3] : 0.0f;
-            }
-            xc[i + 0] = make_float2(xv.x, 0.0f);
-            xc[i + 1] = make_float2(xv.y, 0.0f);
-            xc[i + 2] = make_float2(xv.z, 0.0f);
-            xc[i + 3] = make_float2(xv.w, 0.0f);
-        }
-        if (tid < m) {
-            off0[tid] = offT[(int64_t)s * m + tid];
-            off1[tid] = offT[(int64_t)(s + 1) * m + tid];
-        }
-        __syncthreads();
-        {   // scatter the newest row's entries of this slice next to x
-            const int64_t rb = (int64_t)slot * row_stride;
-            const int32_t p1 = off1[slot];
-            for (int32_t p = off0[slot] + tid; p < p1; p += 1024) {
-                const int32_t li = (ring_idx[rb + p] - base) & mask;
-                xc[li].y = ring_val[rb + p];
-            }
-        }
-        __syncthreads();
+    // state carried from one slice to the next (prefetched while the previous one streams)
+    float4 xr[4];
+    int32_t o0, o1, di;
+    float dv;
+    int32_t it = 0;                           // index of the current slice in this workgroup's list
+    int32_t s = s_first;
 
-        // Two register batches used alternately (no copies between them): while one batch is
-        // accumulated, the loads of the group's next batch are in flight.
-        auto first = [&](RunBatch &b) {
-            b.r = grp;
-            const int32_t rc = min(b.r, n_filled - 1);
-            b.p0 = off0[rc]; b.p1 = off1[rc];
-            b.pcs = b.p0 & ~3;
-        };
-        auto advance = [&](const RunBatch &a, RunBatch &b) {      // b = the batch after a
-            const int32_t cont = a.pcs + kChunksAhead * 64;
-            const bool same = cont < a.p1;
-            b.r = same ? a.r : a.r + kRowGroups;
-            const int32_t rc = min(b.r, n_filled - 1);            // past the end: repeat of the last row
-            const int32_t q0 = off0[rc], q1 = off1[rc];
-            b.p0 = same ? a.p0 : q0;
-            b.p1 = same ? a.p1 : q1;
-            b.pcs = same ? cont : (q0 & ~3);
-        };
-        auto load = [&](RunBatch &b) {
-            const int32_t rc = min(b.r, n_filled - 1);
-            const int32_t *ir = ring_idx + (int64_t)rc * row_stride;
-            const float *vr = ring_val + (int64_t)rc * row_stride;
+    auto prefetch = [&](int32_t sp, int32_t ip, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const int64_t b64 = (int64_t)sp << slice_log2;
+        if (FULL) {
 #pragma unroll
-            for (int c = 0; c < kChunksAhead; c++) {
-                // always load (from the row start when the chunk lies past the run)
-                const int32_t pc = b.pcs + gl * 4 + c * 64;
-                const int32_t pcl = pc < b.p1 ? pc : 0;
-                b.iv[c] = *reinterpret_cast<const int4 *>(ir + pcl);
-                b.vv[c] = *reinterpret_cast<const float4 *>(vr + pcl);
+            for (int u = 0; u < 4; u++) xr[u] = load_stream_f4(x + b64 + tid * 4 + u * 4096);
+        } else {
+            const int32_t len = (int32_t)(d - b64);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int32_t i = tid * 4 + u * 4096;
+                xr[u].x = (i + 0 < len) ? x[b64 + i + 0] : 0.0f;
+                xr[u].y = (i + 1 < len) ? x[b64 + i + 1] : 0.0f;
+                xr[u].z = (i + 2 < len) ? x[b64 + i + 2] : 0.0f;
+                xr[u].w = (i + 3 < len) ? x[b64 + i + 3] : 0.0f;
             }
-        };
+        }
+        o0 = offT[(int64_t)sp * m + trow];
+        o1 = offT[(int64_t)(sp + 1) * m + trow];
+        const int32_t p = min(np0[ip] + tid, klast);     // clamped: always a valid entry
+        di = nidx[p];
+        dv = nval[p];
+    };
+
+    const int32_t n_full = (int32_t)(d >> slice_log2);           // slices with all coordinates
+    __syncthreads();                          // np0/np1 visible, racc zeroed
+    if (s < n_full) prefetch(s, 0, std::true_type{}); else prefetch(s, 0, std::false_type{});
+
+    RunBatch ba, bb;
+    auto first = [&](RunBatch &b) {
+        b.r = grp;
+        const int32_t rc = min(b.r, n_filled - 1);
+        b.p0 = off0[rc]; b.p1 = off1[rc];
+        b.pcs = b.p0 & ~3;
+    };
+    auto advance = [&](const RunBatch &a, RunBatch &b) {          // b = the batch after a
+        const int32_t cont = a.pcs + kChunksAhead * 64;
+        const bool same = cont < a.p1;
+        b.r = same ? a.r : a.r + kRowGroups;
+        const int32_t rc = min(b.r, n_filled - 1);                // past the end: repeat of the last row
+        const int32_t q0 = off0[rc], q1 = off1[rc];
+        b.p0 = same ? a.p0 : q0;
+        b.p1 = same ? a.p1 : q1;
+        b.pcs = same ? cont : (q0 & ~3);
+    };
+    auto load = [&](RunBatch &b) {
+        const int32_t rc = min(b.r, n_filled - 1);
+        const int32_t *ir = ring_idx + (int64_t)rc * row_stride;
+        const float *vr = ring_val + (int64_t)rc * row_stride;
+#pragma unroll
+        for (int c = 0; c < kChunksAhead; c++) {
+            // always load (from the row start when the chunk lies past the run)
+            const int32_t pc = b.pcs + gl * 4 + c * 64;
+            const int32_t pcl = pc < b.p1 ? pc : 0;
+            b.iv[c] = *reinterpret_cast<const int4 *>(ir + pcl);
+            b.vv[c] = *reinterpret_cast<const float4 *>(vr + pcl);
+        }
+    };
+
+    for (; s < s_end; s += cpx, it++) {
+        const int32_t base = (int32_t)((int64_t)s << slice_log2);
+        // ---- switch to slice s: everything comes from registers ----
+        __syncthreads();            // previous slice fully consumed
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int32_t i = tid * 4 + u * 4096;
+            xc[i + 0] = make_float2(xr[u].x, 0.0f);
+            xc[i + 1] = make_float2(xr[u].y, 0.0f);
+            xc[i + 2] = make_float2(xr[u].z, 0.0f);
+            xc[i + 3] = make_float2(xr[u].w, 0.0f);
+        }
+        off0[tid] = o0;
+        off1[tid] = o1;
+        const int32_t q0 = np0[it], q1 = np1[it];
+        __syncthreads();            // x and offsets of slice s in LDS
+        first(ba);
+        load(ba);                   // first ring batch in flight during the scatter below
+        if (q0 + tid < q1) xc[(di - base) & mask].y = dv;         // newest row next to x
+        for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)      // runs longer than 1024 entries
+            xc[(nidx[p] - base) & mask].y = nval[p];
+        __syncthreads();
+
+        // ---- prefetch for the next slice of this workgroup ----
+        const int32_t sn = s + cpx;
+        if (sn < s_end) {           // uniform
+            if (sn < n_full) prefetch(sn, it + 1, std::true_type{});
+            else prefetch(sn, it + 1, std::false_type{});
+        }
+
+        // ---- stream the rows: two register batches used alternately ----
         auto consume = [&](const RunBatch &b) {
             double aq = 0.0, ag = 0.0;
             const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
@@ -164,9 +221,6 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
                 racc[b.r] = t;
             }
         };
-        RunBatch ba, bb;
-        first(ba);
-        load(ba);
         while (__any(ba.r < n_filled)) {
             advance(ba, bb);
             load(bb);
@@ -216,7 +270,7 @@ hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int
                      int32_t slot, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_sp, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled, slot,
-                       g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8, p.ring_idx, p.ring_val,
+                       g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8, p.ring_idx, p.ring_val,
                        p.offT, p.partial);
     return hipGetLastError();
 }
