@@ -7,7 +7,15 @@ on a gradient already resident in HBM.  The workload is the BERT-base-sized
 configuration (d = 110,000,000, m = 1024, k = 1,100,000, lambda = 1e-6) with a
 FULL 1024-row window: the window is filled with 1024 untimed steps first.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line:
+  value / ms_per_step   steps per second and milliseconds per step, timed over --steps steps
+  step_bytes            algorithmic bytes of one step, 16*n*k + 24*d + 8*k (n rows filled)
+  achieved_GBps, hbm_frac   step_bytes / step time, and that over the 8 TB/s HBM peak
+  kernel_ms             HIP-event time per step of each kernel group (events on the step's stream)
+  roofline              the slower of the two window passes (k_sp, k_lcg): algorithmic bytes per
+                        launch / HIP-event time per launch, against the HBM peak; `traffic` is the
+                        measured HBM bytes per launch from rocprofv3 counters (full window only)
+  cpu_baseline          the CPU oracle timed on this host on a bounded sample (see its `sample`)
 """
 from __future__ import annotations
 

@@ -99,6 +99,25 @@ int efcp_get_error(efcp_ctx *ctx, float *e_host);
 int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, double *coef_host,
                    uint32_t *tau, int64_t *step);
 
+/* ---- checkpoint / resume ----
+ * The complete state of a context (step count, e, the filled window rows with
+ * their slice offsets, S, the coefficient factor, the Top-k prediction) as
+ * one host buffer.  A context that imports it continues bit-identically to the
+ * one that exported it.  The layout is private to the library version (a
+ * header with a magic word, d, m, k, lambda and the geometry is checked on
+ * import); both calls synchronise the stream of the last step. */
+
+/* Bytes efcp_export_state writes now (grows with the rows filled); 0 if ctx is NULL. */
+size_t efcp_state_bytes(efcp_ctx *ctx);
+
+/* host_buf: at least efcp_state_bytes(ctx) bytes (EFCP_ENOMEM if `bytes` is smaller). */
+int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes);
+
+/* ctx must have been created with the same d, m, k and lambda as the exporter
+ * (EFCP_EINVAL otherwise, and on a damaged or truncated buffer); its previous
+ * state is replaced. */
+int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes);
+
 /* Geometry chosen at creation; any pointer may be NULL.
  *   slice      coordinates per d-slice staged in LDS by the SP and LCG kernels
  *   n_slices   ceil(d / slice)

@@ -18,7 +18,8 @@ KERNEL_GROUPS = ("ef_hist", "select", "compact", "sp", "coef", "lcg")
 
 EXPORTS = (
     "efcp_workspace_bytes", "efcp_create", "efcp_step", "efcp_destroy", "efcp_get_row",
-    "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_profile_enable",
+    "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_state_bytes",
+    "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
     "efcp_profile_read", "efcp_last_error",
 )
 
@@ -57,6 +58,12 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_get_small.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.efcp_get_geometry.restype = ctypes.c_int
     lib.efcp_get_geometry.argtypes = [vp, vp, vp, vp]
+    lib.efcp_state_bytes.restype = ctypes.c_size_t
+    lib.efcp_state_bytes.argtypes = [vp]
+    lib.efcp_export_state.restype = ctypes.c_int
+    lib.efcp_export_state.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.efcp_import_state.restype = ctypes.c_int
+    lib.efcp_import_state.argtypes = [vp, vp, ctypes.c_size_t]
     lib.efcp_profile_enable.restype = ctypes.c_int
     lib.efcp_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.efcp_profile_read.restype = ctypes.c_int
@@ -148,6 +155,18 @@ class Efcp:
         self._check(self._lib.efcp_get_geometry(self._ctx, ctypes.addressof(sl), ctypes.addressof(ns),
                                                 ctypes.addressof(rs)))
         return dict(slice=sl.value, n_slices=ns.value, row_stride=rs.value)
+
+    # ---- checkpoint / resume ----
+    def export_state(self) -> np.ndarray:
+        """The whole state as one uint8 host array."""
+        n = int(self._lib.efcp_state_bytes(self._ctx))
+        buf = np.empty(n, dtype=np.uint8)
+        self._check(self._lib.efcp_export_state(self._ctx, buf.ctypes.data, n))
+        return buf
+
+    def import_state(self, buf: np.ndarray) -> None:
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        self._check(self._lib.efcp_import_state(self._ctx, buf.ctypes.data, buf.size))
 
     # ---- per-kernel timing ----
     def profile_enable(self, on: bool = True) -> None:

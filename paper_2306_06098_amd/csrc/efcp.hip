@@ -338,6 +338,117 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
     return EFCP_OK;
 }
 
+// ---------------------------------------------------------------- checkpoint
+
+namespace {
+
+struct StateHeader {
+    uint64_t magic;          // "EFCPST01"
+    int64_t d, k, row_stride, t;
+    int32_t m, ldm, slice, n_slices;
+    double lambda;
+    uint32_t t_lo, status;
+    int32_t filled, pad;
+};
+constexpr uint64_t kStateMagic = 0x3130545350434645ull;
+
+size_t state_bytes(const efcp_ctx *ctx)
+{
+    const Geometry &g = ctx->g;
+    const size_t filled = (size_t)(ctx->t < g.m ? ctx->t : g.m);
+    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * 8 +
+           (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 + (size_t)g.m * g.ldm * 8 +
+           (size_t)g.m * 4;
+}
+
+}  // namespace
+
+extern "C" size_t efcp_state_bytes(efcp_ctx *ctx) { return ctx ? state_bytes(ctx) : 0; }
+
+extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
+{
+    if (!ctx || !host_buf) return EFCP_EINVAL;
+    if (bytes < state_bytes(ctx)) return fail(ctx, EFCP_ENOMEM, "state buffer too small");
+    if (int rc = sync_last(ctx)) return rc;
+    const Geometry &g = ctx->g;
+    const DevicePtrs &p = ctx->p;
+    SelState st;
+    uint32_t status = 0;
+    if (hipMemcpy(&st, p.sel, sizeof st, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(&status, p.status, 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(ctx, EFCP_EHIP, "copy to host failed");
+    StateHeader h{};
+    h.magic = kStateMagic;
+    h.d = g.d; h.k = g.k; h.row_stride = g.row_stride; h.t = ctx->t;
+    h.m = g.m; h.ldm = g.ldm; h.slice = g.slice; h.n_slices = g.n_slices;
+    h.lambda = ctx->lambda;
+    h.t_lo = st.t_lo; h.status = status;
+    h.filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
+    unsigned char *o = static_cast<unsigned char *>(host_buf);
+    std::memcpy(o, &h, sizeof h);
+    o += sizeof h;
+    hipError_t rc = hipSuccess;
+    auto pull = [&](const void *dev, size_t n) {
+        if (rc == hipSuccess) rc = hipMemcpy(o, dev, n, hipMemcpyDeviceToHost);
+        o += n;
+    };
+    pull(p.e, (size_t)g.d * 4);
+    for (int32_t r = 0; r < h.filled; r++) {
+        pull(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 4);
+        pull(p.ring_val + (size_t)r * g.row_stride, (size_t)g.k * 4);
+    }
+    pull(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
+    pull(p.S, (size_t)g.m * g.m * 8);
+    pull(p.W, (size_t)g.m * g.ldm * 8);
+    pull(p.rowmax, (size_t)g.m * 4);
+    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to host failed");
+    return EFCP_OK;
+}
+
+extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes)
+{
+    if (!ctx || !host_buf) return EFCP_EINVAL;
+    if (bytes < sizeof(StateHeader)) return fail(ctx, EFCP_EINVAL, "state buffer truncated");
+    StateHeader h;
+    std::memcpy(&h, host_buf, sizeof h);
+    const Geometry &g = ctx->g;
+    if (h.magic != kStateMagic || h.d != g.d || h.k != g.k || h.m != g.m || h.row_stride != g.row_stride ||
+        h.ldm != g.ldm || h.slice != g.slice || h.n_slices != g.n_slices || h.lambda != ctx->lambda ||
+        h.t < 0 || h.filled != (int32_t)(h.t < g.m ? h.t : g.m))
+        return fail(ctx, EFCP_EINVAL, "state does not belong to a context of this shape");
+    const int64_t t_keep = ctx->t;
+    ctx->t = h.t;                                    // state_bytes() depends on the step count
+    if (bytes < state_bytes(ctx)) {
+        ctx->t = t_keep;
+        return fail(ctx, EFCP_EINVAL, "state buffer truncated");
+    }
+    if (hipDeviceSynchronize() != hipSuccess) { ctx->t = t_keep; return fail(ctx, EFCP_EHIP, "sync failed"); }
+    const DevicePtrs &p = ctx->p;
+    const unsigned char *o = static_cast<const unsigned char *>(host_buf) + sizeof h;
+    hipError_t rc = hipSuccess;
+    auto push = [&](void *dev, size_t n) {
+        if (rc == hipSuccess) rc = hipMemcpy(dev, o, n, hipMemcpyHostToDevice);
+        o += n;
+    };
+    push(p.e, (size_t)g.d * 4);
+    for (int32_t r = 0; r < h.filled; r++) {
+        push(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 4);
+        push(p.ring_val + (size_t)r * g.row_stride, (size_t)g.k * 4);
+    }
+    push(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
+    push(p.S, (size_t)g.m * g.m * 8);
+    push(p.W, (size_t)g.m * g.ldm * 8);
+    push(p.rowmax, (size_t)g.m * 4);
+    SelState st{};
+    st.t_lo = h.t_lo;
+    if (rc == hipSuccess) rc = hipMemcpy(p.sel, &st, sizeof st, hipMemcpyHostToDevice);
+    if (rc == hipSuccess) rc = hipMemcpy(p.status, &h.status, 4, hipMemcpyHostToDevice);
+    if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, kBins1 * sizeof(uint32_t));
+    if (rc == hipSuccess) rc = hipDeviceSynchronize();
+    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
+    return EFCP_OK;
+}
+
 extern "C" int efcp_get_geometry(efcp_ctx *ctx, int32_t *slice, int32_t *n_slices, int64_t *row_stride)
 {
     if (!ctx) return EFCP_EINVAL;

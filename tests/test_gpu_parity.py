@@ -67,6 +67,31 @@ def test_shapes_and_edges(env, d, m, k, lam, T):
     print((d, m, k), w)
 
 
+def test_random_shapes_sweep(env):
+    """Thirty seeded random (d, m, k, lambda) with d from a handful of elements to
+    several slices plus a ragged tail, k from 1 to d, windows that fill and evict;
+    some streams quantised to force ties at the threshold."""
+    torch, oracle_mod, binding = env
+    rng = np.random.default_rng(2024)
+    for case in range(30):
+        d = int(rng.choice([rng.integers(1, 64), rng.integers(64, 5_000), rng.integers(5_000, 140_000)]))
+        m = int(rng.integers(1, 24))
+        k = int(rng.choice([1, d, rng.integers(1, d + 1), max(1, d // 100)]))
+        lam = float(10.0 ** rng.uniform(-5, 0))
+        T = m + int(rng.integers(1, 8))
+        quant = case % 3 == 0
+        scale = np.exp(rng.standard_normal(d)).astype(np.float32)
+
+        def grads():
+            z = np.zeros(d, np.float32)
+            for _ in range(T):
+                z = (0.8 * z + rng.standard_normal(d)).astype(np.float32)
+                g = scale * z
+                yield (np.round(g * 4) / 4).astype(np.float32) if quant else g
+        w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads())
+        print(case, (d, m, k, lam, T, quant), w["out"])
+
+
 def test_forced_ties_integer_gradients(env):
     """Small-integer gradients: the threshold magnitude is shared by many
     coordinates on every step, so the lowest-index tie rule decides."""
@@ -216,6 +241,42 @@ def test_steps_without_output_update_the_same_state(env):
         assert np.array_equal(a[i], b[i])
     for (i0, v0), (i1, v1) in zip(a[5], b[5]):
         assert np.array_equal(i0, i1) and np.array_equal(bits(v0), bits(v1))
+
+
+def test_export_import_resumes_bit_identically(env):
+    """Checkpoint in the middle of a run (partly filled window, then an evicting
+    one), import into a fresh context, continue both: same bits everywhere."""
+    torch, _, binding = env
+    d, m, k, lam = 70_001, 7, 650, 1e-3
+    grads = list(_stream(synth.Workload("x", d, m, k, lam, 24, 0.9, 8), 24))
+    g = torch.empty(d, dtype=torch.float32, device="cuda:0")
+    for cut in (4, 15):
+        a = binding.Efcp(d, m, k, lam)
+        out_a = torch.empty_like(g)
+        for x in grads[:cut]:
+            g.copy_(torch.from_numpy(x)); a.step(g, out_a)
+        blob = a.export_state()
+        b = binding.Efcp(d, m, k, lam)
+        b.import_state(blob)
+        assert b.get_small()["step"] == cut
+        out_b = torch.empty_like(g)
+        for x in grads[cut:]:
+            g.copy_(torch.from_numpy(x)); a.step(g, out_a); b.step(g, out_b)
+            assert bool((out_a.view(torch.int32) == out_b.view(torch.int32)).all())
+        assert np.array_equal(bits(a.get_error()), bits(b.get_error()))
+        sa, sb = a.get_small(), b.get_small()
+        assert np.array_equal(sa["S"], sb["S"]) and np.array_equal(sa["coef"], sb["coef"])
+        for r in range(m):
+            (i0, v0), (i1, v1) = a.get_row(r), b.get_row(r)
+            assert np.array_equal(i0, i1) and np.array_equal(bits(v0), bits(v1))
+        # a context of another shape refuses the blob; a truncated blob is refused too
+        c = binding.Efcp(d, m, k + 1, lam)
+        with pytest.raises(binding.EfcpError):
+            c.import_state(blob)
+        with pytest.raises(binding.EfcpError):
+            b.import_state(blob[: blob.size // 2])
+        for ctx in (a, b, c):
+            ctx.destroy()
 
 
 def test_argument_checks(env):
