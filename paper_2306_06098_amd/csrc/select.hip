@@ -418,7 +418,7 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
                 row_idx[pos] = j;
                 row_val[pos] = v;
-                e[j] = 0.0f;
+                __builtin_nontemporal_store(0.0f, &e[j]);      // scattered, not read again this step
             }
             eq_run += __popcll(eq_mask);
             out_run += __popcll(take_mask);
