@@ -36,17 +36,18 @@ MEASURED_TRAFFIC = {("bert_base", "lcg"): 10.40e9, ("bert_base", "sp"): 9.94e9}
 METRIC = "Sparse M-FAC EFCP steps/s + achieved HBM GB/s (d=110M, m=1024, 1% density)"
 
 
-def step_bytes(d, k, n):
-    """Algorithmic bytes of one step with n filled rows."""
+def step_bytes(d, k, n, entry=8):
+    """Algorithmic bytes of one step with n filled rows; entry = bytes per window
+    entry (8: int32 index + fp32 value, 4: 16-bit in-slice index + bf16 value)."""
     return {
-        "ef": 12 * d + 8 * k,              # read g, read e, write e; write the new row
-        "sp": 8 * n * k + 4 * d,           # window once + x
-        "lcg": 8 * n * k + 8 * d,          # window once + x + out
-        "total": 16 * n * k + 24 * d + 8 * k,
+        "ef": 12 * d + entry * k,              # read g, read e, write e; write the new row
+        "sp": entry * n * k + 4 * d,           # window once + x
+        "lcg": entry * n * k + 8 * d,          # window once + x + out
+        "total": 2 * entry * n * k + 24 * d + entry * k,
     }
 
 
-def cpu_baseline(wl, seconds_budget=30.0):
+def cpu_baseline(wl, bf16=False, seconds_budget=30.0):
     """The oracle as it stands, on this host, on a bounded sample: d/100 with
     the full m-row window preloaded with random sparse rows, then timed steps
     on the workload's own gradient recipe."""
@@ -56,7 +57,7 @@ def cpu_baseline(wl, seconds_budget=30.0):
     oracle.build()
     scale = 100
     d, k = wl.d // scale, wl.k // scale
-    o = oracle.Oracle(d, wl.m, k, wl.lam)
+    o = oracle.Oracle(d, wl.m, k, wl.lam, values_bf16=bf16)
     rng = np.random.default_rng(1234)
     for _ in range(wl.m):
         o.load_row(*synth.random_sparse_row(d, k, rng))
@@ -83,6 +84,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--fill", type=int, default=-1, help="untimed steps before warm-up (default m)")
+    ap.add_argument("--values", choices=["fp32", "bf16"], default="fp32",
+                    help="window format: fp32 = the benchmark's definition (8-byte entries); "
+                         "bf16 = bfloat16 values + 16-bit in-slice indices (4-byte entries)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -94,7 +98,9 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    ctx = binding.Efcp(wl.d, wl.m, wl.k, wl.lam)
+    bf16 = args.values == "bf16"
+    ctx = binding.Efcp(wl.d, wl.m, wl.k, wl.lam,
+                       values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
     stream = synth.TorchGradientStream(wl.d, wl.rho, wl.seed, dev)
     out = torch.empty(wl.d, dtype=torch.float32, device=dev)
     pool = [torch.empty(wl.d, dtype=torch.float32, device=dev) for _ in range(4)]
@@ -127,7 +133,7 @@ def main():
     assert torch.isfinite(out).all().item()
 
     n = min(sm["step"], wl.m)
-    by = step_bytes(wl.d, wl.k, n)
+    by = step_bytes(wl.d, wl.k, n, 4 if bf16 else 8)
     ms_step = (t1 - t0) * 1e3 / args.steps
     per_launch = {kname: ms_groups[kname] / max(covered, 1) for kname in ms_groups}
     dom = "lcg" if per_launch["lcg"] >= per_launch["sp"] else "sp"
@@ -138,21 +144,22 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: d={wl.d} m={wl.m} k={wl.k} lambda={wl.lam} "
-                               f"window rows filled={n}", "fill_steps": fill},
+                               f"window rows filled={n}", "fill_steps": fill,
+                   "window_format": "bf16 value + u16 in-slice index" if bf16 else "fp32 value + i32 index"},
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_step * 1e-3) / 1e9,
         "hbm_frac": by["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernel_ms": per_launch,
         "roofline": {"bound": "hbm", "kernel": "k_" + dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, dom)) if n == wl.m else None,
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, dom)) if (n == wl.m and not bf16) else None,
                      "bytes_per_launch": by[dom], "ms_per_launch": per_launch[dom]},
     }
     ctx.destroy()
     del pool, out, stream
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl)
+        result["cpu_baseline"] = cpu_baseline(wl, bf16)
     print(json.dumps(result), flush=True)
 
 

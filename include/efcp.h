@@ -46,9 +46,20 @@ typedef enum {
     EFCP_ENUMERIC = -4  /* the coefficient factorisation met a non-positive pivot */
 } efcp_status;
 
+/* Storage format of the window G = (I, V) (Section "Format for V"). */
+typedef enum {
+    EFCP_VALUES_FP32 = 0,  /* int32 index + fp32 value per entry (8 bytes), the default        */
+    EFCP_VALUES_BF16 = 1   /* bfloat16 value + 16-bit index inside the entry's 16384-coordinate
+                              slice (4 bytes).  c holds bf16(a_j) (round to nearest even) at the
+                              selected positions and, as xi = a - c says, e keeps the rounding
+                              remainder a_j - bf16(a_j) there instead of 0.  Selection is still
+                              done on the fp32 accumulator.                                     */
+} efcp_value_format;
+
 /* Bytes of device memory a context for (d, m, k) needs; 0 if the arguments
- * are invalid.  Uses the current device's LDS size to choose the slice width. */
+ * are invalid (or the device lacks the 160 KiB of LDS per workgroup of gfx950). */
 size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k);
+size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int32_t value_format);
 
 /* Create a context: error feedback e = 0, empty window, S = 0, step count 0.
  *   d       dimension,            1 <= d < 2^31
@@ -62,6 +73,10 @@ size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k);
  * Synchronises the device once (state initialisation). */
 int efcp_create(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
                 void *workspace, size_t workspace_bytes);
+
+/* Same with an explicit window format (efcp_value_format); efcp_create is the fp32 format. */
+int efcp_create_fmt(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
+                    int32_t value_format, void *workspace, size_t workspace_bytes);
 
 /* One step (see the top of this file).
  *   grad    device, d floats, 16-byte aligned, read only
@@ -82,8 +97,9 @@ int efcp_destroy(efcp_ctx *ctx);
 /* ---- inspection (parity tests, checkpointing); each synchronises `stream`
  * of the last step before copying to host memory ---- */
 
-/* Row stored in `slot` (0 <= slot < m): k ascending indices and k values.
- * EFCP_EINVAL if the slot has not been filled yet. */
+/* Row stored in `slot` (0 <= slot < m): k ascending (absolute) indices and k
+ * values as fp32, whatever the storage format.  EFCP_EINVAL if the slot has
+ * not been filled yet. */
 int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, float *val_host);
 
 /* Error feedback vector e, d floats. */

@@ -43,6 +43,10 @@ def _load():
     vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
     lib.eo_create.restype = vp
     lib.eo_create.argtypes = [i64, i32, i64, dbl]
+    lib.eo_create_fmt.restype = vp
+    lib.eo_create_fmt.argtypes = [i64, i32, i64, dbl, ctypes.c_int]
+    lib.eo_bf16_round.restype = ctypes.c_float
+    lib.eo_bf16_round.argtypes = [ctypes.c_float]
     lib.eo_destroy.restype = None
     lib.eo_destroy.argtypes = [vp]
     lib.eo_step.restype = ctypes.c_int
@@ -100,13 +104,19 @@ def coefficients(S: np.ndarray, q: np.ndarray, m: int, lam: float) -> np.ndarray
     return coef
 
 
+def bf16_round(a: float) -> float:
+    """fp32 -> bfloat16 (nearest even) -> fp32, as the oracle stores values."""
+    return float(_load().eo_bf16_round(ctypes.c_float(a)))
+
+
 class Oracle:
     """State of the oracle: error feedback e, window G=(I,V), Gram matrix S."""
 
-    def __init__(self, d: int, m: int, k: int, lam: float):
+    def __init__(self, d: int, m: int, k: int, lam: float, values_bf16: bool = False):
         self._lib = _load()
         self.d, self.m, self.k, self.lam = int(d), int(m), int(k), float(lam)
-        self._st = self._lib.eo_create(self.d, self.m, self.k, self.lam)
+        self.values_bf16 = bool(values_bf16)
+        self._st = self._lib.eo_create_fmt(self.d, self.m, self.k, self.lam, int(self.values_bf16))
         if not self._st:
             raise ValueError("eo_create rejected (d, m, k, lambda)")
 

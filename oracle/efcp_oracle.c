@@ -17,6 +17,7 @@ struct eo_state {
     int64_t d, k;
     int32_t m;
     double lambda;
+    int values_bf16;    /* stored values are bfloat16 */
     int64_t t;          /* steps done */
     float *e;           /* error feedback xi, d */
     int32_t **idx;      /* m row pointers, NULL until the slot is filled */
@@ -26,6 +27,24 @@ struct eo_state {
     float *a;           /* d, accumulator scratch */
     float *dense;       /* d, newest row scattered to dense, scratch */
 };
+
+float eo_bf16_round(float a)
+{
+    uint32_t bits;
+    memcpy(&bits, &a, 4);
+    bits += 0x7fffu + ((bits >> 16) & 1u);      /* nearest, ties to even */
+    bits &= 0xffff0000u;
+    float r;
+    memcpy(&r, &bits, 4);
+    return r;
+}
+
+eo_state *eo_create_fmt(int64_t d, int32_t m, int64_t k, double lambda, int values_bf16)
+{
+    eo_state *st = eo_create(d, m, k, lambda);
+    if (st) st->values_bf16 = values_bf16 != 0;
+    return st;
+}
 
 eo_state *eo_create(int64_t d, int32_t m, int64_t k, double lambda)
 {
@@ -218,9 +237,13 @@ int eo_step(eo_state *st, const float *g, const float *x, double *y)
     if (!idx || !val) { free(idx); free(val); return -1; }
     if (eo_topk(st->a, d, k, idx, val) != 0) { free(idx); free(val); return -1; }
 
+    /* bfloat16 window: c holds the rounded values. */
+    if (st->values_bf16)
+        for (int64_t p = 0; p < k; p++) val[p] = eo_bf16_round(val[p]);
+
     /* line 7: xi = a - c. */
     memcpy(st->e, st->a, (size_t)d * sizeof(float));
-    for (int64_t p = 0; p < k; p++) st->e[idx[p]] = 0.0f;
+    for (int64_t p = 0; p < k; p++) st->e[idx[p]] = st->a[idx[p]] - val[p];
 
     /* line 8, first half: update G (ring buffer) and S. */
     int rc = insert_row(st, idx, val);

@@ -42,6 +42,16 @@ typedef struct eo_state eo_state;
 /* Returns NULL on invalid arguments or allocation failure.
  * Requires 1 <= k <= d < 2^31, m >= 1, lambda > 0. */
 eo_state *eo_create(int64_t d, int32_t m, int64_t k, double lambda);
+
+/* Same with the stored values V kept in bfloat16 (Section "Format for V"):
+ * values_bf16 != 0 makes the compressed vector c hold bf16(a_j) (round to
+ * nearest even on the upper 16 bits) at the selected positions, and, as
+ * xi = a - c says, the error keeps the rounding remainder a_j - bf16(a_j) there
+ * instead of 0.  Selection itself is done on the fp32 accumulator. */
+eo_state *eo_create_fmt(int64_t d, int32_t m, int64_t k, double lambda, int values_bf16);
+
+/* Round an fp32 value to bfloat16 (nearest, ties to even), returned as fp32. */
+float eo_bf16_round(float a);
 void eo_destroy(eo_state *st);
 
 /* One full step.  g: d floats (gradient).  x: d floats to precondition, or

@@ -16,8 +16,10 @@ LIB_PATH = os.path.join(_HERE, "libefcp.so")
 EFCP_OK, EFCP_EINVAL, EFCP_ENOMEM, EFCP_EHIP, EFCP_ENUMERIC = 0, -1, -2, -3, -4
 KERNEL_GROUPS = ("ef_hist", "select", "compact", "sp", "coef", "lcg")
 
+VALUES_FP32, VALUES_BF16 = 0, 1
+
 EXPORTS = (
-    "efcp_workspace_bytes", "efcp_create", "efcp_step", "efcp_destroy", "efcp_get_row",
+    "efcp_workspace_bytes", "efcp_workspace_bytes_fmt", "efcp_create", "efcp_create_fmt", "efcp_step", "efcp_destroy", "efcp_get_row",
     "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
     "efcp_profile_read", "efcp_last_error",
@@ -46,6 +48,10 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_workspace_bytes.argtypes = [i64, i32, i64]
     lib.efcp_create.restype = ctypes.c_int
     lib.efcp_create.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, vp, ctypes.c_size_t]
+    lib.efcp_workspace_bytes_fmt.restype = ctypes.c_size_t
+    lib.efcp_workspace_bytes_fmt.argtypes = [i64, i32, i64, i32]
+    lib.efcp_create_fmt.restype = ctypes.c_int
+    lib.efcp_create_fmt.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, i32, vp, ctypes.c_size_t]
     lib.efcp_step.restype = ctypes.c_int
     lib.efcp_step.argtypes = [vp, vp, vp, vp]
     lib.efcp_destroy.restype = ctypes.c_int
@@ -74,23 +80,24 @@ def load_library() -> ctypes.CDLL:
     return lib
 
 
-def efcp_workspace_bytes(d: int, m: int, k: int) -> int:
-    return int(load_library().efcp_workspace_bytes(d, m, k))
+def efcp_workspace_bytes(d: int, m: int, k: int, values: int = VALUES_FP32) -> int:
+    return int(load_library().efcp_workspace_bytes_fmt(d, m, k, values))
 
 
 class Efcp:
     """One libefcp context: efcp_create / efcp_step / efcp_destroy."""
 
-    def __init__(self, d: int, m: int, k: int, lam: float, workspace=None):
+    def __init__(self, d: int, m: int, k: int, lam: float, workspace=None, values: int = VALUES_FP32):
         self._lib = load_library()
         self.d, self.m, self.k, self.lam = int(d), int(m), int(k), float(lam)
+        self.values = int(values)
         self._ctx = ctypes.c_void_p()
         self._workspace = workspace          # torch tensor kept alive, or None
         ws_ptr, ws_bytes = None, 0
         if workspace is not None:
             ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-        rc = self._lib.efcp_create(ctypes.byref(self._ctx), self.d, self.m, self.k, self.lam,
-                                   ws_ptr, ws_bytes)
+        rc = self._lib.efcp_create_fmt(ctypes.byref(self._ctx), self.d, self.m, self.k, self.lam,
+                                       self.values, ws_ptr, ws_bytes)
         if rc != EFCP_OK:
             self._ctx = ctypes.c_void_p()
             raise EfcpError(rc, "efcp_create failed")

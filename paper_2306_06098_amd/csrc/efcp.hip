@@ -20,8 +20,9 @@ constexpr int kProfEvents = EFCP_K_COUNT + 1;
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Largest power-of-two slice whose LDS working set fits the device.
-bool make_geometry(int64_t d, int32_t m, int64_t k, Geometry &g, const char **why)
+bool make_geometry(int64_t d, int32_t m, int64_t k, int32_t fmt, Geometry &g, const char **why)
 {
+    if (fmt != kFmtF32 && fmt != kFmtBf16) { *why = "unknown value format"; return false; }
     if (d < 1 || d >= ((int64_t)1 << 31)) { *why = "d out of range [1, 2^31)"; return false; }
     if (m < 1 || m > kMaxM) { *why = "m out of range [1, 1024]"; return false; }
     if (k < 1 || k > d) { *why = "k out of range [1, d]"; return false; }
@@ -31,7 +32,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k, Geometry &g, const char **wh
         *why = "no HIP device";
         return false;
     }
-    g.d = d; g.k = k; g.m = m;
+    g.d = d; g.k = k; g.m = m; g.fmt = fmt;
     g.row_stride = (int64_t)align_up((size_t)k, 64);
     g.ldm = (int32_t)align_up((size_t)m, 8);
     const size_t fixed_sp = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2) + 2 * 512 * sizeof(int32_t);
@@ -65,8 +66,9 @@ Layout make_layout(const Geometry &g)
     Layout l{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    l.ring_idx = take((size_t)g.m * g.row_stride * sizeof(int32_t));
-    l.ring_val = take((size_t)g.m * g.row_stride * sizeof(float));
+    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;          // bytes per index and per value
+    l.ring_idx = take((size_t)g.m * g.row_stride * esz);
+    l.ring_val = take((size_t)g.m * g.row_stride * esz);
     l.partial = take((size_t)g.sp_grid * g.m * sizeof(double2));
     l.cand_idx = take((size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
     l.cand_val = take((size_t)g.n_sel_blocks * kCandBlock * sizeof(float));
@@ -121,23 +123,34 @@ static int fail(efcp_ctx *ctx, int code, const char *msg)
     return code;
 }
 
-extern "C" size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k)
+extern "C" size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int32_t value_format)
 {
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, g, &why)) return 0;
+    if (!make_geometry(d, m, k, value_format, g, &why)) return 0;
     return make_layout(g).total;
+}
+
+extern "C" size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k)
+{
+    return efcp_workspace_bytes_fmt(d, m, k, EFCP_VALUES_FP32);
 }
 
 extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
                            void *workspace, size_t workspace_bytes)
+{
+    return efcp_create_fmt(out, d, m, k, lambda, EFCP_VALUES_FP32, workspace, workspace_bytes);
+}
+
+extern "C" int efcp_create_fmt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
+                               int32_t value_format, void *workspace, size_t workspace_bytes)
 {
     if (!out) return EFCP_EINVAL;
     *out = nullptr;
     if (!(lambda > 0.0) || !std::isfinite(lambda)) return EFCP_EINVAL;
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, g, &why)) return EFCP_EINVAL;
+    if (!make_geometry(d, m, k, value_format, g, &why)) return EFCP_EINVAL;
     const Layout l = make_layout(g);
 
     efcp_ctx *ctx = new (std::nothrow) efcp_ctx();
@@ -171,8 +184,8 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
     unsigned char *b = static_cast<unsigned char *>(ctx->ws);
     DevicePtrs &p = ctx->p;
     p.e = reinterpret_cast<float *>(b + l.e);
-    p.ring_idx = reinterpret_cast<int32_t *>(b + l.ring_idx);
-    p.ring_val = reinterpret_cast<float *>(b + l.ring_val);
+    p.ring_idx = b + l.ring_idx;
+    p.ring_val = b + l.ring_val;
     p.offT = reinterpret_cast<int32_t *>(b + l.offT);
     p.S = reinterpret_cast<double *>(b + l.S);
     p.W = reinterpret_cast<double *>(b + l.W);
@@ -299,9 +312,32 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
     if (slot < 0 || slot >= filled) return fail(ctx, EFCP_EINVAL, "slot not filled");
     if (int rc = sync_last(ctx)) return rc;
     const size_t off = (size_t)slot * g.row_stride;
-    if (hipMemcpy(idx_host, ctx->p.ring_idx + off, (size_t)g.k * 4, hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(val_host, ctx->p.ring_val + off, (size_t)g.k * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    if (g.fmt == kFmtF32) {
+        if (hipMemcpy(idx_host, static_cast<int32_t *>(ctx->p.ring_idx) + off, (size_t)g.k * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess ||
+            hipMemcpy(val_host, static_cast<float *>(ctx->p.ring_val) + off, (size_t)g.k * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess)
+            return fail(ctx, EFCP_EHIP, "copy to host failed");
+        return EFCP_OK;
+    }
+    // bfloat16 format: 16-bit in-slice indices become absolute with the row's slice offsets
+    std::vector<uint16_t> i16((size_t)g.k), v16((size_t)g.k);
+    std::vector<int32_t> offs((size_t)g.n_slices + 1);
+    if (hipMemcpy(i16.data(), static_cast<uint16_t *>(ctx->p.ring_idx) + off, (size_t)g.k * 2,
+                  hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(v16.data(), static_cast<uint16_t *>(ctx->p.ring_val) + off, (size_t)g.k * 2,
+                  hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy2D(offs.data(), sizeof(int32_t), ctx->p.offT + slot, (size_t)g.m * sizeof(int32_t),
+                    sizeof(int32_t), (size_t)g.n_slices + 1, hipMemcpyDeviceToHost) != hipSuccess)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
+    for (int32_t s = 0; s < g.n_slices; s++) {
+        const int32_t base = s << g.slice_log2;
+        for (int32_t p = offs[s]; p < offs[s + 1]; p++) idx_host[p] = base + (int32_t)i16[(size_t)p];
+    }
+    for (int64_t p = 0; p < g.k; p++) {
+        const uint32_t bits = (uint32_t)v16[(size_t)p] << 16;
+        std::memcpy(&val_host[p], &bits, 4);
+    }
     return EFCP_OK;
 }
 
@@ -348,7 +384,7 @@ struct StateHeader {
     int32_t m, ldm, slice, n_slices;
     double lambda;
     uint32_t t_lo, status;
-    int32_t filled, pad;
+    int32_t filled, fmt;
 };
 constexpr uint64_t kStateMagic = 0x3130545350434645ull;
 
@@ -356,7 +392,8 @@ size_t state_bytes(const efcp_ctx *ctx)
 {
     const Geometry &g = ctx->g;
     const size_t filled = (size_t)(ctx->t < g.m ? ctx->t : g.m);
-    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * 8 +
+    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
+    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * 2 * esz +
            (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 + (size_t)g.m * g.ldm * 8 +
            (size_t)g.m * 4;
 }
@@ -384,6 +421,8 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     h.lambda = ctx->lambda;
     h.t_lo = st.t_lo; h.status = status;
     h.filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
+    h.fmt = g.fmt;
+    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
     unsigned char *o = static_cast<unsigned char *>(host_buf);
     std::memcpy(o, &h, sizeof h);
     o += sizeof h;
@@ -394,8 +433,8 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     };
     pull(p.e, (size_t)g.d * 4);
     for (int32_t r = 0; r < h.filled; r++) {
-        pull(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 4);
-        pull(p.ring_val + (size_t)r * g.row_stride, (size_t)g.k * 4);
+        pull(static_cast<unsigned char *>(p.ring_idx) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
+        pull(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
     }
     pull(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     pull(p.S, (size_t)g.m * g.m * 8);
@@ -414,6 +453,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     const Geometry &g = ctx->g;
     if (h.magic != kStateMagic || h.d != g.d || h.k != g.k || h.m != g.m || h.row_stride != g.row_stride ||
         h.ldm != g.ldm || h.slice != g.slice || h.n_slices != g.n_slices || h.lambda != ctx->lambda ||
+        h.fmt != g.fmt ||
         h.t < 0 || h.filled != (int32_t)(h.t < g.m ? h.t : g.m))
         return fail(ctx, EFCP_EINVAL, "state does not belong to a context of this shape");
     const int64_t t_keep = ctx->t;
@@ -424,6 +464,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     }
     if (hipDeviceSynchronize() != hipSuccess) { ctx->t = t_keep; return fail(ctx, EFCP_EHIP, "sync failed"); }
     const DevicePtrs &p = ctx->p;
+    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
     const unsigned char *o = static_cast<const unsigned char *>(host_buf) + sizeof h;
     hipError_t rc = hipSuccess;
     auto push = [&](void *dev, size_t n) {
@@ -432,8 +473,8 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     };
     push(p.e, (size_t)g.d * 4);
     for (int32_t r = 0; r < h.filled; r++) {
-        push(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 4);
-        push(p.ring_val + (size_t)r * g.row_stride, (size_t)g.k * 4);
+        push(static_cast<unsigned char *>(p.ring_idx) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
+        push(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
     }
     push(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     push(p.S, (size_t)g.m * g.m * 8);

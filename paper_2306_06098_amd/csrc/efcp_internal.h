@@ -2,8 +2,11 @@
 //
 // Data layout in device memory (one context):
 //   e         float  [d]                 error feedback xi (Algorithm 1)
-//   ring_idx  int32  [m][row_stride]     window indices I, ascending inside a row
-//   ring_val  float  [m][row_stride]     window values  V
+//   ring_idx  idx_t  [m][row_stride]     window indices I, ascending inside a row
+//   ring_val  val_t  [m][row_stride]     window values  V
+//                                        (int32 absolute index + fp32 value, or, in the
+//                                        bfloat16 format, uint16 index inside the slice
+//                                        + bf16 value: 4 bytes per entry instead of 8)
 //   offT      int32  [n_slices+1][m]     offT[s][r] = first entry of row r whose
 //                                        index is >= s*slice (slice-major so one
 //                                        workgroup reads its m offsets contiguously)
@@ -33,6 +36,52 @@ constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
 constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
 constexpr int kHistPriv = 128;       // private histograms of the candidate passes
 
+// Window entry formats.  EPL = entries one 16-byte load brings per array; a chunk is what
+// a 16-lane group reads with one load per array; kBatch = chunks a lane keeps in flight.
+enum : int { kFmtF32 = 0, kFmtBf16 = 1 };
+
+template <int FMT> struct Fmt;
+template <> struct Fmt<kFmtF32> {
+    using idx_t = int32_t;
+    using val_t = float;
+    static constexpr int EPL = 4, kChunk = 64, kBatch = 3;
+};
+template <> struct Fmt<kFmtBf16> {
+    using idx_t = uint16_t;
+    using val_t = uint16_t;
+    static constexpr int EPL = 8, kChunk = 128, kBatch = 2;
+};
+
+// Entry c (0..EPL-1) of a 16-byte load: position inside the slice and value.
+template <int FMT>
+__device__ __forceinline__ int32_t entry_pos(const int4 &raw, int c, int32_t base, int32_t mask)
+{
+    const int32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    if constexpr (FMT == kFmtF32) return (w[c] - base) & mask;
+    else return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
+}
+
+template <int FMT>
+__device__ __forceinline__ float entry_val(const int4 &raw, int c)
+{
+    const int32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    if constexpr (FMT == kFmtF32) return __int_as_float(w[c]);
+    else return __uint_as_float((((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) << 16);
+}
+
+// A single stored entry as (position in its slice, fp32 value).
+__device__ __forceinline__ float stored_val(float v) { return v; }
+__device__ __forceinline__ float stored_val(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+__device__ __forceinline__ int32_t stored_pos(int32_t i, int32_t base, int32_t mask) { return (i - base) & mask; }
+__device__ __forceinline__ int32_t stored_pos(uint16_t i, int32_t, int32_t mask) { return (int32_t)i & mask; }
+
+// fp32 -> bfloat16 bits, round to nearest even (inputs are finite).
+__device__ __forceinline__ uint32_t bf16_bits(float a)
+{
+    const uint32_t b = __float_as_uint(a);
+    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
 // Device-resident state of the radix select of the current step.
 struct SelState {
     uint32_t prefix;     // key bits fixed so far
@@ -50,6 +99,7 @@ enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
 struct Geometry {
     int64_t d, k, row_stride;
     int32_t m, ldm;
+    int32_t fmt;             // kFmtF32 / kFmtBf16
     int32_t slice, slice_log2, n_slices;
     int32_t n_sel_blocks;
     int32_t sp_grid;         // persistent SP workgroups: 8 * (workgroups per XCD)
@@ -58,8 +108,8 @@ struct Geometry {
 
 struct DevicePtrs {
     float *e;
-    int32_t *ring_idx;
-    float *ring_val;
+    void *ring_idx;          // Fmt<fmt>::idx_t [m][row_stride]
+    void *ring_val;          // Fmt<fmt>::val_t [m][row_stride]
     int32_t *offT;
     double *S, *W;
     double2 *partial, *sq, *zw;

@@ -18,35 +18,33 @@
 
 namespace efcp {
 
-constexpr int kLcgChunksAhead = 3;
-
-// One batch = up to kLcgChunksAhead chunks of 64 entries of one row's run in the slice.  A run
+// One batch = up to kBatch chunks of one row's run in the slice (see the SP pass).  A run
 // longer than a batch is continued by the next batch (same row, pcs advanced), so the row
 // loop has a single shape and the number of loads in flight is always known.
+template <int FMT>
 struct LcgBatch {
-    int4 iv[kLcgChunksAhead];
-    float4 vv[kLcgChunksAhead];
+    int4 iv[Fmt<FMT>::kBatch];
+    int4 vv[Fmt<FMT>::kBatch];
     int32_t r;          // row (may be >= n_filled: then nothing is valid)
-    int32_t pcs;        // position of chunk 0, lane 0 (multiple of 4)
+    int32_t pcs;        // position of chunk 0, lane 0 (multiple of EPL)
     int32_t p0, p1;     // the row's run in this slice
     double c;
 };
 
 // round(c*v / unit) as an integer: the magic constant puts the product's
 // units digit at the last mantissa bit; integer LDS atomics add it.
-__device__ __forceinline__ void lcg_scatter(const int4 &iv, const float4 &vv, int32_t pc, int32_t p0,
+template <int FMT>
+__device__ __forceinline__ void lcg_scatter(const int4 &iv, const int4 &vv, int32_t pc, int32_t p0,
                                             int32_t p1, int32_t base, int32_t mask, double c,
                                             double magic, long long magic_bits,
                                             unsigned long long *__restrict__ acc)
 {
-    const int32_t ii[4] = {iv.x, iv.y, iv.z, iv.w};
-    const float fv[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
+    for (int q = 0; q < Fmt<FMT>::EPL; q++) {
         const int32_t p = pc + q;
         if (p >= p0 && p < p1) {
-            const int32_t li = (ii[q] - base) & mask;
-            const double t = fma(c, (double)fv[q], magic);
+            const int32_t li = entry_pos<FMT>(iv, q, base, mask);
+            const double t = fma(c, (double)entry_val<FMT>(vv, q), magic);
             const long long cnt = __double_as_longlong(t) - magic_bits;
             atomicAdd(&acc[li], (unsigned long long)cnt);
         }
@@ -57,16 +55,20 @@ __device__ __forceinline__ void lcg_scatter(const int4 &iv, const float4 &vv, in
 // contiguous slice range [x*per, (x+1)*per) and its workgroups work on neighbouring slices at any
 // moment (same mapping as the SP pass).  While a slice's rows stream, the x values of its epilogue and
 // the row offsets of the workgroup's next slice are already on their way in registers.
+template <int FMT>
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
                                               int64_t d, int32_t m, int32_t n_filled, int64_t row_stride,
                                               int32_t slice_log2, int32_t nsl, int32_t cpx,
-                                              const int32_t *__restrict__ ring_idx,
-                                              const float *__restrict__ ring_val,
+                                              const typename Fmt<FMT>::idx_t *__restrict__ ring_idx,
+                                              const typename Fmt<FMT>::val_t *__restrict__ ring_val,
                                               const int32_t *__restrict__ offT,
                                               const double *__restrict__ coef,
                                               const uint32_t *__restrict__ rowmax,
                                               uint32_t *__restrict__ status, double inv_lambda)
 {
+    using idx_t = typename Fmt<FMT>::idx_t;
+    using val_t = typename Fmt<FMT>::val_t;
+    constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t slice = 1 << slice_log2;
     unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem);   // [slice]
@@ -117,14 +119,14 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     // Batches: two register sets used alternately (no copies between them): while one batch
     // is scattered, the loads of the group's next batch are in flight.
     const int32_t *off0 = offs, *off1 = offs + kMaxM;             // offsets of the current slice
-    auto first = [&](LcgBatch &b) {
+    auto first = [&](LcgBatch<FMT> &b) {
         b.r = grp;
         const int32_t rc = min(b.r, n_filled - 1);
         b.p0 = off0[rc]; b.p1 = off1[rc]; b.c = cf[rc];
-        b.pcs = b.p0 & ~3;
+        b.pcs = b.p0 & ~(EPL - 1);
     };
-    auto advance = [&](const LcgBatch &a, LcgBatch &b) {          // b = the batch after a
-        const int32_t cont = a.pcs + kLcgChunksAhead * 64;
+    auto advance = [&](const LcgBatch<FMT> &a, LcgBatch<FMT> &b) {   // b = the batch after a
+        const int32_t cont = a.pcs + kBatch * kChunk;
         const bool same = cont < a.p1;
         b.r = same ? a.r : a.r + kRowGroups;
         const int32_t rc = min(b.r, n_filled - 1);                // past the end: repeat of the last row
@@ -132,23 +134,23 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         b.p0 = same ? a.p0 : q0;
         b.p1 = same ? a.p1 : q1;
         b.c = cf[rc];
-        b.pcs = same ? cont : (q0 & ~3);
+        b.pcs = same ? cont : (q0 & ~(EPL - 1));
     };
-    auto load = [&](LcgBatch &b) {
+    auto load = [&](LcgBatch<FMT> &b) {
         const int32_t rc = min(b.r, n_filled - 1);
-        const int32_t *ir = ring_idx + (int64_t)rc * row_stride;
-        const float *vr = ring_val + (int64_t)rc * row_stride;
+        const idx_t *ir = ring_idx + (int64_t)rc * row_stride;
+        const val_t *vr = ring_val + (int64_t)rc * row_stride;
 #pragma unroll
-        for (int q = 0; q < kLcgChunksAhead; q++) {
+        for (int q = 0; q < kBatch; q++) {
             // always load (from the row start when the chunk lies past the run)
-            const int32_t pc = b.pcs + gl * 4 + q * 64;
+            const int32_t pc = b.pcs + gl * EPL + q * kChunk;
             const int32_t pcl = pc < b.p1 ? pc : 0;
             b.iv[q] = *reinterpret_cast<const int4 *>(ir + pcl);
-            b.vv[q] = *reinterpret_cast<const float4 *>(vr + pcl);
+            b.vv[q] = *reinterpret_cast<const int4 *>(vr + pcl);
         }
     };
 
-    LcgBatch ba, bb;
+    LcgBatch<FMT> ba, bb;
     first(ba);
     load(ba);                                 // first batch of the first slice
     int buf = 0;
@@ -162,12 +164,12 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         const int32_t len = FULL ? slice : (int32_t)(d - base64);
         const int32_t sn = s + cpx;
         const int32_t sl = sn < s_end ? sn : s;
-        auto consume = [&](const LcgBatch &b) {
+        auto consume = [&](const LcgBatch<FMT> &b) {
             const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
 #pragma unroll
-            for (int q = 0; q < kLcgChunksAhead; q++)
-                lcg_scatter(b.iv[q], b.vv[q], b.pcs + gl * 4 + q * 64, b.p0, hi, base, mask, b.c, magic,
-                            magic_bits, acc);
+            for (int q = 0; q < kBatch; q++)
+                lcg_scatter<FMT>(b.iv[q], b.vv[q], b.pcs + gl * EPL + q * kChunk, b.p0, hi, base, mask, b.c,
+                                 magic, magic_bits, acc);
         };
 
         // on their way while the rows stream: x of this slice (for the epilogue) and the row
@@ -247,16 +249,28 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
 hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
                       int32_t n_filled, double lambda, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_lcg, dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m, n_filled,
-                       g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8, p.ring_idx, p.ring_val,
-                       p.offT, p.coef, p.rowmax, p.status, 1.0 / lambda);
+    if (g.fmt == kFmtBf16)
+        hipLaunchKernelGGL(k_lcg<kFmtBf16>, dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m,
+                           n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                           static_cast<const uint16_t *>(p.ring_idx),
+                           static_cast<const uint16_t *>(p.ring_val), p.offT, p.coef, p.rowmax, p.status,
+                           1.0 / lambda);
+    else
+        hipLaunchKernelGGL(k_lcg<kFmtF32>, dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m,
+                           n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                           static_cast<const int32_t *>(p.ring_idx), static_cast<const float *>(p.ring_val),
+                           p.offT, p.coef, p.rowmax, p.status, 1.0 / lambda);
     return hipGetLastError();
 }
 
 hipError_t configure_lcg(const Geometry &g)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<kFmtF32>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    if (rc == hipSuccess)
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<kFmtBf16>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    return rc;
 }
 
 }  // namespace efcp

@@ -373,8 +373,11 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
 
 // ------------------------------------------------------------------
 // Ordered compaction of the selected candidates of segment b into the ring
-// row, and e = a - c: selected entries of the error buffer become +0.
+// row, and e = a - c: selected entries of the error buffer become +0 (fp32
+// window) or the rounding remainder a - bf16(a) (bfloat16 window, whose
+// entries also keep only the index inside the segment = slice).
 // One wave per segment; candidates are already in index order.
+template <int FMT>
 __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__restrict__ cand_idx,
                                                               const float *__restrict__ cand_val,
                                                               const uint32_t *__restrict__ cand_cnt,
@@ -382,12 +385,13 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
                                                               const SelState *__restrict__ sel,
                                                               const uint32_t *__restrict__ sel_off,
                                                               const uint32_t *__restrict__ eq_before,
-                                                              int32_t *__restrict__ row_idx,
-                                                              float *__restrict__ row_val)
+                                                              typename Fmt<FMT>::idx_t *__restrict__ row_idx,
+                                                              typename Fmt<FMT>::val_t *__restrict__ row_val)
 {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int32_t b = blockIdx.x * 4 + w;
     if (b >= nb) return;
+    const int32_t seg_first = b * kCandBlock;
     const uint32_t tau = sel->tau, quota = sel->quota;
     const uint32_t cnt = cand_cnt[b];
     const int32_t *sidx = cand_idx + (int64_t)b * kCandBlock;
@@ -416,9 +420,17 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
             const uint64_t take_mask = __ballot(take);
             if (take) {
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
-                row_idx[pos] = j;
-                row_val[pos] = v;
-                __builtin_nontemporal_store(0.0f, &e[j]);      // scattered, not read again this step
+                float rem = 0.0f;
+                if constexpr (FMT == kFmtF32) {
+                    row_idx[pos] = j;
+                    row_val[pos] = v;
+                } else {
+                    const uint32_t hb = bf16_bits(v);
+                    row_idx[pos] = (typename Fmt<FMT>::idx_t)(j - seg_first);
+                    row_val[pos] = (typename Fmt<FMT>::val_t)hb;
+                    rem = v - __uint_as_float(hb << 16);
+                }
+                __builtin_nontemporal_store(rem, &e[j]);       // scattered, not read again this step
             }
             eq_run += __popcll(eq_mask);
             out_run += __popcll(take_mask);
@@ -460,10 +472,16 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, h
 
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_cand_compact, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0, stream,
-                       p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
-                       p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
-                       p.ring_val + (int64_t)slot * g.row_stride);
+    if (g.fmt == kFmtBf16)
+        hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
+                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
+                           p.eq_before, static_cast<uint16_t *>(p.ring_idx) + (int64_t)slot * g.row_stride,
+                           static_cast<uint16_t *>(p.ring_val) + (int64_t)slot * g.row_stride);
+    else
+        hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
+                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
+                           p.eq_before, static_cast<int32_t *>(p.ring_idx) + (int64_t)slot * g.row_stride,
+                           static_cast<float *>(p.ring_val) + (int64_t)slot * g.row_stride);
     return hipGetLastError();
 }
 

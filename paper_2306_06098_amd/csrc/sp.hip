@@ -21,32 +21,30 @@
 
 namespace efcp {
 
-constexpr int kChunksAhead = 3;      // 16-byte loads per array a lane keeps in flight per batch
-
-// One batch = up to kChunksAhead chunks of 64 entries of one row's run in the slice: lane gl of
-// the 16-lane group reads entries [pc, pc+4), pc = pcs + 4*gl + 64*c.  A run longer than a batch
-// is continued by the next batch (same row, pcs advanced), so the row loop has a single shape
+// One batch = up to kBatch chunks of one row's run in the slice: lane gl of the 16-lane group
+// reads entries [pc, pc+EPL), pc = pcs + EPL*gl + kChunk*c.  A run longer than a batch is
+// continued by the next batch (same row, pcs advanced), so the row loop has a single shape
 // and the number of loads in flight is always known.
+template <int FMT>
 struct RunBatch {
-    int4 iv[kChunksAhead];
-    float4 vv[kChunksAhead];
+    int4 iv[Fmt<FMT>::kBatch];
+    int4 vv[Fmt<FMT>::kBatch];
     int32_t r;          // row (may be >= n_filled: then nothing is valid)
-    int32_t pcs;        // position of chunk 0, lane 0 (multiple of 4)
+    int32_t pcs;        // position of chunk 0, lane 0 (multiple of EPL)
     int32_t p0, p1;     // the row's run in this slice
 };
 
-__device__ __forceinline__ void sp_accumulate(const int4 &iv, const float4 &vv, int32_t pc, int32_t p0,
+template <int FMT>
+__device__ __forceinline__ void sp_accumulate(const int4 &iv, const int4 &vv, int32_t pc, int32_t p0,
                                               int32_t p1, int32_t base, int32_t mask,
                                               const float2 *__restrict__ xc, double &aq, double &ag)
 {
-    const int32_t ii[4] = {iv.x, iv.y, iv.z, iv.w};
-    const float fv[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
-    for (int c = 0; c < 4; c++) {
+    for (int c = 0; c < Fmt<FMT>::EPL; c++) {
         const int32_t p = pc + c;
         const bool ok = (p >= p0) && (p < p1);
-        const int32_t li = ok ? ((ii[c] - base) & mask) : 0;
-        const double v = ok ? (double)fv[c] : 0.0;
+        const int32_t li = ok ? entry_pos<FMT>(iv, c, base, mask) : 0;
+        const double v = ok ? (double)entry_val<FMT>(vv, c) : 0.0;
         const float2 t = xc[li];
         aq = fma(v, (double)t.x, aq);
         ag = fma(v, (double)t.y, ag);
@@ -66,14 +64,18 @@ constexpr int kMaxSlicesPerWg = 512;     // ceil(2^31 / 16384 / 8 / 32)
 // newest row's entries that fall into it.  The switch between slices is then
 // three barriers and LDS traffic, with the first batch of ring loads of the
 // new slice issued before the last two.
+template <int FMT>
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              int32_t n_filled, int32_t slot, int64_t row_stride,
                                              int64_t k, int32_t slice_log2, int32_t nsl, int32_t cpx,
-                                             const int32_t *__restrict__ ring_idx,
-                                             const float *__restrict__ ring_val,
+                                             const typename Fmt<FMT>::idx_t *__restrict__ ring_idx,
+                                             const typename Fmt<FMT>::val_t *__restrict__ ring_val,
                                              const int32_t *__restrict__ offT,
                                              double2 *__restrict__ partial)
 {
+    using idx_t = typename Fmt<FMT>::idx_t;
+    using val_t = typename Fmt<FMT>::val_t;
+    constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t slice = 1 << slice_log2;
     float2 *xc = reinterpret_cast<float2 *>(smem);                 // [slice]: (x_j, c_new_j)
@@ -91,8 +93,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int32_t s_first = xcd * per + cu;
     const int32_t mask = slice - 1;
     const int32_t trow = min(tid, m - 1);
-    const int32_t *nidx = ring_idx + (int64_t)slot * row_stride;   // newest row
-    const float *nval = ring_val + (int64_t)slot * row_stride;
+    const idx_t *nidx = ring_idx + (int64_t)slot * row_stride;     // newest row
+    const val_t *nval = ring_val + (int64_t)slot * row_stride;
     const int32_t klast = (int32_t)(k - 1);
 
     racc[tid] = make_double2(0.0, 0.0);
@@ -108,8 +110,9 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 
     // state carried from one slice to the next (prefetched while the previous one streams)
     float4 xr[4];
-    int32_t o0, o1, di;
-    float dv;
+    int32_t o0, o1;
+    idx_t di;
+    val_t dv;
     int32_t it = 0;                           // index of the current slice in this workgroup's list
     int32_t s = s_first;
 
@@ -141,34 +144,34 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     __syncthreads();                          // np0/np1 visible, racc zeroed
     if (s < n_full) prefetch(s, 0, std::true_type{}); else prefetch(s, 0, std::false_type{});
 
-    RunBatch ba, bb;
-    auto first = [&](RunBatch &b) {
+    RunBatch<FMT> ba, bb;
+    auto first = [&](RunBatch<FMT> &b) {
         b.r = grp;
         const int32_t rc = min(b.r, n_filled - 1);
         b.p0 = off0[rc]; b.p1 = off1[rc];
-        b.pcs = b.p0 & ~3;
+        b.pcs = b.p0 & ~(EPL - 1);
     };
-    auto advance = [&](const RunBatch &a, RunBatch &b) {          // b = the batch after a
-        const int32_t cont = a.pcs + kChunksAhead * 64;
+    auto advance = [&](const RunBatch<FMT> &a, RunBatch<FMT> &b) {   // b = the batch after a
+        const int32_t cont = a.pcs + kBatch * kChunk;
         const bool same = cont < a.p1;
         b.r = same ? a.r : a.r + kRowGroups;
         const int32_t rc = min(b.r, n_filled - 1);                // past the end: repeat of the last row
         const int32_t q0 = off0[rc], q1 = off1[rc];
         b.p0 = same ? a.p0 : q0;
         b.p1 = same ? a.p1 : q1;
-        b.pcs = same ? cont : (q0 & ~3);
+        b.pcs = same ? cont : (q0 & ~(EPL - 1));
     };
-    auto load = [&](RunBatch &b) {
+    auto load = [&](RunBatch<FMT> &b) {
         const int32_t rc = min(b.r, n_filled - 1);
-        const int32_t *ir = ring_idx + (int64_t)rc * row_stride;
-        const float *vr = ring_val + (int64_t)rc * row_stride;
+        const idx_t *ir = ring_idx + (int64_t)rc * row_stride;
+        const val_t *vr = ring_val + (int64_t)rc * row_stride;
 #pragma unroll
-        for (int c = 0; c < kChunksAhead; c++) {
+        for (int c = 0; c < kBatch; c++) {
             // always load (from the row start when the chunk lies past the run)
-            const int32_t pc = b.pcs + gl * 4 + c * 64;
+            const int32_t pc = b.pcs + gl * EPL + c * kChunk;
             const int32_t pcl = pc < b.p1 ? pc : 0;
             b.iv[c] = *reinterpret_cast<const int4 *>(ir + pcl);
-            b.vv[c] = *reinterpret_cast<const float4 *>(vr + pcl);
+            b.vv[c] = *reinterpret_cast<const int4 *>(vr + pcl);
         }
     };
 
@@ -190,9 +193,9 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         __syncthreads();            // x and offsets of slice s in LDS
         first(ba);
         load(ba);                   // first ring batch in flight during the scatter below
-        if (q0 + tid < q1) xc[(di - base) & mask].y = dv;         // newest row next to x
-        for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)      // runs longer than 1024 entries
-            xc[(nidx[p] - base) & mask].y = nval[p];
+        if (q0 + tid < q1) xc[stored_pos(di, base, mask)].y = stored_val(dv);   // newest row next to x
+        for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)       // runs longer than 1024 entries
+            xc[stored_pos(nidx[p], base, mask)].y = stored_val(nval[p]);
         __syncthreads();
 
         // ---- prefetch for the next slice of this workgroup ----
@@ -203,12 +206,13 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         }
 
         // ---- stream the rows: two register batches used alternately ----
-        auto consume = [&](const RunBatch &b) {
+        auto consume = [&](const RunBatch<FMT> &b) {
             double aq = 0.0, ag = 0.0;
             const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
 #pragma unroll
-            for (int c = 0; c < kChunksAhead; c++)
-                sp_accumulate(b.iv[c], b.vv[c], b.pcs + gl * 4 + c * 64, b.p0, hi, base, mask, xc, aq, ag);
+            for (int c = 0; c < kBatch; c++)
+                sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, base, mask,
+                                   xc, aq, ag);
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) {
                 aq += __shfl_xor(aq, o, 16);
@@ -269,9 +273,16 @@ __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ 
 hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
                      int32_t slot, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_sp, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled, slot,
-                       g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8, p.ring_idx, p.ring_val,
-                       p.offT, p.partial);
+    if (g.fmt == kFmtBf16)
+        hipLaunchKernelGGL(k_sp<kFmtBf16>, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m,
+                           n_filled, slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                           static_cast<const uint16_t *>(p.ring_idx),
+                           static_cast<const uint16_t *>(p.ring_val), p.offT, p.partial);
+    else
+        hipLaunchKernelGGL(k_sp<kFmtF32>, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m,
+                           n_filled, slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                           static_cast<const int32_t *>(p.ring_idx), static_cast<const float *>(p.ring_val),
+                           p.offT, p.partial);
     return hipGetLastError();
 }
 
@@ -284,8 +295,12 @@ hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_fi
 
 hipError_t configure_sp(const Geometry &g)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<kFmtF32>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    if (rc == hipSuccess)
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<kFmtBf16>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    return rc;
 }
 
 }  // namespace efcp

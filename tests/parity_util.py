@@ -26,11 +26,13 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 
 
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
-               check_small=True, verbose=False, out_tol=OUT_TOL):
-    """grads: iterable of float32 numpy arrays.  Returns dict of worst errors."""
+               check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False):
+    """grads: iterable of float32 numpy arrays.  bf16: the bfloat16 window
+    format on both sides.  Returns dict of worst errors."""
     dev = torch.device("cuda:0")
-    o = oracle_mod.Oracle(d, m, k, lam)
-    g_gpu = binding.Efcp(d, m, k, lam)
+    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16)
+    g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
+    e_prev = np.zeros(d, np.float32)
     grad_d = torch.empty(d, dtype=torch.float32, device=dev)
     out_d = torch.empty(d, dtype=torch.float32, device=dev)
     worst = dict(out=0.0, S=0.0, q=0.0, coef=0.0)
@@ -39,7 +41,9 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
         for g in grads:
             t += 1
             g = np.ascontiguousarray(g, dtype=np.float32)
+            a = e_prev + g                      # the accumulator, one fp32 rounding per element
             y = o.step(g)
+            e_prev = o.error.copy()
             grad_d.copy_(torch.from_numpy(g))
             g_gpu.step(grad_d, out_d)
             torch.cuda.synchronize()
@@ -69,7 +73,7 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
                 worst["coef"] = max(worst["coef"], sc)
                 assert sS <= 1e-10, f"step {t}: Gram matrix off by {sS:.3e}"
                 assert sq <= 1e-10, f"step {t}: q off by {sq:.3e}"
-                sel_key = bits(ov) & np.uint32(0x7FFFFFFF)
+                sel_key = bits(a[oi]) & np.uint32(0x7FFFFFFF)
                 assert sm["tau"] == int(sel_key.min()), f"step {t}: threshold key differs"
             if verbose:
                 print(f"  step {t}: out {err:.2e}", flush=True)

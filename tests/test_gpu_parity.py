@@ -34,6 +34,25 @@ def test_tiny_workload_all_steps(env):
     assert w["steps"] == wl.T
 
 
+def test_tiny_workload_all_steps_bf16_window(env):
+    """Same workload with the bfloat16 window format (bf16 values, 16-bit
+    in-slice indices): stored values, indices, e (with the rounding remainders)
+    bit-exact against the oracle in the same mode; F^-1 g within 1e-3."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, wl.lam, _stream(wl, wl.T), bf16=True)
+    print("tiny bf16", w)
+    assert w["steps"] == wl.T
+
+
+def test_resnet20_workload_bf16_window(env):
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["resnet20"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, wl.lam, _stream(wl, 120),
+                   check_error_every=10, bf16=True)
+    print("resnet20 bf16", w)
+
+
 def test_resnet20_workload_all_steps(env):
     """d=272,474 (not a multiple of the slice, the compaction block or 4), m=1024,
     k=2,725, lambda=1e-5, 500 steps."""
@@ -45,6 +64,7 @@ def test_resnet20_workload_all_steps(env):
     assert w["steps"] == wl.T
 
 
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("d,m,k,lam,T", [
     (20_001, 8, 201, 1e-3, 40),       # ragged tail, eviction from step 9 on
     (4_099, 3, 4_099, 1e-2, 9),       # k = d: Dense M-FAC, e stays 0
@@ -53,7 +73,7 @@ def test_resnet20_workload_all_steps(env):
     (16_384 * 3, 7, 500, 1e-4, 20),   # exact multiple of the slice
     (100_003, 1, 1000, 1e-3, 5),      # m = 1: every step evicts
 ])
-def test_shapes_and_edges(env, d, m, k, lam, T):
+def test_shapes_and_edges(env, d, m, k, lam, T, bf16):
     torch, oracle_mod, binding = env
     rng = np.random.default_rng(d + m)
     scale = np.exp(rng.standard_normal(d)).astype(np.float32)
@@ -63,8 +83,8 @@ def test_shapes_and_edges(env, d, m, k, lam, T):
         for _ in range(T):
             z = (0.7 * z + rng.standard_normal(d)).astype(np.float32)
             yield scale * z
-    w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads())
-    print((d, m, k), w)
+    w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16)
+    print((d, m, k, bf16), w)
 
 
 def test_random_shapes_sweep(env):
@@ -88,7 +108,7 @@ def test_random_shapes_sweep(env):
                 z = (0.8 * z + rng.standard_normal(d)).astype(np.float32)
                 g = scale * z
                 yield (np.round(g * 4) / 4).astype(np.float32) if quant else g
-        w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads())
+        w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=case % 2 == 1)
         print(case, (d, m, k, lam, T, quant), w["out"])
 
 
@@ -100,6 +120,9 @@ def test_forced_ties_integer_gradients(env):
     it = synth.integer_stream(d, seed=9)
     w = run_parity(torch, oracle_mod, binding, d, m, k, 1e-2, (next(it) for _ in range(15)))
     print("ties", w)
+    it = synth.integer_stream(d, seed=10, lo=-700, hi=700)
+    w = run_parity(torch, oracle_mod, binding, d, m, k, 1e-2, (next(it) for _ in range(15)), bf16=True)
+    print("ties bf16", w)
 
 
 def test_threshold_jumps_between_steps(env):
@@ -250,13 +273,13 @@ def test_export_import_resumes_bit_identically(env):
     d, m, k, lam = 70_001, 7, 650, 1e-3
     grads = list(_stream(synth.Workload("x", d, m, k, lam, 24, 0.9, 8), 24))
     g = torch.empty(d, dtype=torch.float32, device="cuda:0")
-    for cut in (4, 15):
-        a = binding.Efcp(d, m, k, lam)
+    for cut, values in ((4, binding.VALUES_FP32), (15, binding.VALUES_FP32), (15, binding.VALUES_BF16)):
+        a = binding.Efcp(d, m, k, lam, values=values)
         out_a = torch.empty_like(g)
         for x in grads[:cut]:
             g.copy_(torch.from_numpy(x)); a.step(g, out_a)
         blob = a.export_state()
-        b = binding.Efcp(d, m, k, lam)
+        b = binding.Efcp(d, m, k, lam, values=values)
         b.import_state(blob)
         assert b.get_small()["step"] == cut
         out_b = torch.empty_like(g)
@@ -270,7 +293,11 @@ def test_export_import_resumes_bit_identically(env):
             (i0, v0), (i1, v1) = a.get_row(r), b.get_row(r)
             assert np.array_equal(i0, i1) and np.array_equal(bits(v0), bits(v1))
         # a context of another shape refuses the blob; a truncated blob is refused too
-        c = binding.Efcp(d, m, k + 1, lam)
+        c = binding.Efcp(d, m, k + 1, lam, values=values)
+        with pytest.raises(binding.EfcpError):
+            c.import_state(blob)
+        c.destroy()
+        c = binding.Efcp(d, m, k, lam, values=1 - values)          # other window format
         with pytest.raises(binding.EfcpError):
             c.import_state(blob)
         with pytest.raises(binding.EfcpError):

@@ -52,6 +52,19 @@ def test_step_matches_dense_inversion(oracle_mod, d, m, k, lam, T):
         assert _rel(y, g.astype(np.float64) / lam - o.coef @ C) < 1e-10   # summation order only
 
 
+def test_bf16_window_matches_dense_inversion(oracle_mod):
+    """With bfloat16 values F is built from the rounded rows actually stored."""
+    d, m, k, lam = 400, 6, 37, 1e-3
+    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=True)
+    rng = np.random.default_rng(21)
+    for t in range(15):
+        g = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+        y = o.step(g)
+        C = _dense_rows(o)
+        assert _rel(y, _dense_solve(C, m, lam, g)) < 1e-9
+        assert np.allclose(o.gram, C @ C.T, rtol=1e-12, atol=1e-12)
+
+
 def test_general_x_matches_dense_inversion(oracle_mod):
     d, m, k, lam = 256, 8, 20, 1e-3
     o = oracle_mod.Oracle(d, m, k, lam)

@@ -165,3 +165,52 @@ def test_ring_slot_order_and_eviction(oracle_mod):
             i, v = o.row(slot)
             assert np.array_equal(i, history[t - 1 - back][0])
             assert np.array_equal(v, history[t - 1 - back][1])
+
+
+# ---------------------------------------------------------------------------
+# bfloat16 window values (Section "Format for V")
+
+def test_bf16_rounding_matches_torch_bfloat16(oracle_mod):
+    """The oracle's fp32 -> bf16 rounding against torch's CPU conversion
+    (round to nearest even), on random values, exact ties and the extremes."""
+    import torch
+    rng = np.random.default_rng(5)
+    vals = (rng.standard_normal(4000) * np.exp(rng.uniform(-60, 60, 4000))).astype(np.float32)
+    ties = np.array([0x3F808000, 0x3F818000, 0x3F80FFFF, 0x3F808001, 0x00008000, 0x00018000,
+                     0x7F7F7FFF, 0xBF808000, 0x80000000, 0x00000000], dtype=np.uint32).view(np.float32)
+    allv = np.concatenate([vals, ties])
+    ref = torch.from_numpy(allv).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([oracle_mod.bf16_round(float(v)) for v in allv], dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert not (got.view(np.uint32) & np.uint32(0xFFFF)).any()
+
+
+def test_bf16_window_error_feedback_keeps_the_rounding_remainder(oracle_mod):
+    """xi = a - c with c = bf16(a) on the selection: the remainder stays in e,
+    so the telescoping identity still holds exactly (integer gradients)."""
+    d, m, k, T = 3000, 4, 60, 25
+    o = oracle_mod.Oracle(d, m, k, 1e-2, values_bf16=True)
+    stream = synth.integer_stream(d, seed=6, lo=-300, hi=300)      # beyond bf16's 8 exact bits
+    sum_g = np.zeros(d)
+    sum_c = np.zeros(d)
+    e_prev = np.zeros(d, np.float32)
+    saw_remainder = False
+    for _ in range(T):
+        g = next(stream)
+        o.step(g)
+        idx, val = o.row(o.newest_slot)
+        a = e_prev + g
+        assert not (val.view(np.uint32) & np.uint32(0xFFFF)).any()          # representable in bf16
+        assert (np.abs(val - a[idx]) <= np.abs(a[idx]) * 2.0 ** -8).all()   # half an ulp of 8 bits
+        e = o.error
+        assert np.array_equal(e[idx], a[idx] - val)
+        saw_remainder |= bool(e[idx].any())
+        mask = np.ones(d, bool); mask[idx] = False
+        assert np.array_equal(e[mask], a[mask])
+        # selection is by |a| in fp32, before rounding
+        assert np.array_equal(idx, oracle_mod.topk(a, k)[0])
+        sum_g += g
+        sum_c[idx] += val
+        assert np.array_equal(sum_c + e, sum_g)
+        e_prev = e.copy()
+    assert saw_remainder
