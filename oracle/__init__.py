@@ -51,6 +51,10 @@ def _load():
     lib.eo_destroy.argtypes = [vp]
     lib.eo_step.restype = ctypes.c_int
     lib.eo_step.argtypes = [vp, vp, vp, vp]
+    lib.eo_step_compressed.restype = ctypes.c_int
+    lib.eo_step_compressed.argtypes = [vp, vp, vp]
+    lib.eo_apply.restype = ctypes.c_int
+    lib.eo_apply.argtypes = [vp, vp, vp]
     lib.eo_step_count.restype = i64
     lib.eo_step_count.argtypes = [vp]
     lib.eo_filled.restype = i32
@@ -139,6 +143,24 @@ class Oracle:
         y = np.empty(self.d, dtype=np.float64)
         if self._lib.eo_step(self._st, _ptr(g), xp, _ptr(y)) != 0:
             raise MemoryError("eo_step")
+        return y
+
+    def step_compressed(self, g: np.ndarray) -> np.ndarray:
+        """One step that preconditions the compressed accumulator c_t itself."""
+        g = np.ascontiguousarray(g, dtype=np.float32)
+        assert g.size == self.d
+        y = np.empty(self.d, dtype=np.float64)
+        if self._lib.eo_step_compressed(self._st, _ptr(g), _ptr(y)) != 0:
+            raise MemoryError("eo_step_compressed")
+        return y
+
+    def apply(self, x: np.ndarray) -> np.ndarray:
+        """y = F^{-1} x for the current window; no insertion."""
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        assert x.size == self.d
+        y = np.empty(self.d, dtype=np.float64)
+        if self._lib.eo_apply(self._st, _ptr(x), _ptr(y)) != 0:
+            raise MemoryError("eo_apply")
         return y
 
     def load_row(self, idx: np.ndarray, val: np.ndarray) -> None:

@@ -222,11 +222,59 @@ int eo_load_row(eo_state *st, const int32_t *idx, const float *val)
     return insert_row(st, idx, val);
 }
 
-int eo_step(eo_state *st, const float *g, const float *x, double *y)
+/* q_r = <c_r, x>, coefficients in age order, y = x/lambda - sum_r coef_r c_r
+ * for the window as it stands. */
+static int precondition(eo_state *st, const float *x, double *y)
 {
     const int64_t d = st->d, k = st->k;
     const int32_t m = st->m;
-    if (!x) x = g;
+    for (int32_t r = 0; r < m; r++) {
+        st->q[r] = 0.0;
+        st->coef[r] = 0.0;
+        if (!st->idx[r]) continue;
+        double s = 0.0;
+        for (int64_t p = 0; p < k; p++)
+            s += (double)st->val[r][p] * (double)x[st->idx[r][p]];
+        st->q[r] = s;
+    }
+    const int32_t n = eo_filled(st);
+    if (n > 0) {
+        const int32_t newest = (int32_t)((st->t - 1) % m);
+        int32_t *order = malloc((size_t)n * sizeof(int32_t));
+        double *Sn = malloc((size_t)n * n * sizeof(double));
+        double *qn = malloc((size_t)n * sizeof(double));
+        double *cn = malloc((size_t)n * sizeof(double));
+        if (!order || !Sn || !qn || !cn) { free(order); free(Sn); free(qn); free(cn); return -1; }
+        for (int32_t a = 0; a < n; a++)          /* age a: 0 = oldest, n-1 = newest */
+            order[a] = (int32_t)(((int64_t)newest - (n - 1) + a + (int64_t)m * 2) % m);
+        for (int32_t a = 0; a < n; a++) {
+            qn[a] = st->q[order[a]];
+            for (int32_t b = 0; b < n; b++)
+                Sn[(size_t)a * n + b] = st->S[(size_t)order[a] * m + order[b]];
+        }
+        const int rc = eo_coefficients(Sn, qn, n, m, st->lambda, cn);
+        for (int32_t a = 0; a < n; a++) st->coef[order[a]] = cn[a];
+        free(order); free(Sn); free(qn); free(cn);
+        if (rc != 0) return -1;
+    }
+    /* eq. (2): y = x/lambda - sum_r coef_r c_r. */
+    for (int64_t j = 0; j < d; j++) y[j] = (double)x[j] / st->lambda;
+    for (int32_t r = 0; r < m; r++) {
+        if (!st->idx[r]) continue;
+        const double c = st->coef[r];
+        for (int64_t p = 0; p < k; p++)
+            y[st->idx[r][p]] -= c * (double)st->val[r][p];
+    }
+    return 0;
+}
+
+int eo_apply(eo_state *st, const float *x, double *y) { return precondition(st, x, y); }
+
+/* Lines 5-7 of Algorithm 1 and the window update; on return idx/val of the
+ * newest slot hold c_t. */
+static int compress_and_insert(eo_state *st, const float *g)
+{
+    const int64_t d = st->d, k = st->k;
 
     /* Algorithm 1 line 5: a = xi + g (fp32). */
     for (int64_t j = 0; j < d; j++) st->a[j] = st->e[j] + g[j];
@@ -246,48 +294,25 @@ int eo_step(eo_state *st, const float *g, const float *x, double *y)
     for (int64_t p = 0; p < k; p++) st->e[idx[p]] = st->a[idx[p]] - val[p];
 
     /* line 8, first half: update G (ring buffer) and S. */
-    int rc = insert_row(st, idx, val);
+    const int rc = insert_row(st, idx, val);
     free(idx); free(val);
-    if (rc != 0) return -1;
+    return rc;
+}
 
-    /* Scalar products with x. */
-    for (int32_t r = 0; r < m; r++) {
-        st->q[r] = 0.0;
-        st->coef[r] = 0.0;
-        if (!st->idx[r]) continue;
-        double s = 0.0;
-        for (int64_t p = 0; p < k; p++)
-            s += (double)st->val[r][p] * (double)x[st->idx[r][p]];
-        st->q[r] = s;
-    }
+int eo_step(eo_state *st, const float *g, const float *x, double *y)
+{
+    if (compress_and_insert(st, g) != 0) return -1;
+    return precondition(st, x ? x : g, y);
+}
 
-    /* Coefficients: gather the filled rows in age order (oldest first). */
-    const int32_t n = eo_filled(st);
-    const int32_t newest = (int32_t)((st->t - 1) % m);
-    int32_t *order = malloc((size_t)n * sizeof(int32_t));
-    double *Sn = malloc((size_t)n * n * sizeof(double));
-    double *qn = malloc((size_t)n * sizeof(double));
-    double *cn = malloc((size_t)n * sizeof(double));
-    if (!order || !Sn || !qn || !cn) { free(order); free(Sn); free(qn); free(cn); return -1; }
-    for (int32_t a = 0; a < n; a++)          /* age a: 0 = oldest, n-1 = newest */
-        order[a] = (int32_t)(((int64_t)newest - (n - 1) + a + (int64_t)m * 2) % m);
-    for (int32_t a = 0; a < n; a++) {
-        qn[a] = st->q[order[a]];
-        for (int32_t b = 0; b < n; b++)
-            Sn[(size_t)a * n + b] = st->S[(size_t)order[a] * m + order[b]];
-    }
-    rc = eo_coefficients(Sn, qn, n, m, st->lambda, cn);
-    for (int32_t a = 0; a < n; a++) st->coef[order[a]] = cn[a];
-    free(order); free(Sn); free(qn); free(cn);
-    if (rc != 0) return -1;
-
-    /* eq. (2): y = x/lambda - sum_r coef_r c_r. */
-    for (int64_t j = 0; j < d; j++) y[j] = (double)x[j] / st->lambda;
-    for (int32_t r = 0; r < m; r++) {
-        if (!st->idx[r]) continue;
-        const double c = st->coef[r];
-        for (int64_t p = 0; p < k; p++)
-            y[st->idx[r][p]] -= c * (double)st->val[r][p];
-    }
-    return 0;
+int eo_step_compressed(eo_state *st, const float *g, double *y)
+{
+    if (compress_and_insert(st, g) != 0) return -1;
+    const int32_t slot = (int32_t)((st->t - 1) % st->m);
+    float *x = calloc((size_t)st->d, sizeof(float));            /* c_t scattered to dense */
+    if (!x) return -1;
+    for (int64_t p = 0; p < st->k; p++) x[st->idx[slot][p]] = st->val[slot][p];
+    const int rc = precondition(st, x, y);
+    free(x);
+    return rc;
 }

@@ -59,6 +59,15 @@ void eo_destroy(eo_state *st);
  * allocation failure. */
 int eo_step(eo_state *st, const float *g, const float *x, double *y);
 
+/* Algorithm 1 line 8 as printed: the vector preconditioned is the compressed
+ * accumulator itself, u = A(c_t), i.e. x = c_t scattered to dense.  Otherwise
+ * identical to eo_step. */
+int eo_step_compressed(eo_state *st, const float *g, double *y);
+
+/* y = F^{-1} x for the window as it stands (eq. (2)); the state is not changed
+ * except for the q / coef views below. */
+int eo_apply(eo_state *st, const float *x, double *y);
+
 /* Read-only views of the state after the last step. */
 int64_t eo_step_count(const eo_state *st);          /* t */
 int32_t eo_filled(const eo_state *st);              /* n_t = min(t, m) */

@@ -76,6 +76,52 @@ def test_general_x_matches_dense_inversion(oracle_mod):
         assert _rel(y, _dense_solve(_dense_rows(o), m, lam, x)) < 1e-9
 
 
+def test_apply_matches_dense_inversion_and_leaves_window_alone(oracle_mod):
+    """eo_apply: F^{-1}x for the window as it stands, before the first step
+    (F = lambda I), on a partly filled and on a wrapped window."""
+    d, m, k, lam = 300, 5, 25, 2e-3
+    o = oracle_mod.Oracle(d, m, k, lam)
+    rng = np.random.default_rng(4)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    assert np.array_equal(o.apply(x0), x0.astype(np.float64) / lam)
+    for t in range(9):
+        g = rng.standard_normal(d).astype(np.float32)
+        o.step(g)
+        before = (o.t, o.error.copy(), o.gram.copy(), _dense_rows(o))
+        for _ in range(2):
+            x = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+            y = o.apply(x)
+            assert _rel(y, _dense_solve(before[3], m, lam, x)) < 1e-9
+        assert o.t == before[0] and np.array_equal(o.error, before[1])
+        assert np.array_equal(o.gram, before[2]) and np.array_equal(_dense_rows(o), before[3])
+    g = rng.standard_normal(d).astype(np.float32)
+    y = o.step(g)
+    assert np.array_equal(o.apply(g), y)
+
+
+def test_step_compressed_preconditions_c_t(oracle_mod):
+    """Algorithm 1 line 8 as printed: x is the dense form of the row just
+    inserted; state evolves exactly as under eo_step."""
+    d, m, k, lam = 280, 6, 19, 1e-3
+    a = oracle_mod.Oracle(d, m, k, lam)
+    b = oracle_mod.Oracle(d, m, k, lam)
+    rng = np.random.default_rng(8)
+    for t in range(14):
+        g = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+        y = a.step_compressed(g)
+        b.step(g)
+        assert np.array_equal(a.error, b.error) and np.array_equal(a.gram, b.gram)
+        C = _dense_rows(a)
+        assert np.array_equal(C, _dense_rows(b))
+        c_t = C[a.newest_slot]
+        assert _rel(y, _dense_solve(C, m, lam, c_t)) < 1e-9
+        # q is then the Gram row of the newest slot
+        assert np.allclose(a.q, a.gram[a.newest_slot], rtol=1e-13, atol=0)
+        # outside the support of the window rows y is exactly zero / lambda
+        off = ~(C != 0).any(axis=0)
+        assert not y[off].any()
+
+
 @pytest.mark.parametrize("n,m", [(1, 1), (5, 8), (64, 64), (256, 1024)])
 def test_coefficients_match_woodbury(oracle_mod, n, m):
     """coef = (1/lambda) (m*lambda*I + S)^{-1} q  (Woodbury identity applied to
