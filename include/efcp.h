@@ -90,6 +90,39 @@ int efcp_create_fmt(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lamb
  * order on one stream, or on streams ordered by the caller. */
 int efcp_step(efcp_ctx *ctx, const float *grad, float *out, void *stream);
 
+/* Which vector the step preconditions (Algorithm 1, line 8). */
+typedef enum efcp_x_source {
+    EFCP_X_GRAD = 0,        /* x = grad: the dense gradient is preconditioned by the sparse window */
+    EFCP_X_COMPRESSED = 1   /* x = c_t, the compressed accumulator just inserted, as line 8 is
+                               printed (u_t = A(c_t)).  Nothing dense is read for x: x/lambda is
+                               folded into the coefficient of the newest row, and q equals the
+                               Gram row. */
+} efcp_x_source;
+
+/* efcp_step with options.  State update exactly as efcp_step; what is produced differs:
+ *   x_source     efcp_x_source
+ *   out          device, d floats, or NULL: receives u = F^-1 x
+ *   param        device, d floats, 16-byte aligned, or NULL: the model parameters, updated in
+ *                place by Algorithm 1 line 9 with decoupled weight decay,
+ *                    theta_j <- fp32( (1 - lr*weight_decay) * theta_j - lr * u_j ),
+ *                evaluated in fp64 from the fp64 value of u_j inside the LCG kernel, so u is
+ *                never written to memory.  Must not overlap grad.
+ *   lr, weight_decay   finite doubles, used only with param
+ * At most one of out / param may be given (EFCP_EINVAL for both); with neither the LCG pass is
+ * skipped.  efcp_step(ctx, grad, out, stream) is efcp_step_ex(ctx, grad, EFCP_X_GRAD, out, NULL,
+ * 0, 0, stream).  Same asynchrony and ordering rules as efcp_step. */
+int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, float *out, float *param,
+                 double lr, double weight_decay, void *stream);
+
+/* out = F^-1 x for an arbitrary dense x and the window as it stands (eq. (2)): the SP pass,
+ * the coefficient solve and the LCG pass without any insertion.  Error feedback, window, Gram
+ * matrix, factor and step count are untouched; q and coef reported by efcp_get_small are
+ * overwritten.  Before the first step F = lambda*I and out = x/lambda.
+ *   x, out   device, d floats each, 16-byte aligned, not overlapping
+ * Asynchronous on `stream`; ordered after the steps issued so far (also when those used
+ * another stream).  Must not run concurrently with a step of the same context. */
+int efcp_apply(efcp_ctx *ctx, const float *x, float *out, void *stream);
+
 /* Frees the context (and its workspace if the library allocated it) after
  * synchronising the device.  efcp_destroy(NULL) is EFCP_OK. */
 int efcp_destroy(efcp_ctx *ctx);

@@ -55,6 +55,8 @@ def _load():
     lib.eo_step_compressed.argtypes = [vp, vp, vp]
     lib.eo_apply.restype = ctypes.c_int
     lib.eo_apply.argtypes = [vp, vp, vp]
+    lib.eo_param_update.restype = None
+    lib.eo_param_update.argtypes = [vp, vp, i64, dbl, dbl]
     lib.eo_step_count.restype = i64
     lib.eo_step_count.argtypes = [vp]
     lib.eo_filled.restype = i32
@@ -111,6 +113,16 @@ def coefficients(S: np.ndarray, q: np.ndarray, m: int, lam: float) -> np.ndarray
 def bf16_round(a: float) -> float:
     """fp32 -> bfloat16 (nearest even) -> fp32, as the oracle stores values."""
     return float(_load().eo_bf16_round(ctypes.c_float(a)))
+
+
+def param_update(theta: np.ndarray, u: np.ndarray, lr: float, weight_decay: float) -> np.ndarray:
+    """theta <- (1 - lr*weight_decay)*theta - lr*u (Algorithm 1 line 9 with
+    decoupled weight decay); returns the new fp32 parameters."""
+    out = np.array(theta, dtype=np.float32, copy=True)
+    u = np.ascontiguousarray(u, dtype=np.float64)
+    assert out.size == u.size
+    _load().eo_param_update(_ptr(out), _ptr(u), out.size, float(lr), float(weight_decay))
+    return out
 
 
 class Oracle:

@@ -316,3 +316,10 @@ int eo_step_compressed(eo_state *st, const float *g, double *y)
     free(x);
     return rc;
 }
+
+void eo_param_update(float *theta, const double *u, int64_t d, double lr, double weight_decay)
+{
+    const double decay = 1.0 - lr * weight_decay;
+    for (int64_t j = 0; j < d; j++)
+        theta[j] = (float)(decay * (double)theta[j] - lr * u[j]);
+}

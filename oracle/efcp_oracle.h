@@ -68,6 +68,10 @@ int eo_step_compressed(eo_state *st, const float *g, double *y);
  * except for the q / coef views below. */
 int eo_apply(eo_state *st, const float *x, double *y);
 
+/* Algorithm 1 line 9 with decoupled weight decay (the AdamW-style decay the paper's
+ * experiments use): theta_j <- fp32( (1 - lr*weight_decay)*theta_j - lr*u_j ), in fp64. */
+void eo_param_update(float *theta, const double *u, int64_t d, double lr, double weight_decay);
+
 /* Read-only views of the state after the last step. */
 int64_t eo_step_count(const eo_state *st);          /* t */
 int32_t eo_filled(const eo_state *st);              /* n_t = min(t, m) */

@@ -19,11 +19,14 @@ KERNEL_GROUPS = ("ef_hist", "select", "compact", "sp", "coef", "lcg")
 VALUES_FP32, VALUES_BF16 = 0, 1
 
 EXPORTS = (
-    "efcp_workspace_bytes", "efcp_workspace_bytes_fmt", "efcp_create", "efcp_create_fmt", "efcp_step", "efcp_destroy", "efcp_get_row",
+    "efcp_workspace_bytes", "efcp_workspace_bytes_fmt", "efcp_create", "efcp_create_fmt", "efcp_step", "efcp_step_ex", "efcp_apply",
+    "efcp_destroy", "efcp_get_row",
     "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
     "efcp_profile_read", "efcp_last_error",
 )
+
+X_GRAD, X_COMPRESSED = 0, 1
 
 _lib = None
 
@@ -54,6 +57,10 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_create_fmt.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, i32, vp, ctypes.c_size_t]
     lib.efcp_step.restype = ctypes.c_int
     lib.efcp_step.argtypes = [vp, vp, vp, vp]
+    lib.efcp_step_ex.restype = ctypes.c_int
+    lib.efcp_step_ex.argtypes = [vp, vp, i32, vp, vp, dbl, dbl, vp]
+    lib.efcp_apply.restype = ctypes.c_int
+    lib.efcp_apply.argtypes = [vp, vp, vp, vp]
     lib.efcp_destroy.restype = ctypes.c_int
     lib.efcp_destroy.argtypes = [vp]
     lib.efcp_get_row.restype = ctypes.c_int
@@ -119,6 +126,27 @@ class Efcp:
             assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == self.d
         s = stream if stream is not None else torch.cuda.current_stream(grad.device)
         self.step_ptr(grad.data_ptr(), out.data_ptr() if out is not None else None, s.cuda_stream)
+
+    def step_ex(self, grad, x_source: int = X_GRAD, out=None, param=None, lr: float = 0.0,
+                weight_decay: float = 0.0, stream=None) -> None:
+        """efcp_step_ex: x_source X_GRAD / X_COMPRESSED; `out` receives F^-1 x, or
+        `param` is updated in place: theta <- (1 - lr*weight_decay)*theta - lr*F^-1 x."""
+        import torch
+        ok = lambda t: t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == self.d
+        assert ok(grad) and (out is None or ok(out)) and (param is None or ok(param))
+        s = stream if stream is not None else torch.cuda.current_stream(grad.device)
+        self._check(self._lib.efcp_step_ex(self._ctx, grad.data_ptr(), x_source,
+                                           out.data_ptr() if out is not None else None,
+                                           param.data_ptr() if param is not None else None,
+                                           float(lr), float(weight_decay), s.cuda_stream))
+
+    def apply(self, x, out, stream=None) -> None:
+        """efcp_apply: out = F^-1 x on the current window; nothing is inserted."""
+        import torch
+        ok = lambda t: t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == self.d
+        assert ok(x) and ok(out)
+        s = stream if stream is not None else torch.cuda.current_stream(x.device)
+        self._check(self._lib.efcp_apply(self._ctx, x.data_ptr(), out.data_ptr(), s.cuda_stream))
 
     def destroy(self) -> None:
         if getattr(self, "_ctx", None) and self._ctx.value:

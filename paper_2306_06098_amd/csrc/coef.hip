@@ -255,6 +255,38 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t sl
     }
 }
 
+// ------------------------------------------------------------------
+// Coefficients for a vector applied to the window as it stands: with w = W q over all rows,
+// coef = (1/lambda) W^T w.  Block b owns columns [64b, 64b+64); its 16 waves split the rows.
+__global__ __launch_bounds__(1024) void k_apply_bwd(int32_t m, int32_t ldm, double lambda,
+                                                    const double *__restrict__ W,
+                                                    const double2 *__restrict__ sq,
+                                                    const double2 *__restrict__ zw,
+                                                    double *__restrict__ q_out,
+                                                    double *__restrict__ coef_out)
+{
+    __shared__ double s_w[kMaxM];
+    __shared__ double red[16][64];
+    const int tid = threadIdx.x;
+    s_w[tid] = tid < m ? zw[tid].y : 0.0;
+    __syncthreads();
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = blockIdx.x * 64 + lane;
+    const int colc = min(col, m - 1);
+    double ac = 0.0;
+    for (int i = wv; i < m; i += 16) ac = fma(W[(int64_t)i * ldm + colc], s_w[i], ac);
+    red[wv][lane] = ac;
+    __syncthreads();
+    if (wv == 0 && col < m) {
+        double c = 0.0;
+#pragma unroll
+        for (int i = 0; i < 16; i++) c += red[i][lane];
+        coef_out[col] = c / lambda;
+        q_out[col] = sq[col].x;
+    }
+}
+
 hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, p.W);
@@ -268,6 +300,15 @@ hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled,
                        p.zw);
     hipLaunchKernelGGL(k_bwd, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, lambda,
                        p.W, p.sq, p.zw, p.S, p.q, p.coef, p.status);
+    return hipGetLastError();
+}
+
+hipError_t launch_coef_apply(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream)
+{
+    // slot = -1: no row is left out; unfilled rows and columns of W are exact zeros
+    hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, -1, p.W, p.sq, p.zw);
+    hipLaunchKernelGGL(k_apply_bwd, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, lambda, p.W,
+                       p.sq, p.zw, p.q, p.coef);
     return hipGetLastError();
 }
 

@@ -234,12 +234,30 @@ extern "C" int efcp_create_fmt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, 
 
 extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *stream_v)
 {
+    return efcp_step_ex(ctx, grad, EFCP_X_GRAD, outp, nullptr, 0.0, 0.0, stream_v);
+}
+
+static bool overlap(const void *a, const void *b, size_t bytes)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return a && b && x < y + bytes && y < x + bytes;
+}
+
+extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, float *outp, float *param,
+                            double lr, double weight_decay, void *stream_v)
+{
     if (!ctx) return EFCP_EINVAL;
     if (!grad) return fail(ctx, EFCP_EINVAL, "grad is NULL");
-    const uintptr_t ga = reinterpret_cast<uintptr_t>(grad), oa = reinterpret_cast<uintptr_t>(outp);
-    if ((ga & 15) || (oa & 15)) return fail(ctx, EFCP_EINVAL, "grad/out not 16-byte aligned");
+    if (x_source != EFCP_X_GRAD && x_source != EFCP_X_COMPRESSED)
+        return fail(ctx, EFCP_EINVAL, "unknown x_source");
+    if (outp && param) return fail(ctx, EFCP_EINVAL, "give out or param, not both");
+    if (param && !(std::isfinite(lr) && std::isfinite(weight_decay)))
+        return fail(ctx, EFCP_EINVAL, "lr / weight_decay not finite");
+    float *dst = param ? param : outp;
+    if ((reinterpret_cast<uintptr_t>(grad) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15))
+        return fail(ctx, EFCP_EINVAL, "grad/out/param not 16-byte aligned");
     const size_t bytes = (size_t)ctx->g.d * sizeof(float);
-    if (outp && ga < oa + bytes && oa < ga + bytes) return fail(ctx, EFCP_EINVAL, "grad and out overlap");
+    if (overlap(grad, dst, bytes)) return fail(ctx, EFCP_EINVAL, "grad and out/param overlap");
 
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const Geometry &g = ctx->g;
@@ -248,6 +266,7 @@ extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *st
     const int32_t slot = (int32_t)((t - 1) % g.m);
     const int32_t n_filled = (int32_t)(t < g.m ? t : g.m);
     const int32_t evict = t > g.m ? 1 : 0;
+    const bool x_is_row = x_source == EFCP_X_COMPRESSED;
 
     hipEvent_t *ev = nullptr;
     if (ctx->prof_on) ev = &ctx->ev[(size_t)(ctx->prof_count % kProfSteps) * kProfEvents];
@@ -267,18 +286,53 @@ extern "C" int efcp_step(efcp_ctx *ctx, const float *grad, float *outp, void *st
     mark(2);
     if (rc == hipSuccess) rc = launch_compact(g, p, slot, stream);
     mark(3);
-    if (rc == hipSuccess) rc = launch_sp(g, p, grad, n_filled, slot, stream);
+    if (rc == hipSuccess) rc = launch_sp(g, p, grad, n_filled, slot, x_is_row ? 1 : 0, stream);
     mark(4);
     if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
     if (evict && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);      // join
     if (rc == hipSuccess) rc = launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
     mark(5);
-    if (rc == hipSuccess && outp) rc = launch_lcg(g, p, grad, outp, n_filled, ctx->lambda, stream);
+    if (rc == hipSuccess && dst) {
+        LcgMode md;
+        md.x_row = x_is_row ? slot : -1;
+        md.update = param != nullptr;
+        md.lr = lr;
+        md.decay = 1.0 - lr * weight_decay;
+        rc = launch_lcg(g, p, grad, dst, n_filled, ctx->lambda, md, stream);
+    }
     mark(6);
 
     ctx->t = t;
     ctx->last_stream = stream;
     if (ctx->prof_on) ctx->prof_count++;
+    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
+    return EFCP_OK;
+}
+
+extern "C" int efcp_apply(efcp_ctx *ctx, const float *x, float *outp, void *stream_v)
+{
+    if (!ctx) return EFCP_EINVAL;
+    if (!x || !outp) return fail(ctx, EFCP_EINVAL, "x or out is NULL");
+    if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(outp) & 15))
+        return fail(ctx, EFCP_EINVAL, "x/out not 16-byte aligned");
+    if (overlap(x, outp, (size_t)ctx->g.d * sizeof(float))) return fail(ctx, EFCP_EINVAL, "x and out overlap");
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const Geometry &g = ctx->g;
+    const DevicePtrs &p = ctx->p;
+    const int32_t n_filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
+    hipError_t rc = hipSuccess;
+    if (ctx->last_stream != stream && ctx->t > 0) {
+        // the window was written on another stream: order this call after it
+        rc = hipEventRecord(ctx->ev_fork, ctx->last_stream);
+        if (rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_fork, 0);
+    }
+    if (n_filled > 0) {
+        if (rc == hipSuccess) rc = launch_sp(g, p, x, n_filled, 0, 2, stream);
+        if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
+        if (rc == hipSuccess) rc = launch_coef_apply(g, p, ctx->lambda, stream);
+    }
+    if (rc == hipSuccess) rc = launch_lcg(g, p, x, outp, n_filled, ctx->lambda, LcgMode{}, stream);
+    ctx->last_stream = stream;
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
     return EFCP_OK;
 }

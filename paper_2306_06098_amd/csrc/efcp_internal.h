@@ -128,14 +128,22 @@ struct DevicePtrs {
 hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
+// x_source: 0 = dense x next to the newest row, 1 = the newest row is x, 2 = dense x only
 hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
-                     int32_t slot, hipStream_t stream);
+                     int32_t slot, int32_t x_source, hipStream_t stream);
 hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
 hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
                        int32_t evict, double lambda, hipStream_t stream);
+// Coefficients for an arbitrary x on the window as it stands (nothing is inserted).
+hipError_t launch_coef_apply(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream);
+struct LcgMode {
+    int32_t x_row = -1;      // >= 0: x is this window row (the dense pointer is not read)
+    bool update = false;     // out holds parameters: theta <- decay*theta - lr*(F^-1 x)
+    double decay = 1.0, lr = 0.0;
+};
 hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
-                      int32_t n_filled, double lambda, hipStream_t stream);
+                      int32_t n_filled, double lambda, const LcgMode &md, hipStream_t stream);
 hipError_t configure_sp(const Geometry &g);
 hipError_t configure_lcg(const Geometry &g);
 

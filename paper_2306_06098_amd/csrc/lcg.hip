@@ -55,7 +55,14 @@ __device__ __forceinline__ void lcg_scatter(const int4 &iv, const int4 &vv, int3
 // contiguous slice range [x*per, (x+1)*per) and its workgroups work on neighbouring slices at any
 // moment (same mapping as the SP pass).  While a slice's rows stream, the x values of its epilogue and
 // the row offsets of the workgroup's next slice are already on their way in registers.
-template <int FMT>
+//
+// XDENSE = false: x is window row `x_row` itself (x = c_t, Algorithm 1 line 8 as printed).  Then
+// x/lambda is one more multiple of a stored row, out = -sum_r (coef_r - [r = x_row]/lambda) c_r,
+// and no dense x is read at all.
+// UPDATE = true: `out` holds the parameters and receives the optimizer step with decoupled
+// weight decay, theta <- decay*theta - lr*(x/lambda - sum) (Algorithm 1 line 9), instead of
+// the preconditioned vector.
+template <int FMT, bool XDENSE, bool UPDATE>
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
                                               int64_t d, int32_t m, int32_t n_filled, int64_t row_stride,
                                               int32_t slice_log2, int32_t nsl, int32_t cpx,
@@ -64,7 +71,8 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
                                               const int32_t *__restrict__ offT,
                                               const double *__restrict__ coef,
                                               const uint32_t *__restrict__ rowmax,
-                                              uint32_t *__restrict__ status, double inv_lambda)
+                                              uint32_t *__restrict__ status, double inv_lambda,
+                                              int32_t x_row, double decay, double lr)
 {
     using idx_t = typename Fmt<FMT>::idx_t;
     using val_t = typename Fmt<FMT>::val_t;
@@ -91,7 +99,8 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     {
         offs[tid] = offT[(int64_t)s * m + trow];
         offs[kMaxM + tid] = offT[(int64_t)(s + 1) * m + trow];
-        const double c = tid < n_filled ? coef[tid] : 0.0;
+        double c = tid < n_filled ? coef[tid] : 0.0;
+        if (!XDENSE && tid == x_row) c -= inv_lambda;
         cf[tid] = c;
         // |coef_r| * (upper bound of the largest |value| of row r)
         cabs = fabs(c) * (double)__uint_as_float(tid < n_filled ? rowmax[tid] : 0u);
@@ -175,7 +184,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         // on their way while the rows stream: x of this slice (for the epilogue) and the row
         // offsets of this workgroup's next slice
         float4 xr[4];
-        if (FULL) {
+        if (FULL && XDENSE) {
 #pragma unroll
             for (int u = 0; u < 4; u++)
                 xr[u] = load_stream_f4(x + base64 + tid * 4 + u * 4096);
@@ -202,6 +211,12 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
             }
             if (!more) break;
         }
+        float4 th[4];               // parameters of this slice: requested before the barrier
+        if (FULL && UPDATE) {
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                th[u] = load_stream_f4(out + base64 + tid * 4 + u * 4096);
+        }
         __syncthreads();            // all rows of this slice are in the accumulators; offn visible
 
         off0 = offn;
@@ -212,25 +227,31 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         first(ba);
         load(ba);
 
-        // out = x/lambda - sum; accumulators back to zero for the next slice
+        // out = x/lambda - sum (or the parameter update); accumulators back to zero for the next slice
+        auto result = [&](float xj, float thj, unsigned long long a) {
+            const double sum = (double)(long long)a * unit;
+            const double y = XDENSE ? (double)xj * inv_lambda - sum : -sum;
+            return UPDATE ? (float)((double)thj * decay - lr * y) : (float)y;
+        };
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             const int32_t i = tid * 4 + u * 4096;
             float o[4];
             if (FULL) {
-                const float xv[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
+                const float xv[4] = {XDENSE ? xr[u].x : 0.f, XDENSE ? xr[u].y : 0.f, XDENSE ? xr[u].z : 0.f,
+                                     XDENSE ? xr[u].w : 0.f};
+                const float tv[4] = {UPDATE ? th[u].x : 0.f, UPDATE ? th[u].y : 0.f, UPDATE ? th[u].z : 0.f,
+                                     UPDATE ? th[u].w : 0.f};
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const double sum = (double)(long long)acc[i + q] * unit;
-                    o[q] = (float)((double)xv[q] * inv_lambda - sum);
-                }
+                for (int q = 0; q < 4; q++) o[q] = result(xv[q], tv[q], acc[i + q]);
                 store_stream_f4(out + base64 + i, make_float4(o[0], o[1], o[2], o[3]));
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     if (i + q < len) {
-                        const double sum = (double)(long long)acc[i + q] * unit;
-                        out[base64 + i + q] = (float)((double)x[base64 + i + q] * inv_lambda - sum);
+                        const float xj = XDENSE ? x[base64 + i + q] : 0.f;
+                        const float tj = UPDATE ? out[base64 + i + q] : 0.f;
+                        out[base64 + i + q] = result(xj, tj, acc[i + q]);
                     }
                 }
             }
@@ -246,30 +267,79 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     if (s < s_end) do_slice(std::false_type{});                   // uniform
 }
 
-hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
-                      int32_t n_filled, double lambda, hipStream_t stream)
+// out = x/lambda (empty window: F = lambda*I), or the parameter update with that vector.
+__global__ __launch_bounds__(256) void k_scale(const float *__restrict__ x, float *__restrict__ out, int64_t d,
+                                               double inv_lambda, int32_t update, double decay, double lr)
 {
-    if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL(k_lcg<kFmtBf16>, dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m,
-                           n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                           static_cast<const uint16_t *>(p.ring_idx),
-                           static_cast<const uint16_t *>(p.ring_val), p.offT, p.coef, p.rowmax, p.status,
-                           1.0 / lambda);
-    else
-        hipLaunchKernelGGL(k_lcg<kFmtF32>, dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out, g.d, g.m,
-                           n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                           static_cast<const int32_t *>(p.ring_idx), static_cast<const float *>(p.ring_val),
-                           p.offT, p.coef, p.rowmax, p.status, 1.0 / lambda);
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d) return;
+    const double y = (double)x[j] * inv_lambda;
+    out[j] = update ? (float)((double)out[j] * decay - lr * y) : (float)y;
+}
+
+namespace {
+
+template <int FMT, bool XDENSE, bool UPDATE>
+void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float *out, int32_t n_filled,
+                   double lambda, const LcgMode &md, hipStream_t stream)
+{
+    using idx_t = typename Fmt<FMT>::idx_t;
+    using val_t = typename Fmt<FMT>::val_t;
+    hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
+                       g.d, g.m, n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                       static_cast<const idx_t *>(p.ring_idx), static_cast<const val_t *>(p.ring_val), p.offT,
+                       p.coef, p.rowmax, p.status, 1.0 / lambda, md.x_row, md.decay, md.lr);
+}
+
+template <int FMT>
+void launch_lcg_fmt(const Geometry &g, const DevicePtrs &p, const float *x, float *out, int32_t n_filled,
+                    double lambda, const LcgMode &md, hipStream_t stream)
+{
+    const bool dense = md.x_row < 0;
+    if (dense && !md.update) launch_lcg_as<FMT, true, false>(g, p, x, out, n_filled, lambda, md, stream);
+    else if (dense) launch_lcg_as<FMT, true, true>(g, p, x, out, n_filled, lambda, md, stream);
+    else if (!md.update) launch_lcg_as<FMT, false, false>(g, p, x, out, n_filled, lambda, md, stream);
+    else launch_lcg_as<FMT, false, true>(g, p, x, out, n_filled, lambda, md, stream);
+}
+
+template <int FMT, bool XDENSE, bool UPDATE>
+hipError_t set_lds_lcg(const Geometry &g)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<FMT, XDENSE, UPDATE>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+}
+
+template <int FMT>
+hipError_t set_lds_lcg_fmt(const Geometry &g)
+{
+    hipError_t rc = set_lds_lcg<FMT, true, false>(g);
+    if (rc == hipSuccess) rc = set_lds_lcg<FMT, true, true>(g);
+    if (rc == hipSuccess) rc = set_lds_lcg<FMT, false, false>(g);
+    if (rc == hipSuccess) rc = set_lds_lcg<FMT, false, true>(g);
+    return rc;
+}
+
+}  // namespace
+
+// `out` receives x/lambda - sum_r coef_r c_r, or (md.update) is the parameter vector updated in
+// place.  md.x_row >= 0: x is that window row and the pointer x is not read.
+hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
+                      int32_t n_filled, double lambda, const LcgMode &md, hipStream_t stream)
+{
+    if (n_filled == 0) {                      // only reachable with a dense x
+        hipLaunchKernelGGL(k_scale, dim3((unsigned)((g.d + 255) / 256)), dim3(256), 0, stream, x, out, g.d,
+                           1.0 / lambda, md.update ? 1 : 0, md.decay, md.lr);
+        return hipGetLastError();
+    }
+    if (g.fmt == kFmtBf16) launch_lcg_fmt<kFmtBf16>(g, p, x, out, n_filled, lambda, md, stream);
+    else launch_lcg_fmt<kFmtF32>(g, p, x, out, n_filled, lambda, md, stream);
     return hipGetLastError();
 }
 
 hipError_t configure_lcg(const Geometry &g)
 {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<kFmtF32>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
-    if (rc == hipSuccess)
-        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<kFmtBf16>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    hipError_t rc = set_lds_lcg_fmt<kFmtF32>(g);
+    if (rc == hipSuccess) rc = set_lds_lcg_fmt<kFmtBf16>(g);
     return rc;
 }
 

@@ -53,6 +53,13 @@ __device__ __forceinline__ void sp_accumulate(const int4 &iv, const int4 &vv, in
 
 constexpr int kMaxSlicesPerWg = 512;     // ceil(2^31 / 16384 / 8 / 32)
 
+// What the staged pair (x_j, c_new_j) holds:
+//   kXDense    x from memory, newest row scattered next to it      (step with x = gradient)
+//   kXNewest   x IS the newest row: nothing dense is read, the scatter fills both halves,
+//              and q equals the Gram row                          (step with x = c_t)
+//   kXOnly     x from memory, no newest row: only q is meaningful  (apply on a fixed window)
+enum : int { kXDense = 0, kXNewest = 1, kXOnly = 2 };
+
 // Workgroup b sits on XCD b%8 (workgroups are dealt to the 8 XCDs round-robin)
 // and is the (b/8)-th of `cpx` workgroups there.  XCD x owns the contiguous
 // slice range [x*per, (x+1)*per); at any time its workgroups work on
@@ -64,7 +71,7 @@ constexpr int kMaxSlicesPerWg = 512;     // ceil(2^31 / 16384 / 8 / 32)
 // newest row's entries that fall into it.  The switch between slices is then
 // three barriers and LDS traffic, with the first batch of ring loads of the
 // new slice issued before the last two.
-template <int FMT>
+template <int FMT, int XM>
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              int32_t n_filled, int32_t slot, int64_t row_stride,
                                              int64_t k, int32_t slice_log2, int32_t nsl, int32_t cpx,
@@ -102,24 +109,29 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         if (tid < m) partial[(int64_t)blockIdx.x * m + tid] = make_double2(0.0, 0.0);
         return;
     }
-    for (int32_t i = tid; s_first + i * cpx < s_end && i < kMaxSlicesPerWg; i += 1024) {
-        const int32_t si = s_first + i * cpx;
-        np0[i] = offT[(int64_t)si * m + slot];
-        np1[i] = offT[(int64_t)(si + 1) * m + slot];
+    if (XM != kXOnly) {
+        for (int32_t i = tid; s_first + i * cpx < s_end && i < kMaxSlicesPerWg; i += 1024) {
+            const int32_t si = s_first + i * cpx;
+            np0[i] = offT[(int64_t)si * m + slot];
+            np1[i] = offT[(int64_t)(si + 1) * m + slot];
+        }
     }
 
     // state carried from one slice to the next (prefetched while the previous one streams)
     float4 xr[4];
     int32_t o0, o1;
-    idx_t di;
-    val_t dv;
+    idx_t di = 0;
+    val_t dv = 0;
     int32_t it = 0;                           // index of the current slice in this workgroup's list
     int32_t s = s_first;
 
     auto prefetch = [&](int32_t sp, int32_t ip, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         const int64_t b64 = (int64_t)sp << slice_log2;
-        if (FULL) {
+        if (XM == kXNewest) {
+#pragma unroll
+            for (int u = 0; u < 4; u++) xr[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else if (FULL) {
 #pragma unroll
             for (int u = 0; u < 4; u++) xr[u] = load_stream_f4(x + b64 + tid * 4 + u * 4096);
         } else {
@@ -135,9 +147,11 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         }
         o0 = offT[(int64_t)sp * m + trow];
         o1 = offT[(int64_t)(sp + 1) * m + trow];
-        const int32_t p = min(np0[ip] + tid, klast);     // clamped: always a valid entry
-        di = nidx[p];
-        dv = nval[p];
+        if (XM != kXOnly) {
+            const int32_t p = min(np0[ip] + tid, klast);     // clamped: always a valid entry
+            di = nidx[p];
+            dv = nval[p];
+        }
     };
 
     const int32_t n_full = (int32_t)(d >> slice_log2);           // slices with all coordinates
@@ -189,13 +203,20 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         }
         off0[tid] = o0;
         off1[tid] = o1;
-        const int32_t q0 = np0[it], q1 = np1[it];
+        const int32_t q0 = XM != kXOnly ? np0[it] : 0, q1 = XM != kXOnly ? np1[it] : 0;
         __syncthreads();            // x and offsets of slice s in LDS
         first(ba);
         load(ba);                   // first ring batch in flight during the scatter below
-        if (q0 + tid < q1) xc[stored_pos(di, base, mask)].y = stored_val(dv);   // newest row next to x
-        for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)       // runs longer than 1024 entries
-            xc[stored_pos(nidx[p], base, mask)].y = stored_val(nval[p]);
+        if (XM != kXOnly) {
+            auto put = [&](idx_t i, val_t v) {                     // newest row next to x (or as x)
+                const float f = stored_val(v);
+                if (XM == kXNewest) xc[stored_pos(i, base, mask)] = make_float2(f, f);
+                else xc[stored_pos(i, base, mask)].y = f;
+            };
+            if (q0 + tid < q1) put(di, dv);
+            for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)   // runs longer than 1024 entries
+                put(nidx[p], nval[p]);
+        }
         __syncthreads();
 
         // ---- prefetch for the next slice of this workgroup ----
@@ -270,19 +291,45 @@ __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ 
     }
 }
 
-hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
-                     int32_t slot, hipStream_t stream)
+namespace {
+
+template <int FMT, int XM>
+void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled, int32_t slot,
+                  hipStream_t stream)
 {
-    if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL(k_sp<kFmtBf16>, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m,
-                           n_filled, slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                           static_cast<const uint16_t *>(p.ring_idx),
-                           static_cast<const uint16_t *>(p.ring_val), p.offT, p.partial);
-    else
-        hipLaunchKernelGGL(k_sp<kFmtF32>, dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m,
-                           n_filled, slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                           static_cast<const int32_t *>(p.ring_idx), static_cast<const float *>(p.ring_val),
-                           p.offT, p.partial);
+    using idx_t = typename Fmt<FMT>::idx_t;
+    using val_t = typename Fmt<FMT>::val_t;
+    hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled,
+                       slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                       static_cast<const idx_t *>(p.ring_idx), static_cast<const val_t *>(p.ring_val), p.offT,
+                       p.partial);
+}
+
+template <int FMT>
+void launch_sp_fmt(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled, int32_t slot,
+                   int32_t xmode, hipStream_t stream)
+{
+    if (xmode == kXNewest) launch_sp_as<FMT, kXNewest>(g, p, x, n_filled, slot, stream);
+    else if (xmode == kXOnly) launch_sp_as<FMT, kXOnly>(g, p, x, n_filled, slot, stream);
+    else launch_sp_as<FMT, kXDense>(g, p, x, n_filled, slot, stream);
+}
+
+template <int FMT, int XM>
+hipError_t set_lds_sp(const Geometry &g)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<FMT, XM>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+}
+
+}  // namespace
+
+// x_source: 0 = dense x plus the newest row (slot), 1 = the newest row is x (x unused),
+// 2 = dense x only (slot unused; the Gram half of the result is meaningless).
+hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
+                     int32_t slot, int32_t x_source, hipStream_t stream)
+{
+    if (g.fmt == kFmtBf16) launch_sp_fmt<kFmtBf16>(g, p, x, n_filled, slot, x_source, stream);
+    else launch_sp_fmt<kFmtF32>(g, p, x, n_filled, slot, x_source, stream);
     return hipGetLastError();
 }
 
@@ -295,11 +342,12 @@ hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_fi
 
 hipError_t configure_sp(const Geometry &g)
 {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<kFmtF32>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
-    if (rc == hipSuccess)
-        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<kFmtBf16>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    hipError_t rc = set_lds_sp<kFmtF32, kXDense>(g);
+    if (rc == hipSuccess) rc = set_lds_sp<kFmtF32, kXNewest>(g);
+    if (rc == hipSuccess) rc = set_lds_sp<kFmtF32, kXOnly>(g);
+    if (rc == hipSuccess) rc = set_lds_sp<kFmtBf16, kXDense>(g);
+    if (rc == hipSuccess) rc = set_lds_sp<kFmtBf16, kXNewest>(g);
+    if (rc == hipSuccess) rc = set_lds_sp<kFmtBf16, kXOnly>(g);
     return rc;
 }
 

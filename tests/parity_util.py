@@ -26,26 +26,42 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 
 
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
-               check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False):
+               check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False,
+               compressed=False, update=None, apply_every=0):
     """grads: iterable of float32 numpy arrays.  bf16: the bfloat16 window
-    format on both sides.  Returns dict of worst errors."""
+    format on both sides.  compressed: the step preconditions c_t instead of
+    the gradient.  update=(lr, weight_decay): the step updates a parameter
+    vector in place instead of writing F^-1 x; the bar is then on the update,
+    |theta_gpu - theta_ref| relative to |lr * F^-1 x|, with both sides starting
+    each step from the same fp32 parameters.  apply_every=n: after every n-th
+    step a seeded random x is applied to the window as it stands on both
+    sides (no insertion).  Returns dict of worst errors."""
     dev = torch.device("cuda:0")
     o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16)
     g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
     e_prev = np.zeros(d, np.float32)
     grad_d = torch.empty(d, dtype=torch.float32, device=dev)
     out_d = torch.empty(d, dtype=torch.float32, device=dev)
-    worst = dict(out=0.0, S=0.0, q=0.0, coef=0.0)
+    worst = dict(out=0.0, S=0.0, q=0.0, coef=0.0, apply=0.0)
+    rng = np.random.default_rng(d + m)
+    theta = (rng.standard_normal(d) * 0.05).astype(np.float32) if update else None
+    x_source = binding.X_COMPRESSED if compressed else binding.X_GRAD
     t = 0
     try:
         for g in grads:
             t += 1
             g = np.ascontiguousarray(g, dtype=np.float32)
             a = e_prev + g                      # the accumulator, one fp32 rounding per element
-            y = o.step(g)
+            y = o.step_compressed(g) if compressed else o.step(g)
             e_prev = o.error.copy()
             grad_d.copy_(torch.from_numpy(g))
-            g_gpu.step(grad_d, out_d)
+            if update:
+                out_d.copy_(torch.from_numpy(theta))
+                g_gpu.step_ex(grad_d, x_source, param=out_d, lr=update[0], weight_decay=update[1])
+            elif compressed:
+                g_gpu.step_ex(grad_d, x_source, out=out_d)
+            else:
+                g_gpu.step(grad_d, out_d)
             torch.cuda.synchronize()
             slot = (t - 1) % m
             idx, val = g_gpu.get_row(slot)
@@ -57,7 +73,13 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
                     f"step {t}: error feedback differs"
             out = out_d.cpu().numpy()
             assert np.isfinite(out).all(), f"step {t}: non-finite output"
-            err = rel_l2(out, y)
+            if update:
+                theta_ref = oracle_mod.param_update(theta, y, update[0], update[1])
+                moved = np.linalg.norm(update[0] * y)
+                err = float(np.linalg.norm(out.astype(np.float64) - theta_ref) / moved) if moved > 0 else 0.0
+                theta = theta_ref
+            else:
+                err = rel_l2(out, y)
             worst["out"] = max(worst["out"], err)
             if out_tol is not None:
                 assert err <= out_tol, f"step {t}: rel L2 of F^-1 x = {err:.3e}"
@@ -75,6 +97,17 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
                 assert sq <= 1e-10, f"step {t}: q off by {sq:.3e}"
                 sel_key = bits(a[oi]) & np.uint32(0x7FFFFFFF)
                 assert sm["tau"] == int(sel_key.min()), f"step {t}: threshold key differs"
+            if apply_every and t % apply_every == 0:
+                x = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+                ya = o.apply(x)
+                grad_d.copy_(torch.from_numpy(x))
+                g_gpu.apply(grad_d, out_d)
+                torch.cuda.synchronize()
+                ea = rel_l2(out_d.cpu().numpy(), ya)
+                worst["apply"] = max(worst["apply"], ea)
+                assert ea <= OUT_TOL, f"step {t}: rel L2 of applied F^-1 x = {ea:.3e}"
+                assert np.array_equal(bits(g_gpu.get_error()), bits(o.error)), f"step {t}: apply changed e"
+                assert g_gpu.get_small()["step"] == t
             if verbose:
                 print(f"  step {t}: out {err:.2e}", flush=True)
     finally:

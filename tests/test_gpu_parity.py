@@ -322,3 +322,125 @@ def test_argument_checks(env):
     with pytest.raises(binding.EfcpError):
         ctx.get_row(0)                                              # not filled yet
     ctx.destroy()
+
+
+# ---------------------------------------------------------------------------
+# efcp_step_ex / efcp_apply: other vectors through the same window
+
+def _edge_grads(d, T, seed):
+    rng = np.random.default_rng(seed)
+    scale = np.exp(rng.standard_normal(d)).astype(np.float32)
+    z = np.zeros(d, np.float32)
+    for _ in range(T):
+        z = (0.7 * z + rng.standard_normal(d)).astype(np.float32)
+        yield scale * z
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_compressed_accumulator_is_preconditioned(env, bf16):
+    """x = c_t (Algorithm 1 line 8 as printed): F^-1 c_t against the oracle on
+    the tiny workload, state bit-exact as in the x = g mode."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, wl.lam, _stream(wl, 80), bf16=bf16,
+                   compressed=True)
+    print("tiny compressed", bf16, w)
+
+
+@pytest.mark.parametrize("d,m,k,lam,T", [(20_001, 8, 201, 1e-3, 30), (4_099, 3, 4_099, 1e-2, 9),
+                                          (16_384 * 3, 7, 500, 1e-4, 16), (100_003, 1, 1000, 1e-3, 5),
+                                          (3, 2, 2, 1e-1, 6)])
+def test_compressed_mode_shapes(env, d, m, k, lam, T):
+    torch, oracle_mod, binding = env
+    w = run_parity(torch, oracle_mod, binding, d, m, k, lam, _edge_grads(d, T, d + m), compressed=True)
+    print((d, m, k), w)
+
+
+@pytest.mark.parametrize("compressed", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_fused_parameter_update(env, bf16, compressed):
+    """theta <- (1 - lr*wd)*theta - lr*F^-1 x inside the LCG kernel, against the
+    oracle's fp64 update of the same fp32 parameters."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, wl.lam, _stream(wl, 60), bf16=bf16,
+                   compressed=compressed, update=(3e-6, 0.01))
+    print("tiny update", bf16, compressed, w)
+    # ragged last slice and a window that evicts
+    d, m, k = 50_001, 4, 300
+    w = run_parity(torch, oracle_mod, binding, d, m, k, 1e-3, _edge_grads(d, 10, 5), bf16=bf16,
+                   compressed=compressed, update=(1e-4, 0.1))
+    print("ragged update", bf16, compressed, w)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_apply_on_fixed_window(env, bf16):
+    """efcp_apply between steps: arbitrary dense x, partly filled and wrapped
+    windows, nothing in the state moves (later steps still match bit for bit)."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, wl.lam, _stream(wl, 70), bf16=bf16,
+                   apply_every=3)
+    print("tiny apply", bf16, w)
+    assert w["apply"] > 0.0
+    d, m, k = 40_003, 5, 77
+    w = run_parity(torch, oracle_mod, binding, d, m, k, 1e-2, _edge_grads(d, 12, 9), bf16=bf16, apply_every=1)
+    print("ragged apply", bf16, w)
+
+
+def test_apply_before_first_step_and_repeats(env):
+    """Empty window: F = lambda*I.  Two applies of the same x give the same bits,
+    and apply(g) right after step(g) repeats the step's output bit for bit."""
+    torch, oracle_mod, binding = env
+    d, m, k, lam = 30_011, 6, 150, 1e-3
+    dev = torch.device("cuda:0")
+    o = oracle_mod.Oracle(d, m, k, lam)
+    g_gpu = binding.Efcp(d, m, k, lam)
+    try:
+        rng = np.random.default_rng(3)
+        x = rng.standard_normal(d).astype(np.float32)
+        x_d = torch.from_numpy(x).to(dev)
+        out_d = torch.empty_like(x_d)
+        g_gpu.apply(x_d, out_d)
+        torch.cuda.synchronize()
+        assert rel_l2(out_d.cpu().numpy(), o.apply(x)) < 1e-6
+        step_out = torch.empty_like(x_d)
+        for t in range(9):
+            g = rng.standard_normal(d).astype(np.float32)
+            g_d = torch.from_numpy(g).to(dev)
+            o.step(g)
+            g_gpu.step(g_d, step_out)
+            g_gpu.apply(g_d, out_d)
+            again = torch.empty_like(out_d)
+            g_gpu.apply(g_d, again)
+            torch.cuda.synchronize()
+            assert torch.equal(out_d, again)
+            assert rel_l2(out_d.cpu().numpy(), o.apply(g)) <= 1e-3
+            # same window, same x: q has a different summation order than in the step, so
+            # the outputs agree to rounding, not necessarily bit for bit
+            assert rel_l2(out_d.cpu().numpy(), step_out.cpu().numpy().astype(np.float64)) < 1e-5
+    finally:
+        g_gpu.destroy()
+        o.close()
+
+
+def test_step_ex_argument_checks(env):
+    torch, oracle_mod, binding = env
+    d = 5000
+    dev = torch.device("cuda:0")
+    g_gpu = binding.Efcp(d, 4, 50, 1e-2)
+    try:
+        g = torch.zeros(d, device=dev)
+        a = torch.zeros(d, device=dev)
+        b = torch.zeros(d, device=dev)
+        with pytest.raises(binding.EfcpError):
+            g_gpu.step_ex(g, binding.X_GRAD, out=a, param=b, lr=0.1)       # both destinations
+        with pytest.raises(binding.EfcpError):
+            g_gpu.step_ex(g, 7, out=a)                                      # unknown source
+        with pytest.raises(binding.EfcpError):
+            g_gpu.step_ex(g, binding.X_GRAD, param=a, lr=float("nan"))
+        with pytest.raises(binding.EfcpError):
+            g_gpu.apply(g, g)                                               # overlap
+        assert g_gpu.get_small()["step"] == 0                               # nothing ran
+    finally:
+        g_gpu.destroy()

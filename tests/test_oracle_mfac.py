@@ -122,6 +122,22 @@ def test_step_compressed_preconditions_c_t(oracle_mod):
         assert not y[off].any()
 
 
+def test_param_update_closed_forms(oracle_mod):
+    """Integers and powers of two make every operation exact."""
+    theta = np.array([4.0, -8.0, 0.5, 0.0, 1024.0], np.float32)
+    u = np.array([2.0, 4.0, -1.0, 8.0, 0.0])
+    assert np.array_equal(oracle_mod.param_update(theta, u, 1.0, 0.0), theta - u)          # plain SGD step
+    assert np.array_equal(oracle_mod.param_update(theta, u, 0.5, 0.0), theta - 0.5 * u)
+    assert np.array_equal(oracle_mod.param_update(theta, u, 0.5, 0.5), 0.75 * theta - 0.5 * u)
+    assert np.array_equal(oracle_mod.param_update(theta, 0 * u, 0.25, 2.0), 0.5 * theta)   # decay only
+    assert np.array_equal(oracle_mod.param_update(theta, u, 0.0, 3.0), theta)             # lr = 0: no change
+    assert np.array_equal(theta, np.array([4.0, -8.0, 0.5, 0.0, 1024.0], np.float32))     # input untouched
+    # with an empty window u = g/lambda: the update is SGD with step lr/lambda
+    o = oracle_mod.Oracle(5, 2, 1, 0.25)
+    g = np.array([1.0, 2.0, -3.0, 0.5, 0.0], np.float32)
+    assert np.array_equal(oracle_mod.param_update(theta, o.apply(g), 0.125, 0.0), theta - 0.5 * g)
+
+
 @pytest.mark.parametrize("n,m", [(1, 1), (5, 8), (64, 64), (256, 1024)])
 def test_coefficients_match_woodbury(oracle_mod, n, m):
     """coef = (1/lambda) (m*lambda*I + S)^{-1} q  (Woodbury identity applied to
