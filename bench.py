@@ -36,15 +36,21 @@ MEASURED_TRAFFIC = {("bert_base", "lcg"): 10.40e9, ("bert_base", "sp"): 9.94e9}
 METRIC = "Sparse M-FAC EFCP steps/s + achieved HBM GB/s (d=110M, m=1024, 1% density)"
 
 
-def step_bytes(d, k, n, entry=8):
+def step_bytes(d, k, n, entry=8, mode="grad"):
     """Algorithmic bytes of one step with n filled rows; entry = bytes per window
-    entry (8: int32 index + fp32 value, 4: 16-bit in-slice index + bf16 value)."""
-    return {
+    entry (8: int32 index + fp32 value, 4: 16-bit in-slice index + bf16 value).
+    mode: "grad" (x = g, F^-1 g written: the benchmark's definition), "compressed"
+    (x = c_t: no dense x is read), "update" / "compressed-update" (the parameters
+    are read and written instead of F^-1 x being written)."""
+    x_read = 0 if mode.startswith("compressed") else 4 * d
+    dst = 8 * d if mode.endswith("update") else 4 * d
+    by = {
         "ef": 12 * d + entry * k,              # read g, read e, write e; write the new row
-        "sp": entry * n * k + 4 * d,           # window once + x
-        "lcg": entry * n * k + 8 * d,          # window once + x + out
-        "total": 2 * entry * n * k + 24 * d + entry * k,
+        "sp": entry * n * k + x_read,          # window once + x
+        "lcg": entry * n * k + x_read + dst,   # window once + x + out (or theta in and out)
     }
+    by["total"] = by["ef"] + by["sp"] + by["lcg"]
+    return by
 
 
 def cpu_baseline(wl, bf16=False, seconds_budget=30.0):
@@ -87,6 +93,9 @@ def main():
     ap.add_argument("--values", choices=["fp32", "bf16"], default="fp32",
                     help="window format: fp32 = the benchmark's definition (8-byte entries); "
                          "bf16 = bfloat16 values + 16-bit in-slice indices (4-byte entries)")
+    ap.add_argument("--mode", choices=["grad", "compressed", "update", "compressed-update"], default="grad",
+                    help="grad = the benchmark's definition (F^-1 g written); compressed: x = c_t; "
+                         "update: parameters updated in place by the LCG kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -107,11 +116,22 @@ def main():
 
     fill = wl.m if args.fill < 0 else args.fill
     t_fill = time.perf_counter()
+    xsrc = binding.X_COMPRESSED if args.mode.startswith("compressed") else binding.X_GRAD
+    if args.mode.endswith("update"):
+        out.normal_(0.0, 0.02)               # stands for the parameters
+        # lr small enough that 50 updates of synthetic gradients keep the parameters finite
+        dest = dict(param=out, lr=1e-12, weight_decay=0.01)
+    else:
+        dest = dict(out=out)
+
     for i in range(fill + args.warmup):
         g = pool[i % len(pool)]
         stream.next_into(g)
         # filling the window needs no output: skip the LCG pass until the warm-up steps
-        ctx.step(g, out if i >= fill else None)
+        if i >= fill:
+            ctx.step_ex(g, xsrc, **dest)
+        else:
+            ctx.step(g, None)
         if (i + 1) % 256 == 0:
             torch.cuda.synchronize()
             print(f"[bench] filled {i + 1} steps, {time.perf_counter() - t_fill:.1f} s",
@@ -123,8 +143,12 @@ def main():
     ctx.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        ctx.step(pool[i % len(pool)], out)
+    if args.mode == "grad":
+        for i in range(args.steps):
+            ctx.step(pool[i % len(pool)], out)
+    else:
+        for i in range(args.steps):
+            ctx.step_ex(pool[i % len(pool)], xsrc, **dest)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_groups, covered = ctx.profile_read()
@@ -133,7 +157,7 @@ def main():
     assert torch.isfinite(out).all().item()
 
     n = min(sm["step"], wl.m)
-    by = step_bytes(wl.d, wl.k, n, 4 if bf16 else 8)
+    by = step_bytes(wl.d, wl.k, n, 4 if bf16 else 8, args.mode)
     ms_step = (t1 - t0) * 1e3 / args.steps
     per_launch = {kname: ms_groups[kname] / max(covered, 1) for kname in ms_groups}
     dom = "lcg" if per_launch["lcg"] >= per_launch["sp"] else "sp"
@@ -145,14 +169,16 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: d={wl.d} m={wl.m} k={wl.k} lambda={wl.lam} "
                                f"window rows filled={n}", "fill_steps": fill,
-                   "window_format": "bf16 value + u16 in-slice index" if bf16 else "fp32 value + i32 index"},
+                   "window_format": "bf16 value + u16 in-slice index" if bf16 else "fp32 value + i32 index",
+                   "mode": args.mode},
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_step * 1e-3) / 1e9,
         "hbm_frac": by["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernel_ms": per_launch,
         "roofline": {"bound": "hbm", "kernel": "k_" + dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, dom)) if (n == wl.m and not bf16) else None,
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, dom))
+                     if (n == wl.m and not bf16 and args.mode == "grad") else None,
                      "bytes_per_launch": by[dom], "ms_per_launch": per_launch[dom]},
     }
     ctx.destroy()

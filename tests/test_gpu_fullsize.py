@@ -137,6 +137,99 @@ def test_bert_base_full_window_properties(env, capsys):
     ranges = [(0, 1_500_000), (d // 2 - 700_000, d // 2 + 700_000), (d - 1_200_000, d)]
     worst = _check_mfac(ctx, wl.m, newest, x, out.cpu().numpy(), wl.lam, wl.m, ranges)
     _say(capsys, f"full window: q, Gram row, coef, out ok (worst rel L2 on a range {worst:.2e})")
+
+    # apply(g) on the unchanged window takes another route to the coefficients (W^T W q on the
+    # whole factor instead of the bordered update) and must reproduce the step's output
+    def rel(a_t, b_t):
+        return float((a_t.double() - b_t.double()).norm() / b_t.double().norm())
+    ap = torch.empty_like(g)
+    ctx.apply(g, ap)
+    torch.cuda.synchronize()
+    r_apply = rel(ap, out)
+    assert r_apply < 1e-5, f"apply(g) differs from the step's F^-1 g by {r_apply:.3e}"
+    _say(capsys, f"full window: apply(g) within {r_apply:.1e} of the step's output")
+    s_diag = float(np.diag(ctx.get_small()["S"]).mean())
+    ctx.destroy()
+    del ctx, ap, out
+    torch.cuda.empty_cache()
+    _other_entry_points_full_window(env, capsys, wl, s_diag / wl.m)
+
+
+def _other_entry_points_full_window(env, capsys, wl, lam):
+    """x = c_t, the fused update and apply at d = 110M with all 1024 rows filled, chained to
+    one another.  c_t lies in the span of the window, so F^-1 c_t = c_t/lambda - sum coef_r c_r
+    cancels down to about lambda/(|c|^2/m) of its terms; at the benchmark's lambda = 1e-6 that is
+    1e-11 on this gradient recipe, beyond what fp64 coefficients can resolve by any route (the
+    oracle's included), and no tolerance on the result would mean anything.  The damping used
+    here, mean |c_r|^2 / m, keeps the condition number of m*lambda*I + S below ~m, where the
+    results of two different routes must agree to fp32 rounding."""
+    torch, _, binding = env
+    dev = torch.device("cuda:0")
+    ctx = binding.Efcp(wl.d, wl.m, wl.k, lam)
+    stream = synth.TorchGradientStream(wl.d, wl.rho, wl.seed + 100, dev)
+    g = torch.empty(wl.d, dtype=torch.float32, device=dev)
+    for t in range(wl.m + 1):
+        stream.next_into(g)
+        ctx.step(g, None)
+    torch.cuda.synchronize()
+    _say(capsys, f"other entry points: lambda = {lam:.3e}, window filled")
+
+    def rel(a_t, b_t):
+        return float((a_t.double() - b_t.double()).norm() / b_t.double().norm())
+    out = torch.empty_like(g)
+    ap = torch.empty_like(g)
+    # step vs apply (different coefficient routes)
+    stream.next_into(g)
+    ctx.step(g, out)
+    ctx.apply(g, ap)
+    torch.cuda.synchronize()
+    r_apply = rel(ap, out)
+    assert r_apply < 1e-5, f"apply(g) differs from the step's F^-1 g by {r_apply:.3e}"
+    # a step that preconditions c_t vs apply(dense c_t) on the window it leaves behind
+    stream.next_into(g)
+    ctx.step_ex(g, binding.X_COMPRESSED, out=out)
+    torch.cuda.synchronize()
+    sm = ctx.get_small()
+    newest = (sm["step"] - 1) % wl.m
+    assert np.abs(sm["q"] - sm["S"][newest]).max() <= 1e-10 * np.abs(sm["q"]).max()    # q is the Gram row
+    idx, val = ctx.get_row(newest)
+    c_t = torch.zeros_like(g)
+    c_t[torch.from_numpy(idx.astype(np.int64)).to(dev)] = torch.from_numpy(val).to(dev)
+    ctx.apply(c_t, ap)
+    torch.cuda.synchronize()
+    r_comp = rel(out, ap)
+    assert r_comp < 1e-5, f"F^-1 c_t: step and apply differ by {r_comp:.3e}"
+    shrink = float(out.double().norm() / (c_t.double().norm() / lam))
+    del c_t
+    # fused update vs decay*theta - lr*apply(g) formed in fp64, plain and with x = c_t
+    worst_upd = 0.0
+    for xs in (binding.X_GRAD, binding.X_COMPRESSED):
+        stream.next_into(g)
+        theta = torch.randn(wl.d, device=dev) * 0.02
+        theta0 = theta.clone()
+        ctx.step_ex(g, xs, out=out)                     # to size lr: the step moves theta by ~1e-3
+        torch.cuda.synchronize()
+        lr, wd = 1e-3 * float(theta0.norm() / out.norm()), 0.05
+        stream.next_into(g)
+        ctx.step_ex(g, xs, param=theta, lr=lr, weight_decay=wd)
+        if xs == binding.X_GRAD:
+            ctx.apply(g, ap)
+        else:
+            torch.cuda.synchronize()
+            newest = (ctx.get_small()["step"] - 1) % wl.m
+            idx, val = ctx.get_row(newest)
+            c_t = torch.zeros_like(g)
+            c_t[torch.from_numpy(idx.astype(np.int64)).to(dev)] = torch.from_numpy(val).to(dev)
+            ctx.apply(c_t, ap)
+            del c_t
+        torch.cuda.synchronize()
+        expect = (1.0 - lr * wd) * theta0.double() - lr * ap.double()
+        r_upd = float((theta.double() - expect).norm()) / float((lr * ap.double()).norm())
+        assert r_upd <= 1e-3, f"fused update (x source {xs}) off by {r_upd:.3e} of the step length"
+        worst_upd = max(worst_upd, r_upd)
+        del expect, theta, theta0
+    _say(capsys, f"other entry points: apply {r_apply:.1e}, compressed {r_comp:.1e} "
+                 f"(|F^-1 c_t| = {shrink:.1e} |c_t|/lambda), update {worst_upd:.1e}")
     ctx.destroy()
 
 
