@@ -45,6 +45,10 @@ def _load():
     lib.eo_create.argtypes = [i64, i32, i64, dbl]
     lib.eo_create_fmt.restype = vp
     lib.eo_create_fmt.argtypes = [i64, i32, i64, dbl, ctypes.c_int]
+    lib.eo_create_block.restype = vp
+    lib.eo_create_block.argtypes = [i64, i32, i64, i64, dbl, ctypes.c_int]
+    lib.eo_block_row_length.restype = i64
+    lib.eo_block_row_length.argtypes = [i64, i64, i64]
     lib.eo_bf16_round.restype = ctypes.c_float
     lib.eo_bf16_round.argtypes = [ctypes.c_float]
     lib.eo_destroy.restype = None
@@ -128,11 +132,22 @@ def param_update(theta: np.ndarray, u: np.ndarray, lr: float, weight_decay: floa
 class Oracle:
     """State of the oracle: error feedback e, window G=(I,V), Gram matrix S."""
 
-    def __init__(self, d: int, m: int, k: int, lam: float, values_bf16: bool = False):
+    def __init__(self, d: int, m: int, k: int, lam: float, values_bf16: bool = False, block: int = 0):
+        """block = 0: global Top-k of k entries.  block = B > 0: Top-k applied in
+        blocks of B coordinates, k entries kept per full block; self.k is then
+        the resulting row length."""
         self._lib = _load()
-        self.d, self.m, self.k, self.lam = int(d), int(m), int(k), float(lam)
+        self.d, self.m, self.lam = int(d), int(m), float(lam)
         self.values_bf16 = bool(values_bf16)
-        self._st = self._lib.eo_create_fmt(self.d, self.m, self.k, self.lam, int(self.values_bf16))
+        self.block = int(block)
+        if self.block:
+            self.k_per_block = int(k)
+            self.k = int(self._lib.eo_block_row_length(self.d, self.block, self.k_per_block))
+            self._st = self._lib.eo_create_block(self.d, self.m, self.block, self.k_per_block, self.lam,
+                                                 int(self.values_bf16))
+        else:
+            self.k = int(k)
+            self._st = self._lib.eo_create_fmt(self.d, self.m, self.k, self.lam, int(self.values_bf16))
         if not self._st:
             raise ValueError("eo_create rejected (d, m, k, lambda)")
 

@@ -18,6 +18,8 @@ struct eo_state {
     int32_t m;
     double lambda;
     int values_bf16;    /* stored values are bfloat16 */
+    int64_t block;      /* 0: global Top-k; B > 0: Top-k applied in blocks of B coordinates */
+    int64_t kb;         /* entries kept per full block (block mode) */
     int64_t t;          /* steps done */
     float *e;           /* error feedback xi, d */
     int32_t **idx;      /* m row pointers, NULL until the slot is filled */
@@ -44,6 +46,39 @@ eo_state *eo_create_fmt(int64_t d, int32_t m, int64_t k, double lambda, int valu
     eo_state *st = eo_create(d, m, k, lambda);
     if (st) st->values_bf16 = values_bf16 != 0;
     return st;
+}
+
+int64_t eo_block_row_length(int64_t d, int64_t block, int64_t kb)
+{
+    if (d < 1 || block < 1 || kb < 1 || kb > block) return 0;
+    const int64_t full = d / block, tail = d % block;
+    /* the ragged last block keeps the same share, rounded up */
+    return full * kb + (tail ? (kb * tail + block - 1) / block : 0);
+}
+
+eo_state *eo_create_block(int64_t d, int32_t m, int64_t block, int64_t kb, double lambda,
+                          int values_bf16)
+{
+    const int64_t k = eo_block_row_length(d, block, kb);
+    if (k < 1) return NULL;
+    eo_state *st = eo_create_fmt(d, m, k, lambda, values_bf16);
+    if (st) { st->block = block; st->kb = kb; }
+    return st;
+}
+
+/* Top-k applied in blocks (Section "Sparsity Pattern"): the kb largest magnitudes of every
+ * block of B consecutive coordinates, each block on its own; idx ascending overall. */
+static int topk_blockwise(const float *a, int64_t d, int64_t block, int64_t kb, int32_t *idx, float *val)
+{
+    int64_t w = 0;
+    for (int64_t lo = 0; lo < d; lo += block) {
+        const int64_t len = d - lo < block ? d - lo : block;
+        const int64_t keep = len == block ? kb : (kb * len + block - 1) / block;
+        if (eo_topk(a + lo, len, keep, idx + w, val + w) != 0) return -1;
+        for (int64_t p = 0; p < keep; p++) idx[w + p] += (int32_t)lo;
+        w += keep;
+    }
+    return 0;
 }
 
 eo_state *eo_create(int64_t d, int32_t m, int64_t k, double lambda)
@@ -283,7 +318,9 @@ static int compress_and_insert(eo_state *st, const float *g)
     int32_t *idx = malloc((size_t)k * sizeof(int32_t));
     float *val = malloc((size_t)k * sizeof(float));
     if (!idx || !val) { free(idx); free(val); return -1; }
-    if (eo_topk(st->a, d, k, idx, val) != 0) { free(idx); free(val); return -1; }
+    const int rc_sel = st->block ? topk_blockwise(st->a, d, st->block, st->kb, idx, val)
+                                 : eo_topk(st->a, d, k, idx, val);
+    if (rc_sel != 0) { free(idx); free(val); return -1; }
 
     /* bfloat16 window: c holds the rounded values. */
     if (st->values_bf16)

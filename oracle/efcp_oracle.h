@@ -50,6 +50,14 @@ eo_state *eo_create(int64_t d, int32_t m, int64_t k, double lambda);
  * instead of 0.  Selection itself is done on the fp32 accumulator. */
 eo_state *eo_create_fmt(int64_t d, int32_t m, int64_t k, double lambda, int values_bf16);
 
+/* Top-k applied in blocks of `block` consecutive coordinates (Section "Sparsity Pattern"):
+ * every full block keeps exactly kb entries, its kb largest magnitudes (ties -> lower index);
+ * a ragged last block of len coordinates keeps ceil(kb*len/block).  The row length k is
+ * eo_block_row_length(d, block, kb).  Requires 1 <= kb <= block. */
+eo_state *eo_create_block(int64_t d, int32_t m, int64_t block, int64_t kb, double lambda,
+                          int values_bf16);
+int64_t eo_block_row_length(int64_t d, int64_t block, int64_t kb);
+
 /* Round an fp32 value to bfloat16 (nearest, ties to even), returned as fp32. */
 float eo_bf16_round(float a);
 void eo_destroy(eo_state *st);

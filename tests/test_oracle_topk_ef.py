@@ -214,3 +214,71 @@ def test_bf16_window_error_feedback_keeps_the_rounding_remainder(oracle_mod):
         assert np.array_equal(sum_c + e, sum_g)
         e_prev = e.copy()
     assert saw_remainder
+
+
+# ---------------------------------------------------------------------------
+# Top-k applied in blocks (Section "Sparsity Pattern")
+
+def test_blockwise_topk_keeps_exactly_kb_per_block(oracle_mod):
+    """Every full block holds exactly kb selected entries, and they are that
+    block's own Top-kb by brute force; the ragged last block keeps the same
+    share rounded up; e = a - c and the telescoping identity still hold."""
+    d, m, B, kb, T = 1000, 3, 128, 7, 9                 # 7 full blocks + a tail of 104
+    o = oracle_mod.Oracle(d, m, kb, 1e-2, block=B)
+    tail_keep = -(-kb * (d % B) // B)
+    assert o.k == (d // B) * kb + tail_keep == 55
+    stream = synth.integer_stream(d, seed=12)            # many ties
+    e_prev = np.zeros(d, np.float32)
+    sum_g = np.zeros(d)
+    sum_c = np.zeros(d)
+    for _ in range(T):
+        g = next(stream)
+        o.step(g)
+        a = e_prev + g
+        idx, val = o.row(o.newest_slot)
+        assert (np.diff(idx) > 0).all()
+        expect = []
+        for lo in range(0, d, B):
+            blk = a[lo:lo + B]
+            keep = kb if blk.size == B else tail_keep
+            in_blk = idx[(idx >= lo) & (idx < lo + B)]
+            assert in_blk.size == keep
+            expect.append(_brute_topk(blk, keep) + lo)
+        assert np.array_equal(idx, np.concatenate(expect))
+        assert np.array_equal(val, a[idx])
+        e = o.error
+        assert not e[idx].any()
+        mask = np.ones(d, bool); mask[idx] = False
+        assert np.array_equal(e[mask], a[mask])
+        sum_g += g
+        sum_c[idx] += val
+        assert np.array_equal(sum_c + e, sum_g)
+        e_prev = e.copy()
+
+
+def test_blockwise_with_one_block_is_global_topk(oracle_mod):
+    d, k = 777, 31
+    a = oracle_mod.Oracle(d, 4, k, 1e-2, block=d)         # a single block covering everything
+    b = oracle_mod.Oracle(d, 4, k, 1e-2)
+    c = oracle_mod.Oracle(d, 4, k, 1e-2, block=4 * d)     # block larger than d: only a "tail"
+    assert a.k == k and c.k == -(-k * d // (4 * d))
+    rng = np.random.default_rng(14)
+    for _ in range(6):
+        g = rng.standard_normal(d).astype(np.float32)
+        ya, yb = a.step(g), b.step(g)
+        assert np.array_equal(a.row(a.newest_slot)[0], b.row(b.newest_slot)[0])
+        assert np.array_equal(a.error, b.error) and np.array_equal(ya, yb)
+
+
+def test_blockwise_differs_from_global_when_mass_is_concentrated(oracle_mod):
+    """All large entries in one block: global Top-k takes them all, blockwise
+    may take only kb of them -- the rest stays in the error feedback."""
+    d, B, kb = 512, 128, 4
+    g = np.full(d, 0.5, np.float32)
+    g[:16] = np.arange(16, 0, -1, dtype=np.float32) + 10
+    o = oracle_mod.Oracle(d, 2, kb, 1e-2, block=B)
+    o.step(g)
+    idx, _ = o.row(0)
+    assert list(idx[:kb]) == [0, 1, 2, 3]
+    assert np.array_equal(idx[kb:], np.concatenate([np.arange(B * b, B * b + kb) for b in (1, 2, 3)]))
+    assert np.array_equal(o.error[4:16], g[4:16])
