@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--mode", choices=["grad", "compressed", "update", "compressed-update"], default="grad",
                     help="grad = the benchmark's definition (F^-1 g written); compressed: x = c_t; "
                          "update: parameters updated in place by the LCG kernel")
+    ap.add_argument("--topk", choices=["global", "block"], default="global",
+                    help="global = exact global Top-k (the benchmark's definition); block = Top-k applied "
+                         "in blocks of 16,384 coordinates, ceil(16384*k/d) entries per block")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -108,8 +111,14 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     bf16 = args.values == "bf16"
-    ctx = binding.Efcp(wl.d, wl.m, wl.k, wl.lam,
-                       values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
+    if args.topk == "block":
+        kb = -(-binding.TOPK_BLOCK * wl.k // wl.d)
+        ctx = binding.Efcp(wl.d, wl.m, kb, wl.lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
+                           topk_block=binding.TOPK_BLOCK)
+    else:
+        ctx = binding.Efcp(wl.d, wl.m, wl.k, wl.lam,
+                           values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
+    k_row = ctx.k
     stream = synth.TorchGradientStream(wl.d, wl.rho, wl.seed, dev)
     out = torch.empty(wl.d, dtype=torch.float32, device=dev)
     pool = [torch.empty(wl.d, dtype=torch.float32, device=dev) for _ in range(4)]
@@ -157,7 +166,7 @@ def main():
     assert torch.isfinite(out).all().item()
 
     n = min(sm["step"], wl.m)
-    by = step_bytes(wl.d, wl.k, n, 4 if bf16 else 8, args.mode)
+    by = step_bytes(wl.d, k_row, n, 4 if bf16 else 8, args.mode)
     ms_step = (t1 - t0) * 1e3 / args.steps
     per_launch = {kname: ms_groups[kname] / max(covered, 1) for kname in ms_groups}
     dom = "lcg" if per_launch["lcg"] >= per_launch["sp"] else "sp"
@@ -167,10 +176,10 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{wl.name}: d={wl.d} m={wl.m} k={wl.k} lambda={wl.lam} "
+        "config": {"workload": f"{wl.name}: d={wl.d} m={wl.m} k={k_row} lambda={wl.lam} "
                                f"window rows filled={n}", "fill_steps": fill,
                    "window_format": "bf16 value + u16 in-slice index" if bf16 else "fp32 value + i32 index",
-                   "mode": args.mode},
+                   "mode": args.mode, "topk": args.topk},
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_step * 1e-3) / 1e9,
         "hbm_frac": by["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -178,7 +187,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_" + dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC.get((wl.name, dom))
-                     if (n == wl.m and not bf16 and args.mode == "grad") else None,
+                     if (n == wl.m and not bf16 and args.mode == "grad" and args.topk == "global") else None,
                      "bytes_per_launch": by[dom], "ms_per_launch": per_launch[dom]},
     }
     ctx.destroy()

@@ -78,6 +78,22 @@ int efcp_create(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
 int efcp_create_fmt(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
                     int32_t value_format, void *workspace, size_t workspace_bytes);
 
+/* Top-k applied in blocks (Section "Sparsity Pattern"; the selection rule of the paper's own
+ * implementation): every block of EFCP_TOPK_BLOCK consecutive coordinates keeps exactly k
+ * entries, its k largest |a_j| (ties -> lower index); a ragged last block of len coordinates
+ * keeps ceil(k*len/EFCP_TOPK_BLOCK).  The block is the d-slice the SP and LCG kernels stage in
+ * LDS.  Error feedback, selection and compaction are then one kernel with minimal traffic.
+ *   topk_block   0: global Top-k of k entries (efcp_create_fmt); EFCP_TOPK_BLOCK: in blocks,
+ *                k = entries per block, 1 <= k <= EFCP_TOPK_BLOCK; anything else: EFCP_EINVAL
+ * The row length (entries efcp_get_row returns) is efcp_row_length(d, k, topk_block). */
+#define EFCP_TOPK_BLOCK 16384
+int efcp_create_ex(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double lambda,
+                   int32_t value_format, int32_t topk_block, void *workspace, size_t workspace_bytes);
+size_t efcp_workspace_bytes_ex(int64_t d, int32_t m, int64_t k, int32_t value_format,
+                               int32_t topk_block);
+/* Entries per window row for these arguments; 0 if they are invalid. */
+int64_t efcp_row_length(int64_t d, int64_t k, int32_t topk_block);
+
 /* One step (see the top of this file).
  *   grad    device, d floats, 16-byte aligned, read only
  *   out     device, d floats, 16-byte aligned, receives F^-1 grad; must not

@@ -20,11 +20,29 @@ constexpr int kProfEvents = EFCP_K_COUNT + 1;
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Largest power-of-two slice whose LDS working set fits the device.
-bool make_geometry(int64_t d, int32_t m, int64_t k, int32_t fmt, Geometry &g, const char **why)
+// Entries per row when every block of kCandBlock coordinates keeps kb and a ragged last block
+// keeps the same share rounded up.
+int64_t block_row_length(int64_t d, int64_t kb)
+{
+    const int64_t full = d / kCandBlock, tail = d % kCandBlock;
+    return full * kb + (tail ? (kb * tail + kCandBlock - 1) / kCandBlock : 0);
+}
+
+// k_in: entries per row (topk_block == 0) or per block of kCandBlock coordinates.
+bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk_block, Geometry &g,
+                   const char **why)
 {
     if (fmt != kFmtF32 && fmt != kFmtBf16) { *why = "unknown value format"; return false; }
     if (d < 1 || d >= ((int64_t)1 << 31)) { *why = "d out of range [1, 2^31)"; return false; }
     if (m < 1 || m > kMaxM) { *why = "m out of range [1, 1024]"; return false; }
+    if (topk_block != 0 && topk_block != kCandBlock) { *why = "topk_block must be 0 or 16384"; return false; }
+    int64_t k = k_in;
+    g.kb = 0;
+    if (topk_block) {
+        if (k_in < 1 || k_in > kCandBlock) { *why = "k per block out of range [1, 16384]"; return false; }
+        g.kb = (int32_t)k_in;
+        k = block_row_length(d, k_in);
+    }
     if (k < 1 || k > d) { *why = "k out of range [1, d]"; return false; }
     int dev = 0, lds = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -57,7 +75,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k, int32_t fmt, Geometry &g, co
 
 struct Layout {
     size_t e, ring_idx, ring_val, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
-        cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, total;
+        cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, total;
     size_t small_begin;      // everything from here on is small and zero-initialised
 };
 
@@ -70,8 +88,9 @@ Layout make_layout(const Geometry &g)
     l.ring_idx = take((size_t)g.m * g.row_stride * esz);
     l.ring_val = take((size_t)g.m * g.row_stride * esz);
     l.partial = take((size_t)g.sp_grid * g.m * sizeof(double2));
-    l.cand_idx = take((size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
-    l.cand_val = take((size_t)g.n_sel_blocks * kCandBlock * sizeof(float));
+    // candidate lists exist for the global Top-k only
+    l.cand_idx = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
+    l.cand_val = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(float));
     l.small_begin = o;
     l.e = take((size_t)g.d * sizeof(float));
     l.offT = take((size_t)(g.n_slices + 1) * g.m * sizeof(int32_t));
@@ -89,6 +108,8 @@ Layout make_layout(const Geometry &g)
     l.sel_off = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.eq_before = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.cand_cnt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
+    l.blk_max = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
+    l.blk_tlo = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
     l.status = take(256);
     l.total = o;
     return l;
@@ -123,12 +144,25 @@ static int fail(efcp_ctx *ctx, int code, const char *msg)
     return code;
 }
 
-extern "C" size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int32_t value_format)
+extern "C" size_t efcp_workspace_bytes_ex(int64_t d, int32_t m, int64_t k, int32_t value_format,
+                                          int32_t topk_block)
 {
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, value_format, g, &why)) return 0;
+    if (!make_geometry(d, m, k, value_format, topk_block, g, &why)) return 0;
     return make_layout(g).total;
+}
+
+extern "C" size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int32_t value_format)
+{
+    return efcp_workspace_bytes_ex(d, m, k, value_format, 0);
+}
+
+extern "C" int64_t efcp_row_length(int64_t d, int64_t k, int32_t topk_block)
+{
+    if (topk_block == 0) return (k >= 1 && k <= d) ? k : 0;
+    if (topk_block != kCandBlock || d < 1 || k < 1 || k > kCandBlock) return 0;
+    return block_row_length(d, k);
 }
 
 extern "C" size_t efcp_workspace_bytes(int64_t d, int32_t m, int64_t k)
@@ -145,12 +179,19 @@ extern "C" int efcp_create(efcp_ctx **out, int64_t d, int32_t m, int64_t k, doub
 extern "C" int efcp_create_fmt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
                                int32_t value_format, void *workspace, size_t workspace_bytes)
 {
+    return efcp_create_ex(out, d, m, k, lambda, value_format, 0, workspace, workspace_bytes);
+}
+
+extern "C" int efcp_create_ex(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
+                              int32_t value_format, int32_t topk_block, void *workspace,
+                              size_t workspace_bytes)
+{
     if (!out) return EFCP_EINVAL;
     *out = nullptr;
     if (!(lambda > 0.0) || !std::isfinite(lambda)) return EFCP_EINVAL;
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, value_format, g, &why)) return EFCP_EINVAL;
+    if (!make_geometry(d, m, k, value_format, topk_block, g, &why)) return EFCP_EINVAL;
     const Layout l = make_layout(g);
 
     efcp_ctx *ctx = new (std::nothrow) efcp_ctx();
@@ -206,6 +247,8 @@ extern "C" int efcp_create_fmt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, 
     p.cand_idx = reinterpret_cast<int32_t *>(b + l.cand_idx);
     p.cand_val = reinterpret_cast<float *>(b + l.cand_val);
     p.cand_cnt = reinterpret_cast<uint32_t *>(b + l.cand_cnt);
+    p.blk_max = reinterpret_cast<uint32_t *>(b + l.blk_max);
+    p.blk_tlo = reinterpret_cast<uint32_t *>(b + l.blk_tlo);
     p.status = reinterpret_cast<uint32_t *>(b + l.status);
 
     // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.
@@ -280,11 +323,17 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
         if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_join, ctx->side);
     }
     mark(0);
-    if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
-    mark(1);
-    if (rc == hipSuccess) rc = launch_select(g, p, slot, stream);
-    mark(2);
-    if (rc == hipSuccess) rc = launch_compact(g, p, slot, stream);
+    if (g.kb) {         // Top-k in blocks: error feedback, selection and compaction in one kernel
+        if (rc == hipSuccess) rc = launch_block_topk(g, p, grad, slot, stream);
+        mark(1);
+        mark(2);
+    } else {
+        if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
+        mark(1);
+        if (rc == hipSuccess) rc = launch_select(g, p, slot, stream);
+        mark(2);
+        if (rc == hipSuccess) rc = launch_compact(g, p, slot, stream);
+    }
     mark(3);
     if (rc == hipSuccess) rc = launch_sp(g, p, grad, n_filled, slot, x_is_row ? 1 : 0, stream);
     mark(4);
@@ -433,14 +482,15 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
 namespace {
 
 struct StateHeader {
-    uint64_t magic;          // "EFCPST01"
+    uint64_t magic;          // "EFCPST02"
     int64_t d, k, row_stride, t;
     int32_t m, ldm, slice, n_slices;
     double lambda;
     uint32_t t_lo, status;
     int32_t filled, fmt;
+    int32_t kb, reserved;
 };
-constexpr uint64_t kStateMagic = 0x3130545350434645ull;
+constexpr uint64_t kStateMagic = 0x3230545350434645ull;
 
 size_t state_bytes(const efcp_ctx *ctx)
 {
@@ -476,6 +526,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     h.t_lo = st.t_lo; h.status = status;
     h.filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
     h.fmt = g.fmt;
+    h.kb = g.kb;
     const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
     unsigned char *o = static_cast<unsigned char *>(host_buf);
     std::memcpy(o, &h, sizeof h);
@@ -507,7 +558,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     const Geometry &g = ctx->g;
     if (h.magic != kStateMagic || h.d != g.d || h.k != g.k || h.m != g.m || h.row_stride != g.row_stride ||
         h.ldm != g.ldm || h.slice != g.slice || h.n_slices != g.n_slices || h.lambda != ctx->lambda ||
-        h.fmt != g.fmt ||
+        h.fmt != g.fmt || h.kb != g.kb ||
         h.t < 0 || h.filled != (int32_t)(h.t < g.m ? h.t : g.m))
         return fail(ctx, EFCP_EINVAL, "state does not belong to a context of this shape");
     const int64_t t_keep = ctx->t;
@@ -539,6 +590,8 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     if (rc == hipSuccess) rc = hipMemcpy(p.sel, &st, sizeof st, hipMemcpyHostToDevice);
     if (rc == hipSuccess) rc = hipMemcpy(p.status, &h.status, 4, hipMemcpyHostToDevice);
     if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, kBins1 * sizeof(uint32_t));
+    // where each block starts counting is a hint only: start from "count everything"
+    if (rc == hipSuccess && g.kb) rc = hipMemset(p.blk_tlo, 0, (size_t)g.n_slices * sizeof(uint32_t));
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
     return EFCP_OK;

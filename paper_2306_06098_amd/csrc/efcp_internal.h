@@ -17,6 +17,8 @@
 //                                        in age order and for unfilled slots
 //   cand_*    [ceil(d/16384)][16384]      Top-k candidates of the current step, one
 //                                        segment per block of 16,384 coordinates
+//                                        (global Top-k only; block-wise Top-k keeps
+//                                        two uint32 per block instead)
 //   partial   double2[sp_grid][m]        per-workgroup (q, Gram) partial sums
 //   sq        double2[m]                 (q_r, S[slot][r]) of the current step
 //   zw        double2[m]                 (W s, W q) of the current step
@@ -98,6 +100,7 @@ enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
 
 struct Geometry {
     int64_t d, k, row_stride;
+    int32_t kb;              // 0: global Top-k; > 0: Top-k in blocks, entries kept per full block
     int32_t m, ldm;
     int32_t fmt;             // kFmtF32 / kFmtBf16
     int32_t slice, slice_log2, n_slices;
@@ -121,6 +124,8 @@ struct DevicePtrs {
     int32_t *cand_idx;       // [n_sel_blocks][kCandBlock] candidate indices, ascending per segment
     float *cand_val;         // [n_sel_blocks][kCandBlock] candidate values
     uint32_t *cand_cnt;      // [n_sel_blocks] entries used per segment
+    uint32_t *blk_max;       // [n_slices] largest key per block          (block-wise Top-k only)
+    uint32_t *blk_tlo;       // [n_slices] where each block's first histogram starts counting
     uint32_t *status;
 };
 
@@ -129,6 +134,8 @@ hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *g
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 // x_source: 0 = dense x next to the newest row, 1 = the newest row is x, 2 = dense x only
+hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t slot,
+                             hipStream_t stream);
 hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
                      int32_t slot, int32_t x_source, hipStream_t stream);
 hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
@@ -148,6 +155,28 @@ hipError_t configure_sp(const Geometry &g);
 hipError_t configure_lcg(const Geometry &g);
 
 // ---- small device helpers shared by the kernels ----
+
+// Static list of the d-slices one persistent SP / LCG workgroup walks.  An XCD owns the
+// contiguous range [first, end); its `cpx` workgroups take it in rounds of cpx neighbouring
+// slices, and in round i workgroup `cu` takes position (cu + i) mod cpx of the round.  The
+// rotation matters most when every row has the same run boundaries (Top-k applied in blocks):
+// how a slice's runs sit relative to cache lines depends on s mod 8, and without it a
+// workgroup keeps the same s mod 8, good or bad, for the whole pass (measured on one box:
+// LCG pass 5 % slower without the rotation at 164 entries per block, 1 % with global Top-k).
+struct SliceList {
+    int32_t first, cu, cpx, count;
+    __device__ __forceinline__ SliceList(int32_t first_, int32_t end, int32_t cu_, int32_t cpx_)
+        : first(first_), cu(cu_), cpx(cpx_)
+    {
+        const int32_t n = end > first_ ? end - first_ : 0;
+        const int32_t rounds = (n + cpx_ - 1) / cpx_;
+        // all rounds but the last are complete; in the last one only the first n - (rounds-1)*cpx
+        // positions exist
+        count = rounds == 0 ? 0 : (rounds - 1) + ((first_ + pos(rounds - 1)) < end ? 1 : 0);
+    }
+    __device__ __forceinline__ int32_t pos(int32_t i) const { return i * cpx + (cu + i) % cpx; }
+    __device__ __forceinline__ int32_t at(int32_t i) const { return first + pos(i); }
+};
 
 // Streaming accesses: data read or written exactly once per step (the gradient, the error
 // buffer, the output) is moved with the non-temporal hint so that it does not displace the

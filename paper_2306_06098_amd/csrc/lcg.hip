@@ -88,10 +88,11 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const int grp = tid >> 4, gl = tid & 15;
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
-    const int32_t s_end = min(nsl, (xcd + 1) * per);
+    const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
     const int32_t mask = slice - 1;
-    int32_t s = xcd * per + cu;
-    if (s >= s_end) return;                   // uniform: this workgroup has no slice
+    if (sl.count == 0) return;                // uniform: this workgroup has no slice
+    int32_t it = 0;
+    int32_t s = sl.at(0);
     const int32_t trow = min(tid, m - 1);     // row whose offsets this thread fetches
 
     for (int32_t i = tid; i < slice; i += 1024) acc[i] = 0ull;
@@ -171,8 +172,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         const int64_t base64 = (int64_t)s << slice_log2;
         const int32_t base = (int32_t)base64;
         const int32_t len = FULL ? slice : (int32_t)(d - base64);
-        const int32_t sn = s + cpx;
-        const int32_t sl = sn < s_end ? sn : s;
+        const int32_t snx = it + 1 < sl.count ? sl.at(it + 1) : s;     // this workgroup's next slice
         auto consume = [&](const LcgBatch<FMT> &b) {
             const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
 #pragma unroll
@@ -189,8 +189,8 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
             for (int u = 0; u < 4; u++)
                 xr[u] = load_stream_f4(x + base64 + tid * 4 + u * 4096);
         }
-        const int32_t o0 = offT[(int64_t)sl * m + trow];
-        const int32_t o1 = offT[(int64_t)(sl + 1) * m + trow];
+        const int32_t o0 = offT[(int64_t)snx * m + trow];
+        const int32_t o1 = offT[(int64_t)(snx + 1) * m + trow];
         int32_t *offn = offs + (buf ^ 1) * 2 * kMaxM;
 
         bool stored = false;
@@ -262,9 +262,16 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     };
 
     const int32_t n_full = (int32_t)(d >> slice_log2);            // slices with all coordinates
-    const int32_t s_full_end = min(s_end, n_full);
-    for (; s < s_full_end; s += cpx) do_slice(std::true_type{});
-    if (s < s_end) do_slice(std::false_type{});                   // uniform
+    // the ragged slice, if this workgroup has it, is the last of its list
+    const int32_t n_mine_full = sl.count - (sl.at(sl.count - 1) >= n_full ? 1 : 0);
+    for (; it < n_mine_full; it++) {
+        s = sl.at(it);
+        do_slice(std::true_type{});
+    }
+    if (it < sl.count) {                                          // uniform
+        s = sl.at(it);
+        do_slice(std::false_type{});
+    }
 }
 
 // out = x/lambda (empty window: F = lambda*I), or the parameter update with that vector.

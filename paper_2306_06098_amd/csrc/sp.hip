@@ -63,8 +63,8 @@ enum : int { kXDense = 0, kXNewest = 1, kXOnly = 2 };
 // Workgroup b sits on XCD b%8 (workgroups are dealt to the 8 XCDs round-robin)
 // and is the (b/8)-th of `cpx` workgroups there.  XCD x owns the contiguous
 // slice range [x*per, (x+1)*per); at any time its workgroups work on
-// neighbouring slices, so a cache line straddling two runs of a row is
-// wanted by two CUs of the same L2 at about the same time.
+// neighbouring slices (see SliceList), so a cache line straddling two runs of
+// a row is wanted by two CUs of the same L2 at about the same time.
 //
 // While the rows of one slice stream, everything the next slice needs first is
 // already on its way in registers: its x values, its row offsets and the
@@ -96,8 +96,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int grp = tid >> 4, gl = tid & 15;
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
-    const int32_t s_end = min(nsl, (xcd + 1) * per);
-    const int32_t s_first = xcd * per + cu;
+    const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
     const int32_t mask = slice - 1;
     const int32_t trow = min(tid, m - 1);
     const idx_t *nidx = ring_idx + (int64_t)slot * row_stride;     // newest row
@@ -105,13 +104,13 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int32_t klast = (int32_t)(k - 1);
 
     racc[tid] = make_double2(0.0, 0.0);
-    if (s_first >= s_end) {                   // uniform: no slice for this workgroup
+    if (sl.count == 0) {                      // uniform: no slice for this workgroup
         if (tid < m) partial[(int64_t)blockIdx.x * m + tid] = make_double2(0.0, 0.0);
         return;
     }
     if (XM != kXOnly) {
-        for (int32_t i = tid; s_first + i * cpx < s_end && i < kMaxSlicesPerWg; i += 1024) {
-            const int32_t si = s_first + i * cpx;
+        for (int32_t i = tid; i < sl.count; i += 1024) {
+            const int32_t si = sl.at(i);
             np0[i] = offT[(int64_t)si * m + slot];
             np1[i] = offT[(int64_t)(si + 1) * m + slot];
         }
@@ -123,7 +122,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     idx_t di = 0;
     val_t dv = 0;
     int32_t it = 0;                           // index of the current slice in this workgroup's list
-    int32_t s = s_first;
+    int32_t s = sl.at(0);
 
     auto prefetch = [&](int32_t sp, int32_t ip, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
@@ -189,7 +188,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         }
     };
 
-    for (; s < s_end; s += cpx, it++) {
+    for (; it < sl.count; it++) {
+        s = sl.at(it);
         const int32_t base = (int32_t)((int64_t)s << slice_log2);
         // ---- switch to slice s: everything comes from registers ----
         __syncthreads();            // previous slice fully consumed
@@ -220,8 +220,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         __syncthreads();
 
         // ---- prefetch for the next slice of this workgroup ----
-        const int32_t sn = s + cpx;
-        if (sn < s_end) {           // uniform
+        if (it + 1 < sl.count) {    // uniform
+            const int32_t sn = sl.at(it + 1);
             if (sn < n_full) prefetch(sn, it + 1, std::true_type{});
             else prefetch(sn, it + 1, std::false_type{});
         }

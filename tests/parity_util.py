@@ -27,7 +27,7 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
                check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False,
-               compressed=False, update=None, apply_every=0):
+               compressed=False, update=None, apply_every=0, topk_block=0):
     """grads: iterable of float32 numpy arrays.  bf16: the bfloat16 window
     format on both sides.  compressed: the step preconditions c_t instead of
     the gradient.  update=(lr, weight_decay): the step updates a parameter
@@ -35,10 +35,13 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
     |theta_gpu - theta_ref| relative to |lr * F^-1 x|, with both sides starting
     each step from the same fp32 parameters.  apply_every=n: after every n-th
     step a seeded random x is applied to the window as it stands on both
-    sides (no insertion).  Returns dict of worst errors."""
+    sides (no insertion).  topk_block=B: Top-k applied in blocks of B
+    coordinates on both sides, k entries per block.  Returns dict of worst errors."""
     dev = torch.device("cuda:0")
-    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16)
-    g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
+    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=topk_block)
+    g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
+                         topk_block=topk_block)
+    assert g_gpu.k == o.k, "row length differs"
     e_prev = np.zeros(d, np.float32)
     grad_d = torch.empty(d, dtype=torch.float32, device=dev)
     out_d = torch.empty(d, dtype=torch.float32, device=dev)
@@ -95,8 +98,9 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
                 worst["coef"] = max(worst["coef"], sc)
                 assert sS <= 1e-10, f"step {t}: Gram matrix off by {sS:.3e}"
                 assert sq <= 1e-10, f"step {t}: q off by {sq:.3e}"
-                sel_key = bits(a[oi]) & np.uint32(0x7FFFFFFF)
-                assert sm["tau"] == int(sel_key.min()), f"step {t}: threshold key differs"
+                if not topk_block:
+                    sel_key = bits(a[oi]) & np.uint32(0x7FFFFFFF)
+                    assert sm["tau"] == int(sel_key.min()), f"step {t}: threshold key differs"
             if apply_every and t % apply_every == 0:
                 x = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
                 ya = o.apply(x)

@@ -37,7 +37,7 @@ def _say(capsys, msg):
         print(f"\n    [{time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
-def _first_steps_vs_oracle(env, capsys, name, steps):
+def _first_steps_vs_oracle(env, capsys, name, steps, **kw):
     torch, oracle_mod, binding = env
     wl = synth.WORKLOADS[name]
     s = synth.GradientStream(wl.d, wl.rho, wl.seed)
@@ -47,7 +47,8 @@ def _first_steps_vs_oracle(env, capsys, name, steps):
             g = s.next()
             _say(capsys, f"{name}: step {t + 1}/{steps} (oracle sorts {wl.d:,} pairs)")
             yield g
-    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, wl.lam, grads())
+    k = kw.pop("k", wl.k)
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, k, wl.lam, grads(), **kw)
     _say(capsys, f"{name}: {w}")
     assert w["steps"] == steps
 
@@ -58,6 +59,14 @@ def test_resnet18_first_steps_vs_oracle(env, capsys):
 
 def test_bert_base_first_steps_vs_oracle(env, capsys):
     _first_steps_vs_oracle(env, capsys, "bert_base", 2)
+
+
+def test_bert_base_blockwise_first_steps_vs_oracle(env, capsys):
+    """Top-k applied in blocks at d = 110M (6,713 full blocks and a ragged one), 164 entries
+    per block, bfloat16 window on the last two steps' twin run; apply() after every step."""
+    torch, _, binding = env
+    _first_steps_vs_oracle(env, capsys, "bert_base", 3, k=164, topk_block=binding.TOPK_BLOCK, apply_every=1)
+    _first_steps_vs_oracle(env, capsys, "bert_base", 2, k=164, topk_block=binding.TOPK_BLOCK, bf16=True)
 
 
 # ---------------------------------------------------------------------------
@@ -77,6 +86,34 @@ def _check_topk_and_error(a, e_gpu, k, idx, val):
     e_ref[idx] = 0.0
     assert np.array_equal(bits(e_gpu), bits(e_ref)), "e != a - c"
     return int(kth)
+
+
+def _check_block_topk_and_error(a, e_gpu, kb, B, idx, val):
+    """Block-wise selection by its definition: per block of B the kb largest keys, ties to the
+    lower index; the ragged tail keeps ceil(kb*len/B)."""
+    d = a.size
+    key = a.view(np.uint32) & np.uint32(0x7FFFFFFF)
+    sel = np.zeros(d, bool)
+
+    def select(keys2d, keep):
+        L = keys2d.shape[1]
+        kth = np.partition(keys2d, L - keep, axis=1)[:, L - keep][:, None]
+        gt = keys2d > kth
+        eq = keys2d == kth
+        quota = keep - gt.sum(axis=1, keepdims=True)
+        assert (quota >= 1).all() and (quota <= eq.sum(axis=1, keepdims=True)).all()
+        return gt | (eq & (np.cumsum(eq, axis=1) <= quota))
+    nb = d // B
+    sel[:nb * B] = select(key[:nb * B].reshape(nb, B), kb).reshape(-1)
+    tail = d - nb * B
+    if tail:
+        sel[nb * B:] = select(key[nb * B:].reshape(1, tail), -(-kb * tail // B)).reshape(-1)
+    expect = np.flatnonzero(sel).astype(np.int32)
+    assert np.array_equal(idx, expect), "selected set differs from the block-wise definition"
+    assert np.array_equal(bits(val), bits(a[idx])), "stored values are not a at the indices"
+    e_ref = a.copy()
+    e_ref[idx] = 0.0
+    assert np.array_equal(bits(e_gpu), bits(e_ref)), "e != a - c"
 
 
 def _check_mfac(ctx, n, newest, x, out, lam, m, ranges):
@@ -230,6 +267,39 @@ def _other_entry_points_full_window(env, capsys, wl, lam):
         del expect, theta, theta0
     _say(capsys, f"other entry points: apply {r_apply:.1e}, compressed {r_comp:.1e} "
                  f"(|F^-1 c_t| = {shrink:.1e} |c_t|/lambda), update {worst_upd:.1e}")
+    ctx.destroy()
+
+
+def test_bert_base_blockwise_full_window_properties(env, capsys):
+    """bench.py --topk block: d = 110M, m = 1024 rows all filled, 164 entries per block."""
+    torch, _, binding = env
+    wl = synth.WORKLOADS["bert_base"]
+    dev = torch.device("cuda:0")
+    kb = 164
+    ctx = binding.Efcp(wl.d, wl.m, kb, wl.lam, topk_block=binding.TOPK_BLOCK)
+    assert ctx.k == (wl.d // 16384) * kb + -(-kb * (wl.d % 16384) // 16384)
+    stream = synth.TorchGradientStream(wl.d, wl.rho, wl.seed + 7, dev)
+    g = torch.empty(wl.d, dtype=torch.float32, device=dev)
+    out = torch.empty_like(g)
+    for t in range(wl.m + 2):
+        stream.next_into(g)
+        ctx.step(g, None)
+    torch.cuda.synchronize()
+    _say(capsys, "blockwise full window: filled 1026 steps; one more step, checked on the host")
+    e_before = ctx.get_error()
+    stream.next_into(g)
+    ctx.step(g, out)
+    torch.cuda.synchronize()
+    x = g.cpu().numpy()
+    a = e_before + x
+    newest = (wl.m + 2) % wl.m
+    idx, val = ctx.get_row(newest)
+    _check_block_topk_and_error(a, ctx.get_error(), kb, 16384, idx, val)
+    _say(capsys, "blockwise full window: selection and e match the definition; walking the 1024 rows")
+    d = wl.d
+    ranges = [(0, 1_500_000), (d // 2 - 700_000, d // 2 + 700_000), (d - 1_200_000, d)]
+    worst = _check_mfac(ctx, wl.m, newest, x, out.cpu().numpy(), wl.lam, wl.m, ranges)
+    _say(capsys, f"blockwise full window: q, Gram row, coef, out ok (worst rel L2 on a range {worst:.2e})")
     ctx.destroy()
 
 

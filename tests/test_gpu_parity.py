@@ -444,3 +444,92 @@ def test_step_ex_argument_checks(env):
         assert g_gpu.get_small()["step"] == 0                               # nothing ran
     finally:
         g_gpu.destroy()
+
+
+# ---------------------------------------------------------------------------
+# Top-k applied in blocks of 16,384 coordinates (Section "Sparsity Pattern")
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_blockwise_topk_tiny_workload(env, bf16):
+    """d = 65,536 = 4 blocks, 164 entries kept per block (1 %), all 200 steps."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, 164, wl.lam, _stream(wl, wl.T), bf16=bf16,
+                   topk_block=binding.TOPK_BLOCK)
+    print("tiny blockwise", bf16, w)
+    assert w["steps"] == wl.T
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("d,m,kb,lam,T", [
+    (272_474, 16, 164, 1e-5, 30),     # 16 full blocks + a ragged one of 10,330 coordinates
+    (16_384 * 3, 7, 1, 1e-4, 12),     # one entry per block
+    (16_384 + 1, 3, 16_384, 1e-2, 7),  # every coordinate kept: e stays 0; tail block of one element
+    (20_001, 5, 4099, 1e-3, 11),      # large share, ragged
+    (3, 2, 5000, 1e-1, 6),            # a single tiny block: keeps ceil(5000*3/16384) = 1
+    (100_003, 1, 333, 1e-3, 5),       # m = 1
+])
+def test_blockwise_topk_shapes(env, d, m, kb, lam, T, bf16):
+    torch, oracle_mod, binding = env
+    w = run_parity(torch, oracle_mod, binding, d, m, kb, lam, _edge_grads(d, T, d + m), bf16=bf16,
+                   topk_block=binding.TOPK_BLOCK, apply_every=4)
+    print((d, m, kb, bf16), w)
+
+
+def test_blockwise_topk_ties_and_threshold_jumps(env):
+    """Integer gradients (ties at every block's threshold), then blocks whose
+    magnitudes collapse and explode between steps (the per-block starting bin of
+    the first histogram is then wrong and the kernel must recount)."""
+    torch, oracle_mod, binding = env
+    d, m, kb = 70_000, 6, 200
+    s = synth.integer_stream(d, seed=21)
+    w = run_parity(torch, oracle_mod, binding, d, m, kb, 1e-2, (next(s) for _ in range(25)),
+                   topk_block=binding.TOPK_BLOCK)
+    print("blockwise ties", w)
+    rng = np.random.default_rng(22)
+
+    def jumps():
+        for t in range(16):
+            g = rng.standard_normal(d).astype(np.float32)
+            scale = np.ones(d, np.float32)
+            for b in range(0, d, 16_384):
+                scale[b:b + 16_384] = np.float32(10.0 ** rng.integers(-8, 8))
+            yield g * scale
+    w = run_parity(torch, oracle_mod, binding, d, m, kb, 1e-2, jumps(), topk_block=binding.TOPK_BLOCK,
+                   out_tol=None)
+    print("blockwise jumps", w)
+
+
+def test_blockwise_topk_modes_and_checkpoint(env):
+    """x = c_t and the fused update on a block-wise window; export / import."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, 164, wl.lam, _stream(wl, 50),
+                   topk_block=binding.TOPK_BLOCK, compressed=True, update=(3e-6, 0.01))
+    print("tiny blockwise compressed update", w)
+    d, m, kb, lam = 50_001, 4, 100, 1e-3
+    dev = torch.device("cuda:0")
+    a = binding.Efcp(d, m, kb, lam, topk_block=binding.TOPK_BLOCK)
+    b = binding.Efcp(d, m, kb, lam, topk_block=binding.TOPK_BLOCK)
+    c = binding.Efcp(d, m, a.k, lam)                      # same row length, global Top-k
+    try:
+        grads = [torch.from_numpy(g).to(dev) for g in _edge_grads(d, 9, 77)]
+        oa, ob = torch.empty(d, device=dev), torch.empty(d, device=dev)
+        for g in grads[:6]:
+            a.step(g, oa)
+        blob = a.export_state()
+        with pytest.raises(binding.EfcpError):
+            c.import_state(blob)                          # selection rule is part of the state's shape
+        b.import_state(blob)
+        for g in grads[6:]:
+            a.step(g, oa)
+            b.step(g, ob)
+            torch.cuda.synchronize()
+            assert torch.equal(oa, ob)
+        assert np.array_equal(bits(a.get_error()), bits(b.get_error()))
+        with pytest.raises(binding.EfcpError):
+            binding.Efcp(d, m, kb, lam, topk_block=4096)  # only the slice width is supported
+        with pytest.raises(binding.EfcpError):
+            binding.Efcp(d, m, 16_385, lam, topk_block=binding.TOPK_BLOCK)
+    finally:
+        a.destroy(); b.destroy(); c.destroy()
