@@ -49,6 +49,10 @@ def _load():
     lib.eo_create_block.argtypes = [i64, i32, i64, i64, dbl, ctypes.c_int]
     lib.eo_block_row_length.restype = i64
     lib.eo_block_row_length.argtypes = [i64, i64, i64]
+    lib.eo_create_ggt.restype = vp
+    lib.eo_create_ggt.argtypes = [i64, i32, i64, dbl, ctypes.c_int, i64]
+    lib.eo_jacobi_eigh.restype = ctypes.c_int
+    lib.eo_jacobi_eigh.argtypes = [vp, i32, vp, vp]
     lib.eo_bf16_round.restype = ctypes.c_float
     lib.eo_bf16_round.argtypes = [ctypes.c_float]
     lib.eo_destroy.restype = None
@@ -114,6 +118,17 @@ def coefficients(S: np.ndarray, q: np.ndarray, m: int, lam: float) -> np.ndarray
     return coef
 
 
+def jacobi_eigh(A: np.ndarray):
+    """Eigenvalues and eigenvectors (columns) of a symmetric matrix, cyclic Jacobi."""
+    A = np.array(A, dtype=np.float64, order="C", copy=True)
+    n = A.shape[0]
+    assert A.shape == (n, n)
+    lam = np.empty(n)
+    V = np.empty((n, n))
+    _load().eo_jacobi_eigh(_ptr(A), n, _ptr(lam), _ptr(V))
+    return lam, V
+
+
 def bf16_round(a: float) -> float:
     """fp32 -> bfloat16 (nearest even) -> fp32, as the oracle stores values."""
     return float(_load().eo_bf16_round(ctypes.c_float(a)))
@@ -132,17 +147,26 @@ def param_update(theta: np.ndarray, u: np.ndarray, lr: float, weight_decay: floa
 class Oracle:
     """State of the oracle: error feedback e, window G=(I,V), Gram matrix S."""
 
-    def __init__(self, d: int, m: int, k: int, lam: float, values_bf16: bool = False, block: int = 0):
+    def __init__(self, d: int, m: int, k: int, lam: float, values_bf16: bool = False, block: int = 0,
+                 ggt: bool = False):
         """block = 0: global Top-k of k entries.  block = B > 0: Top-k applied in
         blocks of B coordinates, k entries kept per full block; self.k is then
-        the resulting row length."""
+        the resulting row length.  ggt: Sparse GGT instead of Sparse M-FAC, `lam`
+        is then its epsilon."""
         self._lib = _load()
         self.d, self.m, self.lam = int(d), int(m), float(lam)
         self.values_bf16 = bool(values_bf16)
         self.block = int(block)
+        self.ggt = bool(ggt)
         if self.block:
             self.k_per_block = int(k)
             self.k = int(self._lib.eo_block_row_length(self.d, self.block, self.k_per_block))
+        if self.ggt:
+            if not self.block:
+                self.k = int(k)
+            self._st = self._lib.eo_create_ggt(self.d, self.m, int(k), self.lam, int(self.values_bf16),
+                                               self.block)
+        elif self.block:
             self._st = self._lib.eo_create_block(self.d, self.m, self.block, self.k_per_block, self.lam,
                                                  int(self.values_bf16))
         else:

@@ -20,6 +20,7 @@ struct eo_state {
     int values_bf16;    /* stored values are bfloat16 */
     int64_t block;      /* 0: global Top-k; B > 0: Top-k applied in blocks of B coordinates */
     int64_t kb;         /* entries kept per full block (block mode) */
+    int ggt;            /* 0: Sparse M-FAC; 1: Sparse GGT (lambda then holds epsilon) */
     int64_t t;          /* steps done */
     float *e;           /* error feedback xi, d */
     int32_t **idx;      /* m row pointers, NULL until the slot is filled */
@@ -257,10 +258,127 @@ int eo_load_row(eo_state *st, const int32_t *idx, const float *val)
     return insert_row(st, idx, val);
 }
 
+eo_state *eo_create_ggt(int64_t d, int32_t m, int64_t k, double epsilon, int values_bf16,
+                        int64_t block)
+{
+    eo_state *st = block ? eo_create_block(d, m, block, k, epsilon, values_bf16)
+                         : eo_create_fmt(d, m, k, epsilon, values_bf16);
+    if (st) st->ggt = 1;
+    return st;
+}
+
+/* Eigendecomposition of a symmetric n*n matrix by the classical cyclic Jacobi method:
+ * sweep over all (p, q), annihilate a_pq with a plane rotation, repeat until a sweep
+ * rotates nothing.  On return lam holds the eigenvalues and column i of V (V[r*n+i]) the
+ * eigenvector of lam[i]; A is destroyed. */
+int eo_jacobi_eigh(double *A, int32_t n, double *lam, double *V)
+{
+    for (int32_t i = 0; i < n; i++)
+        for (int32_t j = 0; j < n; j++) V[(size_t)i * n + j] = i == j ? 1.0 : 0.0;
+    for (int sweep = 0; sweep < 100; sweep++) {
+        int rotated = 0;
+        for (int32_t p = 0; p < n - 1; p++) {
+            for (int32_t q = p + 1; q < n; q++) {
+                const double apq = A[(size_t)p * n + q];
+                const double app = A[(size_t)p * n + p], aqq = A[(size_t)q * n + q];
+                if (apq == 0.0 || fabs(apq) <= 0x1p-54 * sqrt(fabs(app) * fabs(aqq))) continue;
+                rotated = 1;
+                const double tau = (aqq - app) / (2.0 * apq);
+                const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                const double c = 1.0 / sqrt(1.0 + t * t), sn = t * c;
+                for (int32_t i = 0; i < n; i++) {            /* A <- A J */
+                    const double aip = A[(size_t)i * n + p], aiq = A[(size_t)i * n + q];
+                    A[(size_t)i * n + p] = c * aip - sn * aiq;
+                    A[(size_t)i * n + q] = sn * aip + c * aiq;
+                }
+                for (int32_t j = 0; j < n; j++) {            /* A <- J^T A */
+                    const double apj = A[(size_t)p * n + j], aqj = A[(size_t)q * n + j];
+                    A[(size_t)p * n + j] = c * apj - sn * aqj;
+                    A[(size_t)q * n + j] = sn * apj + c * aqj;
+                }
+                A[(size_t)p * n + q] = A[(size_t)q * n + p] = 0.0;
+                for (int32_t i = 0; i < n; i++) {            /* V <- V J */
+                    const double vip = V[(size_t)i * n + p], viq = V[(size_t)i * n + q];
+                    V[(size_t)i * n + p] = c * vip - sn * viq;
+                    V[(size_t)i * n + q] = sn * vip + c * viq;
+                }
+            }
+        }
+        if (!rotated) break;
+    }
+    for (int32_t i = 0; i < n; i++) lam[i] = A[(size_t)i * n + i];
+    return 0;
+}
+
+/* Sparse GGT direction (Algorithm "Detailed Sparse GGT Implementation"), for the window as it
+ * stands: with G (d x n) holding the stored vectors as columns and G^T G = V Sigma^2 V^T,
+ *   U = G V Sigma^+,   u = x/eps + U [ (Sigma + eps I)^-1 - I/eps ] U^T x,
+ * i.e. u = ((G G^T)^{1/2} + eps I)^-1 x.  Directions with Sigma_i = 0 (up to rounding: Sigma_i^2
+ * <= n * 2^-52 * max Sigma^2) are left out by the pseudo-inverse.  q = G^T x is kept for
+ * inspection; coef is set to the multiples of the stored vectors that u - x/eps consists of,
+ * negated (u = x/eps - sum_r coef_r c_r), so that it reads like eq. (2). */
+static int precondition_ggt(eo_state *st, const float *x, double *y)
+{
+    const int64_t d = st->d, k = st->k;
+    const int32_t m = st->m;
+    const double eps = st->lambda;
+    const int32_t n = eo_filled(st);
+    for (int32_t r = 0; r < m; r++) { st->q[r] = 0.0; st->coef[r] = 0.0; }
+    for (int64_t j = 0; j < d; j++) y[j] = (double)x[j] / eps;
+    if (n == 0) return 0;
+    /* filled slots are 0..n-1 (slot order; the result does not depend on the order) */
+    double *A = malloc((size_t)n * n * sizeof(double));
+    double *V = malloc((size_t)n * n * sizeof(double));
+    double *lam = malloc((size_t)n * sizeof(double));
+    double *U = calloc((size_t)d * n, sizeof(double));
+    double *w = malloc((size_t)n * sizeof(double));
+    if (!A || !V || !lam || !U || !w) { free(A); free(V); free(lam); free(U); free(w); return -1; }
+    for (int32_t a = 0; a < n; a++)
+        for (int32_t b = 0; b < n; b++) A[(size_t)a * n + b] = st->S[(size_t)a * m + b];
+    eo_jacobi_eigh(A, n, lam, V);
+    double lmax = 0.0;
+    for (int32_t i = 0; i < n; i++) if (lam[i] > lmax) lmax = lam[i];
+    /* U = G V Sigma^+ : column i = sum_r c_r V[r][i] / sigma_i */
+    for (int32_t i = 0; i < n; i++) {
+        if (!(lam[i] > (double)n * 0x1p-52 * lmax)) { lam[i] = 0.0; continue; }
+        const double sigma = sqrt(lam[i]);
+        for (int32_t r = 0; r < n; r++) {
+            const double f = V[(size_t)r * n + i] / sigma;
+            for (int64_t p = 0; p < k; p++)
+                U[(size_t)st->idx[r][p] * n + i] += f * (double)st->val[r][p];
+        }
+    }
+    /* w = [ (Sigma + eps)^-1 - 1/eps ] U^T x ;  u = x/eps + U w */
+    for (int32_t i = 0; i < n; i++) {
+        double s = 0.0;
+        for (int64_t j = 0; j < d; j++) s += U[(size_t)j * n + i] * (double)x[j];
+        const double sigma = sqrt(lam[i]);
+        w[i] = lam[i] > 0.0 ? (1.0 / (sigma + eps) - 1.0 / eps) * s : 0.0;
+    }
+    for (int64_t j = 0; j < d; j++) {
+        double s = 0.0;
+        for (int32_t i = 0; i < n; i++) s += U[(size_t)j * n + i] * w[i];
+        y[j] += s;
+    }
+    /* for inspection only: q = G^T x and the equivalent multiples of the stored vectors */
+    for (int32_t r = 0; r < n; r++) {
+        double s = 0.0;
+        for (int64_t p = 0; p < k; p++) s += (double)st->val[r][p] * (double)x[st->idx[r][p]];
+        st->q[r] = s;
+        double c = 0.0;
+        for (int32_t i = 0; i < n; i++)
+            if (lam[i] > 0.0) c += V[(size_t)r * n + i] * w[i] / sqrt(lam[i]);
+        st->coef[r] = -c;
+    }
+    free(A); free(V); free(lam); free(U); free(w);
+    return 0;
+}
+
 /* q_r = <c_r, x>, coefficients in age order, y = x/lambda - sum_r coef_r c_r
  * for the window as it stands. */
 static int precondition(eo_state *st, const float *x, double *y)
 {
+    if (st->ggt) return precondition_ggt(st, x, y);
     const int64_t d = st->d, k = st->k;
     const int32_t m = st->m;
     for (int32_t r = 0; r < m; r++) {

@@ -58,6 +58,18 @@ eo_state *eo_create_block(int64_t d, int32_t m, int64_t block, int64_t kb, doubl
                           int values_bf16);
 int64_t eo_block_row_length(int64_t d, int64_t block, int64_t kb);
 
+/* Sparse GGT instead of Sparse M-FAC on the same error feedback, Top-k and window (Appendix
+ * "Sparse GGT", Algorithm "Detailed Sparse GGT Implementation"): eo_step / eo_step_compressed /
+ * eo_apply then return u = ((G G^T)^{1/2} + epsilon I)^-1 x, G = the stored vectors as columns.
+ * The paper's algorithm preconditions the compressed accumulator (eo_step_compressed).
+ * block = 0: global Top-k of k; block = B: Top-k in blocks of B, k per block. */
+eo_state *eo_create_ggt(int64_t d, int32_t m, int64_t k, double epsilon, int values_bf16,
+                        int64_t block);
+
+/* Symmetric eigendecomposition by cyclic Jacobi: A (n*n, destroyed) = V diag(lam) V^T,
+ * eigenvector i in column i of V (V[r*n+i]). */
+int eo_jacobi_eigh(double *A, int32_t n, double *lam, double *V);
+
 /* Round an fp32 value to bfloat16 (nearest, ties to even), returned as fp32. */
 float eo_bf16_round(float a);
 void eo_destroy(eo_state *st);
