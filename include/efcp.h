@@ -94,6 +94,21 @@ size_t efcp_workspace_bytes_ex(int64_t d, int32_t m, int64_t k, int32_t value_fo
 /* Entries per window row for these arguments; 0 if they are invalid. */
 int64_t efcp_row_length(int64_t d, int64_t k, int32_t topk_block);
 
+/* Sparse GGT instead of Sparse M-FAC on the same error feedback, Top-k, window and SP / LCG
+ * kernels (Appendix "Sparse GGT", Algorithm "Detailed Sparse GGT Implementation"): every step
+ * and efcp_apply then produce u = ((G G^T)^{1/2} + epsilon I)^-1 x, G = the stored vectors as
+ * columns, through the eigendecomposition of the m x m matrix G^T G (a Jacobi method in one
+ * workgroup; directions with a zero singular value are left out).  The paper's algorithm
+ * preconditions the compressed accumulator: efcp_step_ex with EFCP_X_COMPRESSED.
+ *   m        1 <= m <= 128 (the matrix is diagonalised in LDS)
+ *   epsilon  finite, > 0
+ * Other arguments as efcp_create_ex.  efcp_get_small then reports S = G^T G, q = G^T x and
+ * the multiples coef with u = x/epsilon - sum_r coef_r c_r. */
+int efcp_create_ggt(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double epsilon,
+                    int32_t value_format, int32_t topk_block, void *workspace, size_t workspace_bytes);
+size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_format,
+                                int32_t topk_block);
+
 /* One step (see the top of this file).
  *   grad    device, d floats, 16-byte aligned, read only
  *   out     device, d floats, 16-byte aligned, receives F^-1 grad; must not

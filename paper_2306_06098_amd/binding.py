@@ -20,7 +20,7 @@ VALUES_FP32, VALUES_BF16 = 0, 1
 
 EXPORTS = (
     "efcp_workspace_bytes", "efcp_workspace_bytes_fmt", "efcp_create", "efcp_create_fmt", "efcp_create_ex",
-    "efcp_workspace_bytes_ex", "efcp_row_length", "efcp_step", "efcp_step_ex", "efcp_apply",
+    "efcp_workspace_bytes_ex", "efcp_row_length", "efcp_create_ggt", "efcp_workspace_bytes_ggt", "efcp_step", "efcp_step_ex", "efcp_apply",
     "efcp_destroy", "efcp_get_row",
     "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
@@ -60,6 +60,10 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_create_ex.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, i32, i32, vp, ctypes.c_size_t]
     lib.efcp_workspace_bytes_ex.restype = ctypes.c_size_t
     lib.efcp_workspace_bytes_ex.argtypes = [i64, i32, i64, i32, i32]
+    lib.efcp_create_ggt.restype = ctypes.c_int
+    lib.efcp_create_ggt.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, i32, i32, vp, ctypes.c_size_t]
+    lib.efcp_workspace_bytes_ggt.restype = ctypes.c_size_t
+    lib.efcp_workspace_bytes_ggt.argtypes = [i64, i32, i64, i32, i32]
     lib.efcp_row_length.restype = i64
     lib.efcp_row_length.argtypes = [i64, i64, i32]
     lib.efcp_step.restype = ctypes.c_int
@@ -97,18 +101,21 @@ def load_library() -> ctypes.CDLL:
 TOPK_BLOCK = 16384      # EFCP_TOPK_BLOCK
 
 
-def efcp_workspace_bytes(d: int, m: int, k: int, values: int = VALUES_FP32, topk_block: int = 0) -> int:
-    return int(load_library().efcp_workspace_bytes_ex(d, m, k, values, topk_block))
+def efcp_workspace_bytes(d: int, m: int, k: int, values: int = VALUES_FP32, topk_block: int = 0,
+                         ggt: bool = False) -> int:
+    fn = load_library().efcp_workspace_bytes_ggt if ggt else load_library().efcp_workspace_bytes_ex
+    return int(fn(d, m, k, values, topk_block))
 
 
 class Efcp:
     """One libefcp context: efcp_create / efcp_step / efcp_destroy."""
 
     def __init__(self, d: int, m: int, k: int, lam: float, workspace=None, values: int = VALUES_FP32,
-                 topk_block: int = 0):
+                 topk_block: int = 0, ggt: bool = False):
         """topk_block = 0: global Top-k of k entries; TOPK_BLOCK: Top-k applied in
         blocks of that many coordinates, k entries per block (self.k is then the
-        resulting row length, self.k_arg what was passed)."""
+        resulting row length, self.k_arg what was passed).  ggt: Sparse GGT
+        (efcp_create_ggt), `lam` is then its epsilon and m <= 128."""
         self._lib = load_library()
         self.d, self.m, self.lam = int(d), int(m), float(lam)
         self.k_arg, self.topk_block = int(k), int(topk_block)
@@ -119,8 +126,9 @@ class Efcp:
         ws_ptr, ws_bytes = None, 0
         if workspace is not None:
             ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-        rc = self._lib.efcp_create_ex(ctypes.byref(self._ctx), self.d, self.m, self.k_arg, self.lam,
-                                      self.values, self.topk_block, ws_ptr, ws_bytes)
+        create = self._lib.efcp_create_ggt if ggt else self._lib.efcp_create_ex
+        rc = create(ctypes.byref(self._ctx), self.d, self.m, self.k_arg, self.lam,
+                    self.values, self.topk_block, ws_ptr, ws_bytes)
         if rc != EFCP_OK:
             self._ctx = ctypes.c_void_p()
             raise EfcpError(rc, "efcp_create failed")

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libefcp.so")
-SOURCES = ["efcp.hip", "select.hip", "blocktopk.hip", "sp.hip", "coef.hip", "lcg.hip"]
+SOURCES = ["efcp.hip", "select.hip", "blocktopk.hip", "sp.hip", "coef.hip", "ggt.hip", "lcg.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

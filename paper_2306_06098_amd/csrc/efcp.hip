@@ -29,9 +29,11 @@ int64_t block_row_length(int64_t d, int64_t kb)
 }
 
 // k_in: entries per row (topk_block == 0) or per block of kCandBlock coordinates.
-bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk_block, Geometry &g,
-                   const char **why)
+bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk_block, int32_t ggt,
+                   Geometry &g, const char **why)
 {
+    g.ggt = ggt ? 1 : 0;
+    if (ggt && m > kGgtMaxM) { *why = "Sparse GGT: m out of range [1, 128]"; return false; }
     if (fmt != kFmtF32 && fmt != kFmtBf16) { *why = "unknown value format"; return false; }
     if (d < 1 || d >= ((int64_t)1 << 31)) { *why = "d out of range [1, 2^31)"; return false; }
     if (m < 1 || m > kMaxM) { *why = "m out of range [1, 1024]"; return false; }
@@ -75,7 +77,8 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
 
 struct Layout {
     size_t e, ring_idx, ring_val, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
-        cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, total;
+        cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
+        n_stages, total;
     size_t small_begin;      // everything from here on is small and zero-initialised
 };
 
@@ -95,7 +98,7 @@ Layout make_layout(const Geometry &g)
     l.e = take((size_t)g.d * sizeof(float));
     l.offT = take((size_t)(g.n_slices + 1) * g.m * sizeof(int32_t));
     l.S = take((size_t)g.m * g.m * sizeof(double));
-    l.W = take((size_t)g.m * g.ldm * sizeof(double));
+    l.W = take(g.ggt ? 0 : (size_t)g.m * g.ldm * sizeof(double));
     l.sq = take((size_t)g.m * sizeof(double2));
     l.zw = take((size_t)g.m * sizeof(double2));
     l.q = take((size_t)g.m * sizeof(double));
@@ -110,6 +113,9 @@ Layout make_layout(const Geometry &g)
     l.cand_cnt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
     l.blk_max = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
     l.blk_tlo = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
+    l.lam = take(g.ggt ? (size_t)g.m * sizeof(double) : 0);
+    l.rot = take(g.ggt ? (size_t)kGgtMaxSweeps * (kGgtMaxM - 1) * 64 * sizeof(double2) : 0);
+    l.n_stages = take(g.ggt ? 256 : 0);
     l.status = take(256);
     l.total = o;
     return l;
@@ -144,13 +150,25 @@ static int fail(efcp_ctx *ctx, int code, const char *msg)
     return code;
 }
 
-extern "C" size_t efcp_workspace_bytes_ex(int64_t d, int32_t m, int64_t k, int32_t value_format,
-                                          int32_t topk_block)
+static size_t workspace_bytes(int64_t d, int32_t m, int64_t k, int32_t value_format, int32_t topk_block,
+                              int32_t ggt)
 {
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, value_format, topk_block, g, &why)) return 0;
+    if (!make_geometry(d, m, k, value_format, topk_block, ggt, g, &why)) return 0;
     return make_layout(g).total;
+}
+
+extern "C" size_t efcp_workspace_bytes_ex(int64_t d, int32_t m, int64_t k, int32_t value_format,
+                                          int32_t topk_block)
+{
+    return workspace_bytes(d, m, k, value_format, topk_block, 0);
+}
+
+extern "C" size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_format,
+                                           int32_t topk_block)
+{
+    return workspace_bytes(d, m, k, value_format, topk_block, 1);
 }
 
 extern "C" size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int32_t value_format)
@@ -182,16 +200,32 @@ extern "C" int efcp_create_fmt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, 
     return efcp_create_ex(out, d, m, k, lambda, value_format, 0, workspace, workspace_bytes);
 }
 
+static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda, int32_t value_format,
+                       int32_t topk_block, int32_t ggt, void *workspace, size_t workspace_bytes);
+
 extern "C" int efcp_create_ex(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
                               int32_t value_format, int32_t topk_block, void *workspace,
                               size_t workspace_bytes)
+{
+    return create_impl(out, d, m, k, lambda, value_format, topk_block, 0, workspace, workspace_bytes);
+}
+
+extern "C" int efcp_create_ggt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double epsilon,
+                               int32_t value_format, int32_t topk_block, void *workspace,
+                               size_t workspace_bytes)
+{
+    return create_impl(out, d, m, k, epsilon, value_format, topk_block, 1, workspace, workspace_bytes);
+}
+
+static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda, int32_t value_format,
+                       int32_t topk_block, int32_t ggt, void *workspace, size_t workspace_bytes)
 {
     if (!out) return EFCP_EINVAL;
     *out = nullptr;
     if (!(lambda > 0.0) || !std::isfinite(lambda)) return EFCP_EINVAL;
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, value_format, topk_block, g, &why)) return EFCP_EINVAL;
+    if (!make_geometry(d, m, k, value_format, topk_block, ggt, g, &why)) return EFCP_EINVAL;
     const Layout l = make_layout(g);
 
     efcp_ctx *ctx = new (std::nothrow) efcp_ctx();
@@ -249,6 +283,9 @@ extern "C" int efcp_create_ex(efcp_ctx **out, int64_t d, int32_t m, int64_t k, d
     p.cand_cnt = reinterpret_cast<uint32_t *>(b + l.cand_cnt);
     p.blk_max = reinterpret_cast<uint32_t *>(b + l.blk_max);
     p.blk_tlo = reinterpret_cast<uint32_t *>(b + l.blk_tlo);
+    p.lam = reinterpret_cast<double *>(b + l.lam);
+    p.rot = reinterpret_cast<double2 *>(b + l.rot);
+    p.n_stages = reinterpret_cast<int32_t *>(b + l.n_stages);
     p.status = reinterpret_cast<uint32_t *>(b + l.status);
 
     // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.
@@ -261,6 +298,7 @@ extern "C" int efcp_create_ex(efcp_ctx **out, int64_t d, int32_t m, int64_t k, d
     if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
     if (rc == hipSuccess) rc = configure_sp(g);
     if (rc == hipSuccess) rc = configure_lcg(g);
+    if (rc == hipSuccess && g.ggt) rc = configure_ggt();
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) {
         (void)hipGetLastError();
@@ -308,7 +346,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     const int64_t t = ctx->t + 1;
     const int32_t slot = (int32_t)((t - 1) % g.m);
     const int32_t n_filled = (int32_t)(t < g.m ? t : g.m);
-    const int32_t evict = t > g.m ? 1 : 0;
+    const int32_t evict = (t > g.m && !g.ggt) ? 1 : 0;      // Sparse GGT keeps no factor to update
     const bool x_is_row = x_source == EFCP_X_COMPRESSED;
 
     hipEvent_t *ev = nullptr;
@@ -339,7 +377,9 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     mark(4);
     if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
     if (evict && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);      // join
-    if (rc == hipSuccess) rc = launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
+    if (rc == hipSuccess)
+        rc = g.ggt ? launch_ggt_step(g, p, n_filled, slot, ctx->lambda, stream)
+                   : launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
     mark(5);
     if (rc == hipSuccess && dst) {
         LcgMode md;
@@ -378,7 +418,9 @@ extern "C" int efcp_apply(efcp_ctx *ctx, const float *x, float *outp, void *stre
     if (n_filled > 0) {
         if (rc == hipSuccess) rc = launch_sp(g, p, x, n_filled, 0, 2, stream);
         if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
-        if (rc == hipSuccess) rc = launch_coef_apply(g, p, ctx->lambda, stream);
+        if (rc == hipSuccess)
+            rc = g.ggt ? launch_ggt_apply(g, p, n_filled, ctx->lambda, stream)
+                       : launch_coef_apply(g, p, ctx->lambda, stream);
     }
     if (rc == hipSuccess) rc = launch_lcg(g, p, x, outp, n_filled, ctx->lambda, LcgMode{}, stream);
     ctx->last_stream = stream;
@@ -488,7 +530,7 @@ struct StateHeader {
     double lambda;
     uint32_t t_lo, status;
     int32_t filled, fmt;
-    int32_t kb, reserved;
+    int32_t kb, ggt;
 };
 constexpr uint64_t kStateMagic = 0x3230545350434645ull;
 
@@ -498,8 +540,8 @@ size_t state_bytes(const efcp_ctx *ctx)
     const size_t filled = (size_t)(ctx->t < g.m ? ctx->t : g.m);
     const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
     return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * 2 * esz +
-           (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 + (size_t)g.m * g.ldm * 8 +
-           (size_t)g.m * 4;
+           (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 +
+           (g.ggt ? 0 : (size_t)g.m * g.ldm * 8) + (size_t)g.m * 4;
 }
 
 }  // namespace
@@ -527,6 +569,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     h.filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
     h.fmt = g.fmt;
     h.kb = g.kb;
+    h.ggt = g.ggt;
     const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
     unsigned char *o = static_cast<unsigned char *>(host_buf);
     std::memcpy(o, &h, sizeof h);
@@ -543,7 +586,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     }
     pull(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     pull(p.S, (size_t)g.m * g.m * 8);
-    pull(p.W, (size_t)g.m * g.ldm * 8);
+    if (!g.ggt) pull(p.W, (size_t)g.m * g.ldm * 8);
     pull(p.rowmax, (size_t)g.m * 4);
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to host failed");
     return EFCP_OK;
@@ -558,7 +601,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     const Geometry &g = ctx->g;
     if (h.magic != kStateMagic || h.d != g.d || h.k != g.k || h.m != g.m || h.row_stride != g.row_stride ||
         h.ldm != g.ldm || h.slice != g.slice || h.n_slices != g.n_slices || h.lambda != ctx->lambda ||
-        h.fmt != g.fmt || h.kb != g.kb ||
+        h.fmt != g.fmt || h.kb != g.kb || h.ggt != g.ggt ||
         h.t < 0 || h.filled != (int32_t)(h.t < g.m ? h.t : g.m))
         return fail(ctx, EFCP_EINVAL, "state does not belong to a context of this shape");
     const int64_t t_keep = ctx->t;
@@ -583,7 +626,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     }
     push(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     push(p.S, (size_t)g.m * g.m * 8);
-    push(p.W, (size_t)g.m * g.ldm * 8);
+    if (!g.ggt) push(p.W, (size_t)g.m * g.ldm * 8);
     push(p.rowmax, (size_t)g.m * 4);
     SelState st{};
     st.t_lo = h.t_lo;
@@ -592,6 +635,8 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, kBins1 * sizeof(uint32_t));
     // where each block starts counting is a hint only: start from "count everything"
     if (rc == hipSuccess && g.kb) rc = hipMemset(p.blk_tlo, 0, (size_t)g.n_slices * sizeof(uint32_t));
+    // Sparse GGT: the decomposition that efcp_apply replays is rebuilt from the imported S
+    if (rc == hipSuccess && g.ggt && h.filled > 0) rc = launch_ggt_refresh(g, p, h.filled, nullptr);
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
     return EFCP_OK;

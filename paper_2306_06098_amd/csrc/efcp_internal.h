@@ -37,6 +37,8 @@ constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
 constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
 constexpr int kHistPriv = 128;       // private histograms of the candidate passes
+constexpr int kGgtMaxM = 128;        // largest window of the Sparse GGT path (its matrix lives in LDS)
+constexpr int kGgtMaxSweeps = 30;    // Jacobi sweeps at most (a sweep without rotations ends earlier)
 
 // Window entry formats.  EPL = entries one 16-byte load brings per array; a chunk is what
 // a 16-lane group reads with one load per array; kBatch = chunks a lane keeps in flight.
@@ -101,6 +103,7 @@ enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
 struct Geometry {
     int64_t d, k, row_stride;
     int32_t kb;              // 0: global Top-k; > 0: Top-k in blocks, entries kept per full block
+    int32_t ggt;             // 0: Sparse M-FAC coefficients; 1: Sparse GGT
     int32_t m, ldm;
     int32_t fmt;             // kFmtF32 / kFmtBf16
     int32_t slice, slice_log2, n_slices;
@@ -126,6 +129,9 @@ struct DevicePtrs {
     uint32_t *cand_cnt;      // [n_sel_blocks] entries used per segment
     uint32_t *blk_max;       // [n_slices] largest key per block          (block-wise Top-k only)
     uint32_t *blk_tlo;       // [n_slices] where each block's first histogram starts counting
+    double *lam;             // [m] eigenvalues of S                      (Sparse GGT only)
+    double2 *rot;            // [kGgtMaxSweeps*(kGgtMaxM-1)][64] logged rotations (c, s)
+    int32_t *n_stages;       // stages logged by the last decomposition
     uint32_t *status;
 };
 
@@ -144,6 +150,12 @@ hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled,
                        int32_t evict, double lambda, hipStream_t stream);
 // Coefficients for an arbitrary x on the window as it stands (nothing is inserted).
 hipError_t launch_coef_apply(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream);
+hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot, double eps,
+                           hipStream_t stream);
+hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, int32_t n_filled, double eps,
+                            hipStream_t stream);
+hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
+hipError_t configure_ggt();
 struct LcgMode {
     int32_t x_row = -1;      // >= 0: x is this window row (the dense pointer is not read)
     bool update = false;     // out holds parameters: theta <- decay*theta - lr*(F^-1 x)

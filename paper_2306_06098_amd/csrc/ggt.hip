@@ -1,0 +1,236 @@
+// ggt.hip -- the m x m part of Sparse GGT (Appendix "Sparse GGT", Algorithm "Detailed Sparse GGT
+// Implementation"): with G the stored vectors as columns and G^T G = V Sigma^2 V^T,
+//   u = x/eps + U [ (Sigma + eps I)^-1 - I/eps ] U^T x,   U = G V Sigma^+,
+// which in terms of q = G^T x (the SP pass) is  u = x/eps - sum_r coef_r c_r  with
+//   coef = V diag( 1 / (eps sigma_i (sigma_i + eps)) ) V^T q      (sigma_i = 0 left out),
+// so the SP and LCG passes of Sparse M-FAC serve unchanged and only the coefficients differ.
+//
+// The eigendecomposition is a parallel two-sided Jacobi method in one workgroup: the matrix lives
+// in LDS, every stage applies n/2 disjoint plane rotations chosen by a round-robin schedule, and
+// a sweep is n-1 stages.  V is never formed: the rotations are logged, V^T q is the log applied
+// forwards to q and V z the log applied backwards, each rotation touching two numbers.  A later
+// efcp_apply on the same window replays the log with its own q.
+#include "efcp_internal.h"
+
+namespace efcp {
+
+namespace {
+
+constexpr int kGgtLd = kGgtMaxM + 1;          // padded row length of the matrix in LDS
+
+// Pair j of stage r in a round-robin over N (even) players: everybody meets everybody once in
+// N-1 stages.  Returns p < q.
+__device__ __forceinline__ void rr_pair(int32_t N, int32_t r, int32_t j, int32_t &p, int32_t &q)
+{
+    int32_t a, b;
+    if (j == 0) {
+        a = N - 1;
+        b = r;
+    } else {
+        a = (r + j) % (N - 1);
+        b = (r - j + (N - 1)) % (N - 1);
+    }
+    p = a < b ? a : b;
+    q = a < b ? b : a;
+}
+
+}  // namespace
+
+// One workgroup of 1024 threads.  update != 0: first write the new Gram row and column (sq[].y)
+// into S and q (sq[].x) into q_out.  Then diagonalise S[0..n)[0..n).  Outputs: lam[m]
+// (eigenvalues, 0 beyond n), the rotation log rot[stage][64] = (c, s) and *n_stages.
+__global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t slot, int32_t update,
+                                                  double *__restrict__ S, const double2 *__restrict__ sq,
+                                                  double *__restrict__ q_out, double *__restrict__ lam,
+                                                  double2 *__restrict__ rot, int32_t *__restrict__ n_stages,
+                                                  int32_t max_sweeps)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *A = reinterpret_cast<double *>(smem);                          // [kGgtMaxM][kGgtLd]
+    double2 *cs = reinterpret_cast<double2 *>(A + kGgtMaxM * kGgtLd);      // [64]
+    int32_t *pp = reinterpret_cast<int32_t *>(cs + 64);                    // [64]
+    int32_t *qq = pp + 64;                                                 // [64]
+    int32_t *n_rot = qq + 64;                                              // [1]
+
+    const int tid = threadIdx.x;
+    if (update) {
+        if (tid < m) {
+            const double2 t = sq[tid];
+            S[(int64_t)slot * m + tid] = t.y;
+            S[(int64_t)tid * m + slot] = t.y;
+            q_out[tid] = t.x;
+        }
+        __syncthreads();                      // the row and column are read back below
+    }
+    const int32_t N = (n + 1) & ~1;           // even; index n is a dummy player when n is odd
+    const int32_t half = N >> 1;
+    for (int32_t e = tid; e < kGgtMaxM * kGgtLd; e += 1024) {
+        const int32_t i = e / kGgtLd, j = e - i * kGgtLd;
+        A[e] = (i < n && j < n) ? S[(int64_t)i * m + j] : 0.0;
+    }
+    if (tid == 0) *n_rot = 0;
+    __syncthreads();
+
+    int32_t stage_out = 0;
+    for (int32_t sweep = 0; sweep < max_sweeps; sweep++) {
+        for (int32_t r = 0; r < N - 1; r++) {
+            if (tid < 64) {
+                double c = 1.0, s = 0.0;
+                int32_t p = 0, q = 0;
+                if (tid < half) {
+                    rr_pair(N, r, tid, p, q);
+                    if (q < n) {
+                        const double apq = A[p * kGgtLd + q];
+                        const double app = A[p * kGgtLd + p], aqq = A[q * kGgtLd + q];
+                        if (apq != 0.0 && fabs(apq) > 0x1p-54 * sqrt(fabs(app) * fabs(aqq))) {
+                            const double tau = (aqq - app) / (2.0 * apq);
+                            const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                            c = 1.0 / sqrt(1.0 + t * t);
+                            s = t * c;
+                            atomicAdd(n_rot, 1);
+                        }
+                    }
+                }
+                pp[tid] = p;
+                qq[tid] = q;
+                cs[tid] = make_double2(c, s);
+                rot[(int64_t)stage_out * 64 + tid] = make_double2(c, s);
+            }
+            __syncthreads();
+            // A <- J^T A J, one 2x2 block per (row pair, column pair); all blocks are disjoint
+            for (int32_t b = tid; b < half * half; b += 1024) {
+                const int32_t k1 = b / half, k2 = b - k1 * half;
+                const int32_t p1 = pp[k1], q1 = qq[k1], p2 = pp[k2], q2 = qq[k2];
+                const double2 r1 = cs[k1], r2 = cs[k2];
+                const double b00 = A[p1 * kGgtLd + p2], b01 = A[p1 * kGgtLd + q2];
+                const double b10 = A[q1 * kGgtLd + p2], b11 = A[q1 * kGgtLd + q2];
+                const double t00 = r2.x * b00 - r2.y * b01, t01 = r2.y * b00 + r2.x * b01;
+                const double t10 = r2.x * b10 - r2.y * b11, t11 = r2.y * b10 + r2.x * b11;
+                double n00 = r1.x * t00 - r1.y * t10, n01 = r1.x * t01 - r1.y * t11;
+                double n10 = r1.y * t00 + r1.x * t10, n11 = r1.y * t01 + r1.x * t11;
+                if (k1 == k2 && r1.y != 0.0) { n01 = 0.0; n10 = 0.0; }      // the annihilated entry
+                A[p1 * kGgtLd + p2] = n00;
+                A[p1 * kGgtLd + q2] = n01;
+                A[q1 * kGgtLd + p2] = n10;
+                A[q1 * kGgtLd + q2] = n11;
+            }
+            __syncthreads();
+            stage_out++;
+        }
+        const int32_t done = *n_rot == 0;     // read by all before it is cleared
+        __syncthreads();
+        if (tid == 0) *n_rot = 0;
+        __syncthreads();
+        if (done) break;                      // uniform: a whole sweep without a rotation
+    }
+    if (tid < m) lam[tid] = tid < n ? A[tid * kGgtLd + tid] : 0.0;
+    if (tid == 0) *n_stages = stage_out;
+}
+
+// One wave.  y = V^T q by the logged rotations in order, z_i = y_i / (eps sigma_i (sigma_i + eps)),
+// coef = V z by the log backwards.  q is sq[].x; coef of slots >= n is 0.
+__global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, int32_t n, double eps,
+                                                 const double2 *__restrict__ sq,
+                                                 const double *__restrict__ lam,
+                                                 const double2 *__restrict__ rot,
+                                                 const int32_t *__restrict__ n_stages,
+                                                 double *__restrict__ q_out, double *__restrict__ coef_out)
+{
+    __shared__ double y[kGgtMaxM + 2];
+    const int lane = threadIdx.x;
+    const int32_t N = (n + 1) & ~1, half = N >> 1;
+    const int32_t stages = *n_stages;
+    double lmax = 0.0;
+    for (int32_t i = lane; i < kGgtMaxM + 2; i += 64) {
+        const double qi = i < n ? sq[i].x : 0.0;
+        y[i] = qi;
+        if (i < m) q_out[i] = i < n ? qi : 0.0;
+        if (i < n) lmax = fmax(lmax, lam[i]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lmax = fmax(lmax, __shfl_xor(lmax, o, 64));
+    __syncthreads();
+
+    int32_t r = 0;
+    double2 nxt = stages > 0 ? rot[lane] : make_double2(1.0, 0.0);
+    for (int32_t st = 0; st < stages; st++) {
+        const double2 cur = nxt;
+        if (st + 1 < stages) nxt = rot[(int64_t)(st + 1) * 64 + lane];
+        if (lane < half && cur.y != 0.0) {
+            int32_t p, q;
+            rr_pair(N, r, lane, p, q);
+            const double yp = y[p], yq = y[q];
+            y[p] = cur.x * yp - cur.y * yq;
+            y[q] = cur.y * yp + cur.x * yq;
+        }
+        __syncthreads();
+        r = r + 1 == N - 1 ? 0 : r + 1;
+    }
+    const double cut = (double)n * 0x1p-52 * lmax;
+    for (int32_t i = lane; i < n; i += 64) {
+        const double l = lam[i];
+        double z = 0.0;
+        if (l > cut) {
+            const double sg = sqrt(l);
+            z = y[i] / (eps * sg * (sg + eps));
+        }
+        y[i] = z;
+    }
+    __syncthreads();
+    // backwards: stage st used r = st mod (N-1)
+    nxt = stages > 0 ? rot[(int64_t)(stages - 1) * 64 + lane] : make_double2(1.0, 0.0);
+    for (int32_t st = stages - 1; st >= 0; st--) {
+        const double2 cur = nxt;
+        if (st > 0) nxt = rot[(int64_t)(st - 1) * 64 + lane];
+        if (lane < half && cur.y != 0.0) {
+            int32_t p, q;
+            rr_pair(N, st % (N - 1), lane, p, q);
+            const double zp = y[p], zq = y[q];
+            y[p] = cur.x * zp + cur.y * zq;
+            y[q] = -cur.y * zp + cur.x * zq;
+        }
+        __syncthreads();
+    }
+    for (int32_t i = lane; i < m; i += 64) coef_out[i] = i < n ? y[i] : 0.0;
+}
+
+size_t ggt_eig_lds_bytes()
+{
+    return (size_t)kGgtMaxM * kGgtLd * sizeof(double) + 64 * sizeof(double2) + 2 * 64 * sizeof(int32_t) + 16;
+}
+
+hipError_t configure_ggt()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_ggt_eig),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)ggt_eig_lds_bytes());
+}
+
+// Coefficients of the step: new Gram row/column, eigendecomposition, coefficients for q.
+hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot, double eps,
+                           hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, n_filled, slot, 1, p.S,
+                       p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps);
+    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, n_filled, eps, p.sq, p.lam, p.rot,
+                       p.n_stages, p.q, p.coef);
+    return hipGetLastError();
+}
+
+// Decomposition of S as it stands (after a state import), without touching S or q.
+hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, n_filled, 0, 0, p.S,
+                       p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps);
+    return hipGetLastError();
+}
+
+// Coefficients for another x on the window as it stands: the decomposition of the last step is reused.
+hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, int32_t n_filled, double eps,
+                            hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, n_filled, eps, p.sq, p.lam, p.rot,
+                       p.n_stages, p.q, p.coef);
+    return hipGetLastError();
+}
+
+}  // namespace efcp

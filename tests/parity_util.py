@@ -27,7 +27,7 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
                check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False,
-               compressed=False, update=None, apply_every=0, topk_block=0):
+               compressed=False, update=None, apply_every=0, topk_block=0, ggt=False):
     """grads: iterable of float32 numpy arrays.  bf16: the bfloat16 window
     format on both sides.  compressed: the step preconditions c_t instead of
     the gradient.  update=(lr, weight_decay): the step updates a parameter
@@ -36,11 +36,12 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
     each step from the same fp32 parameters.  apply_every=n: after every n-th
     step a seeded random x is applied to the window as it stands on both
     sides (no insertion).  topk_block=B: Top-k applied in blocks of B
-    coordinates on both sides, k entries per block.  Returns dict of worst errors."""
+    coordinates on both sides, k entries per block.  ggt: Sparse GGT on both
+    sides, lam is its epsilon.  Returns dict of worst errors."""
     dev = torch.device("cuda:0")
-    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=topk_block)
+    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=topk_block, ggt=ggt)
     g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
-                         topk_block=topk_block)
+                         topk_block=topk_block, ggt=ggt)
     assert g_gpu.k == o.k, "row length differs"
     e_prev = np.zeros(d, np.float32)
     grad_d = torch.empty(d, dtype=torch.float32, device=dev)

@@ -533,3 +533,82 @@ def test_blockwise_topk_modes_and_checkpoint(env):
             binding.Efcp(d, m, 16_385, lam, topk_block=binding.TOPK_BLOCK)
     finally:
         a.destroy(); b.destroy(); c.destroy()
+
+
+# ---------------------------------------------------------------------------
+# Sparse GGT on the same window (Appendix "Sparse GGT")
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_sparse_ggt_tiny_workload(env, bf16):
+    """d = 65,536, m = 32, k = 655, epsilon = 1e-2: the paper's variant
+    (x = c_t) for 120 steps, with an apply of a random x after every fifth."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["tiny"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, wl.m, wl.k, 1e-2, _stream(wl, 120), bf16=bf16,
+                   ggt=True, compressed=True, apply_every=5)
+    print("tiny ggt", bf16, w)
+    assert w["steps"] == 120 and w["apply"] > 0.0
+
+
+def test_sparse_ggt_resnet20_sized(env):
+    """The paper's GGT setting: d = 272,474 (ResNet-20), m = 100, 1 % density.  The window fills
+    at step 100 and then evicts."""
+    torch, oracle_mod, binding = env
+    wl = synth.WORKLOADS["resnet20"]
+    w = run_parity(torch, oracle_mod, binding, wl.d, 100, wl.k, 1e-3, _stream(wl, 112), ggt=True,
+                   compressed=True, check_error_every=20)
+    print("resnet20 ggt", w)
+
+
+@pytest.mark.parametrize("d,m,k,eps,T,kw", [
+    (20_001, 8, 201, 1e-3, 24, dict()),                         # x = g
+    (20_001, 7, 201, 1e-2, 20, dict(update=(1e-3, 0.05))),      # odd m (dummy player), fused update
+    (4_099, 3, 4_099, 1e-1, 9, dict(compressed=True)),          # k = d
+    (70_000, 128, 40, 1e-2, 140, dict(compressed=True)),        # largest window; fills, then evicts
+    (3, 2, 2, 1e-1, 6, dict()),
+    (100_003, 1, 1000, 1e-3, 5, dict(compressed=True)),         # m = 1
+    (50_000, 6, 100, 1e-2, 14, dict(topk_block=16_384, apply_every=2)),
+])
+def test_sparse_ggt_shapes(env, d, m, k, eps, T, kw):
+    torch, oracle_mod, binding = env
+    w = run_parity(torch, oracle_mod, binding, d, m, k, eps, _edge_grads(d, T, d + m), ggt=True, **kw)
+    print((d, m, k), kw, w)
+
+
+def test_sparse_ggt_duplicate_rows_checkpoint_and_limits(env):
+    """Identical gradients with k = d make G^T G singular (pseudo-inverse path); export/import
+    rebuilds the decomposition that apply replays; m > 128 is refused."""
+    torch, oracle_mod, binding = env
+    d, m, eps = 6_000, 5, 1e-2
+    rng = np.random.default_rng(31)
+    g0 = rng.standard_normal(d).astype(np.float32)
+    grads = [g0, g0, rng.standard_normal(d).astype(np.float32), g0]
+    w = run_parity(torch, oracle_mod, binding, d, m, d, eps, iter(grads), ggt=True, apply_every=1)
+    print("ggt duplicates", w)
+    dev = torch.device("cuda:0")
+    a = binding.Efcp(d, m, 60, eps, ggt=True)
+    b = binding.Efcp(d, m, 60, eps, ggt=True)
+    c = binding.Efcp(d, m, 60, eps)
+    try:
+        out_a, out_b = torch.empty(d, device=dev), torch.empty(d, device=dev)
+        gs = [torch.from_numpy(g).to(dev) for g in _edge_grads(d, 8, 5)]
+        for g in gs[:5]:
+            a.step(g, out_a)
+        blob = a.export_state()
+        with pytest.raises(binding.EfcpError):
+            c.import_state(blob)
+        b.import_state(blob)
+        x = gs[7]
+        a.apply(x, out_a)
+        b.apply(x, out_b)
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, out_b)
+        for g in gs[5:]:
+            a.step(g, out_a)
+            b.step(g, out_b)
+            torch.cuda.synchronize()
+            assert torch.equal(out_a, out_b)
+        with pytest.raises(binding.EfcpError):
+            binding.Efcp(d, 129, 60, eps, ggt=True)
+    finally:
+        a.destroy(); b.destroy(); c.destroy()
