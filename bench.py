@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a torch kernel of known
 # size), full 1024-row window of the bert_base workload:
 # profiles/k_sp_k_lcg_k_ef_hist_bert_base_hbm_counters.txt
-MEASURED_TRAFFIC = {("bert_base", "lcg"): 10.40e9, ("bert_base", "sp"): 9.94e9}
+MEASURED_TRAFFIC = {("bert_base", "lcg"): 10.32e9, ("bert_base", "sp"): 10.02e9}
 METRIC = "Sparse M-FAC EFCP steps/s + achieved HBM GB/s (d=110M, m=1024, 1% density)"
 
 
@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--topk", choices=["global", "block"], default="global",
                     help="global = exact global Top-k (the benchmark's definition); block = Top-k applied "
                          "in blocks of 16,384 coordinates, ceil(16384*k/d) entries per block")
+    ap.add_argument("--precond", choices=["mfac", "ggt"], default="mfac",
+                    help="mfac = Sparse M-FAC (the benchmark's definition); ggt = Sparse GGT on the same "
+                         "window with m = 100 and epsilon = 1e-3 (the paper runs it at the resnet20 size)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -108,16 +111,20 @@ def main():
     from paper_2306_06098_amd import binding, synth
 
     wl = synth.WORKLOADS[args.workload]
+    ggt = args.precond == "ggt"
+    if ggt:
+        import dataclasses
+        wl = dataclasses.replace(wl, m=min(wl.m, 100), lam=1e-3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     bf16 = args.values == "bf16"
     if args.topk == "block":
         kb = -(-binding.TOPK_BLOCK * wl.k // wl.d)
         ctx = binding.Efcp(wl.d, wl.m, kb, wl.lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
-                           topk_block=binding.TOPK_BLOCK)
+                           topk_block=binding.TOPK_BLOCK, ggt=ggt)
     else:
         ctx = binding.Efcp(wl.d, wl.m, wl.k, wl.lam,
-                           values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32)
+                           values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32, ggt=ggt)
     k_row = ctx.k
     stream = synth.TorchGradientStream(wl.d, wl.rho, wl.seed, dev)
     out = torch.empty(wl.d, dtype=torch.float32, device=dev)
@@ -179,7 +186,8 @@ def main():
         "config": {"workload": f"{wl.name}: d={wl.d} m={wl.m} k={k_row} lambda={wl.lam} "
                                f"window rows filled={n}", "fill_steps": fill,
                    "window_format": "bf16 value + u16 in-slice index" if bf16 else "fp32 value + i32 index",
-                   "mode": args.mode, "topk": args.topk},
+                   "mode": args.mode, "topk": args.topk,
+                   "preconditioner": args.precond},
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_step * 1e-3) / 1e9,
         "hbm_frac": by["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -193,7 +201,7 @@ def main():
     ctx.destroy()
     del pool, out, stream
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not ggt:
         result["cpu_baseline"] = cpu_baseline(wl, bf16)
     print(json.dumps(result), flush=True)
 
