@@ -55,7 +55,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
     g.d = d; g.k = k; g.m = m; g.fmt = fmt;
     g.row_stride = (int64_t)align_up((size_t)k, 64);
     g.ldm = (int32_t)align_up((size_t)m, 8);
-    const size_t fixed_sp = 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2) + 2 * 512 * sizeof(int32_t);
+    const size_t fixed_sp = 16 + 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2) + 2 * 512 * sizeof(int32_t);
     const size_t fixed_lcg = 4 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
     const int lg = 14;                             // 16384 coordinates: 128 KiB of the 160 KiB LDS
     if (((size_t)8 << lg) + fixed_sp > (size_t)lds || ((size_t)8 << lg) + fixed_lcg > (size_t)lds) {

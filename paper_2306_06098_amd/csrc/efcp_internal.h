@@ -61,7 +61,8 @@ template <int FMT>
 __device__ __forceinline__ int32_t entry_pos(const int4 &raw, int c, int32_t base, int32_t mask)
 {
     const int32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-    if constexpr (FMT == kFmtF32) return (w[c] - base) & mask;
+    // base is a multiple of the slice width, so masking alone removes it
+    if constexpr (FMT == kFmtF32) return w[c] & mask;
     else return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
 }
 

@@ -39,15 +39,21 @@ __device__ __forceinline__ void lcg_scatter(const int4 &iv, const int4 &vv, int3
                                             double magic, long long magic_bits,
                                             unsigned long long *__restrict__ acc)
 {
+    const uint32_t len = (uint32_t)(p1 - p0);          // pc+q in [p0, p1) as one unsigned compare
+    const uint32_t rel = (uint32_t)(pc - p0);
+    const int32_t magic_hi = (int32_t)(magic_bits >> 32);     // the low word of 1.5 * 2^k is zero
 #pragma unroll
     for (int q = 0; q < Fmt<FMT>::EPL; q++) {
-        const int32_t p = pc + q;
-        if (p >= p0 && p < p1) {
-            const int32_t li = entry_pos<FMT>(iv, q, base, mask);
-            const double t = fma(c, (double)entry_val<FMT>(vv, q), magic);
-            const long long cnt = __double_as_longlong(t) - magic_bits;
-            atomicAdd(&acc[li], (unsigned long long)cnt);
-        }
+        // The arithmetic is done for all lanes, outside the branch, so that the entries of a
+        // chunk overlap; lanes outside the run only sit out the atomic (LDS atomic throughput
+        // is what this kernel runs out of next to HBM, so they must not issue one).
+        const bool ok = rel + (uint32_t)q < len;
+        const int32_t li = entry_pos<FMT>(iv, q, base, mask);
+        const double t = fma(c, (double)entry_val<FMT>(vv, q), magic);
+        const uint32_t lo = (uint32_t)__double2loint(t);
+        uint32_t hi = (uint32_t)(__double2hiint(t) - magic_hi);
+        asm volatile("" : "+v"(hi));          // pins the arithmetic here, subtraction in the high word only
+        if (ok) atomicAdd(&acc[li], ((unsigned long long)hi << 32) | lo);
     }
 }
 
@@ -174,7 +180,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         const int32_t len = FULL ? slice : (int32_t)(d - base64);
         const int32_t snx = it + 1 < sl.count ? sl.at(it + 1) : s;     // this workgroup's next slice
         auto consume = [&](const LcgBatch<FMT> &b) {
-            const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
+            const int32_t hi = b.r < n_filled ? b.p1 : b.p0;       // rows past the end: an empty run
 #pragma unroll
             for (int q = 0; q < kBatch; q++)
                 lcg_scatter<FMT>(b.iv[q], b.vv[q], b.pcs + gl * EPL + q * kChunk, b.p0, hi, base, mask, b.c,

@@ -39,12 +39,15 @@ __device__ __forceinline__ void sp_accumulate(const int4 &iv, const int4 &vv, in
                                               int32_t p1, int32_t base, int32_t mask,
                                               const float2 *__restrict__ xc, double &aq, double &ag)
 {
+    // entry pc+c belongs to the run iff 0 <= pc+c-p0 < p1-p0 (one unsigned compare); an entry
+    // outside gathers the pair of zeros kept behind the slice instead of being zeroed itself
+    const uint32_t len = (uint32_t)(p1 - p0);
+    const uint32_t rel = (uint32_t)(pc - p0);
 #pragma unroll
     for (int c = 0; c < Fmt<FMT>::EPL; c++) {
-        const int32_t p = pc + c;
-        const bool ok = (p >= p0) && (p < p1);
-        const int32_t li = ok ? entry_pos<FMT>(iv, c, base, mask) : 0;
-        const double v = ok ? (double)entry_val<FMT>(vv, c) : 0.0;
+        const bool ok = rel + (uint32_t)c < len;
+        const int32_t li = ok ? entry_pos<FMT>(iv, c, base, mask) : mask + 1;
+        const double v = (double)entry_val<FMT>(vv, c);
         const float2 t = xc[li];
         aq = fma(v, (double)t.x, aq);
         ag = fma(v, (double)t.y, ag);
@@ -85,8 +88,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t slice = 1 << slice_log2;
-    float2 *xc = reinterpret_cast<float2 *>(smem);                 // [slice]: (x_j, c_new_j)
-    double2 *racc = reinterpret_cast<double2 *>(xc + slice);       // [1024] per-row sums
+    float2 *xc = reinterpret_cast<float2 *>(smem);                 // [slice]: (x_j, c_new_j); [slice] = (0, 0)
+    double2 *racc = reinterpret_cast<double2 *>(xc + slice + 2);   // [1024] per-row sums
     int32_t *off0 = reinterpret_cast<int32_t *>(racc + kMaxM);     // [1024]
     int32_t *off1 = off0 + kMaxM;                                  // [1024]
     int32_t *np0 = off1 + kMaxM;                                   // [kMaxSlicesPerWg] newest row's run
@@ -104,6 +107,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int32_t klast = (int32_t)(k - 1);
 
     racc[tid] = make_double2(0.0, 0.0);
+    if (tid == 0) xc[slice] = make_float2(0.0f, 0.0f);             // what entries outside a run gather
     if (sl.count == 0) {                      // uniform: no slice for this workgroup
         if (tid < m) partial[(int64_t)blockIdx.x * m + tid] = make_double2(0.0, 0.0);
         return;
@@ -229,7 +233,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         // ---- stream the rows: two register batches used alternately ----
         auto consume = [&](const RunBatch<FMT> &b) {
             double aq = 0.0, ag = 0.0;
-            const int32_t hi = b.r < n_filled ? b.p1 : 0;          // rows past the end: nothing valid
+            const int32_t hi = b.r < n_filled ? b.p1 : b.p0;       // rows past the end: an empty run
 #pragma unroll
             for (int c = 0; c < kBatch; c++)
                 sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, base, mask,
