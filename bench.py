@@ -9,12 +9,16 @@ FULL 1024-row window: the window is filled with 1024 untimed steps first.
 
 Prints one JSON line:
   value / ms_per_step   steps per second and milliseconds per step, timed over --steps steps
-  step_bytes            algorithmic bytes of one step, 16*n*k + 24*d + 8*k (n rows filled)
+  step_bytes            algorithmic bytes of one step, 16*n*k + 24*d + 8*k (n rows filled): the method's
+                        format, an int32 index and an fp32 value per window entry
   achieved_GBps, hbm_frac   step_bytes / step time, and that over the 8 TB/s HBM peak
+  stored_step_bytes, stored_GBps   the same with the bytes the library really keeps per entry (a 16-bit
+                        in-slice index next to the value): what HBM has to deliver
   kernel_ms             HIP-event time per step of each kernel group (events on the step's stream)
   roofline              the slower of the two window passes (k_sp, k_lcg): algorithmic bytes per
                         launch / HIP-event time per launch, against the HBM peak; `traffic` is the
-                        measured HBM bytes per launch from rocprofv3 counters (full window only)
+                        measured HBM bytes per launch from rocprofv3 counters (full window only);
+                        stored_bytes_per_launch / frac_stored: the same with the stored entry size
   cpu_baseline          the CPU oracle timed on this host on a bounded sample (see its `sample`)
 """
 from __future__ import annotations
@@ -32,13 +36,16 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a torch kernel of known
 # size), full 1024-row window of the bert_base workload:
 # profiles/k_sp_k_lcg_k_ef_hist_bert_base_hbm_counters.txt
-MEASURED_TRAFFIC = {("bert_base", "lcg"): 10.32e9, ("bert_base", "sp"): 10.02e9}
+MEASURED_TRAFFIC = {("bert_base", "lcg"): 7.91e9, ("bert_base", "sp"): 7.54e9}
 METRIC = "Sparse M-FAC EFCP steps/s + achieved HBM GB/s (d=110M, m=1024, 1% density)"
 
 
 def step_bytes(d, k, n, entry=8, mode="grad"):
-    """Algorithmic bytes of one step with n filled rows; entry = bytes per window
-    entry (8: int32 index + fp32 value, 4: 16-bit in-slice index + bf16 value).
+    """Bytes of one step with n filled rows at `entry` bytes per window entry.
+    Algorithmic bytes use the entry of the method's own format: 8 (int32 index +
+    fp32 value; 16*n*k + 24*d + 8*k for the benchmark's step) or 6 (int32 + bf16);
+    stored bytes use what the library keeps in HBM: 6 (16-bit in-slice index +
+    fp32) or 4 (+ bf16).
     mode: "grad" (x = g, F^-1 g written: the benchmark's definition), "compressed"
     (x = c_t: no dense x is read), "update" / "compressed-update" (the parameters
     are read and written instead of F^-1 x being written)."""
@@ -173,7 +180,8 @@ def main():
     assert torch.isfinite(out).all().item()
 
     n = min(sm["step"], wl.m)
-    by = step_bytes(wl.d, k_row, n, 4 if bf16 else 8, args.mode)
+    by = step_bytes(wl.d, k_row, n, 6 if bf16 else 8, args.mode)          # algorithmic
+    st = step_bytes(wl.d, k_row, n, 4 if bf16 else 6, args.mode)          # as stored
     ms_step = (t1 - t0) * 1e3 / args.steps
     per_launch = {kname: ms_groups[kname] / max(covered, 1) for kname in ms_groups}
     dom = "lcg" if per_launch["lcg"] >= per_launch["sp"] else "sp"
@@ -185,18 +193,23 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: d={wl.d} m={wl.m} k={k_row} lambda={wl.lam} "
                                f"window rows filled={n}", "fill_steps": fill,
-                   "window_format": "bf16 value + u16 in-slice index" if bf16 else "fp32 value + i32 index",
+                   "window_format": ("bf16 value" if bf16 else "fp32 value") + " + 16-bit in-slice index "
+                                    "(int32 indices at the interface)",
                    "mode": args.mode, "topk": args.topk,
                    "preconditioner": args.precond},
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_step * 1e-3) / 1e9,
         "hbm_frac": by["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "stored_step_bytes": st["total"],
+        "stored_GBps": st["total"] / (ms_step * 1e-3) / 1e9,
         "kernel_ms": per_launch,
         "roofline": {"bound": "hbm", "kernel": "k_" + dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC.get((wl.name, dom))
                      if (n == wl.m and not bf16 and args.mode == "grad" and args.topk == "global") else None,
-                     "bytes_per_launch": by[dom], "ms_per_launch": per_launch[dom]},
+                     "bytes_per_launch": by[dom], "ms_per_launch": per_launch[dom],
+                     "stored_bytes_per_launch": st[dom],
+                     "frac_stored": st[dom] / (per_launch[dom] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     ctx.destroy()
     del pool, out, stream

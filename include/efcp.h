@@ -11,8 +11,13 @@
  *   c    = TopK(a)                          the k largest |a_j|; ties at the
  *                                           threshold go to the lower index
  *   e    = a - c                            +0 where selected, a_j elsewhere
- *   slot (t-1) mod m of the window <- c     stored as (int32 index, fp32 value),
- *                                           indices ascending, oldest row replaced
+ *   slot (t-1) mod m of the window <- c     (index, fp32 value) pairs, indices
+ *                                           ascending, oldest row replaced.  In memory an
+ *                                           index is its 16-bit position inside the
+ *                                           16384-coordinate slice it falls in (the slice
+ *                                           follows from a per-row offset table): lossless,
+ *                                           6 bytes per entry instead of 8; efcp_get_row
+ *                                           returns plain int32 indices
  *   S[slot][r] = S[r][slot] = <c_r, c>      fp64, every filled row r
  *   q[r] = <c_r, grad>                      fp64 (x = grad is the vector preconditioned)
  *   coef = (1/lambda) (m*lambda*I + S)^-1 q fp64, the coefficients of eq. (2)
@@ -46,11 +51,12 @@ typedef enum {
     EFCP_ENUMERIC = -4  /* the coefficient factorisation met a non-positive pivot */
 } efcp_status;
 
-/* Storage format of the window G = (I, V) (Section "Format for V"). */
+/* Storage format of the values V of the window G = (I, V) (Section "Format for V"); indices are
+ * 16-bit in-slice positions in both. */
 typedef enum {
-    EFCP_VALUES_FP32 = 0,  /* int32 index + fp32 value per entry (8 bytes), the default        */
-    EFCP_VALUES_BF16 = 1   /* bfloat16 value + 16-bit index inside the entry's 16384-coordinate
-                              slice (4 bytes).  c holds bf16(a_j) (round to nearest even) at the
+    EFCP_VALUES_FP32 = 0,  /* fp32 values, exactly a_j (6 bytes per entry), the default          */
+    EFCP_VALUES_BF16 = 1   /* bfloat16 values (4 bytes per entry).
+                              c holds bf16(a_j) (round to nearest even) at the
                               selected positions and, as xi = a - c says, e keeps the rounding
                               remainder a_j - bf16(a_j) there instead of 0.  Selection is still
                               done on the fp32 accumulator.                                     */

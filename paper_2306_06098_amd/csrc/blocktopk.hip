@@ -201,13 +201,12 @@ __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
             float rest = av;
             if (sel) {
                 const uint32_t pos = gtb + min(eqb, quota);
+                irow[pos] = (uint16_t)i;                           // position inside the slice
                 if constexpr (FMT == kFmtF32) {
-                    irow[pos] = (int32_t)(base64 + i);
                     vrow[pos] = av;
                     rest = 0.0f;
                 } else {
                     const uint32_t hb = bf16_bits(av);
-                    irow[pos] = (uint16_t)i;
                     vrow[pos] = (uint16_t)hb;
                     rest = av - __uint_as_float(hb << 16);       // e keeps the rounding remainder
                 }
@@ -257,12 +256,12 @@ hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_block_topk<kFmtBf16>, dim3(g.n_slices), dim3(kBlkThreads), 0, stream, grad, p.e,
                            g.d, g.m, slot, g.row_stride, g.k, g.kb, g.n_slices,
-                           static_cast<uint16_t *>(p.ring_idx), static_cast<uint16_t *>(p.ring_val), p.offT,
+                           p.ring_idx, static_cast<uint16_t *>(p.ring_val), p.offT,
                            p.blk_max, p.blk_tlo);
     else
         hipLaunchKernelGGL(k_block_topk<kFmtF32>, dim3(g.n_slices), dim3(kBlkThreads), 0, stream, grad, p.e,
                            g.d, g.m, slot, g.row_stride, g.k, g.kb, g.n_slices,
-                           static_cast<int32_t *>(p.ring_idx), static_cast<float *>(p.ring_val), p.offT,
+                           p.ring_idx, static_cast<float *>(p.ring_val), p.offT,
                            p.blk_max, p.blk_tlo);
     hipLaunchKernelGGL(k_block_finish, dim3(1), dim3(1024), 0, stream, p.blk_max, g.n_slices,
                        p.rowmax + slot, p.sel);

@@ -75,6 +75,8 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
     return true;
 }
 
+size_t value_bytes(const Geometry &g) { return g.fmt == kFmtBf16 ? 2 : 4; }
+
 struct Layout {
     size_t e, ring_idx, ring_val, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
         cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
@@ -87,9 +89,8 @@ Layout make_layout(const Geometry &g)
     Layout l{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;          // bytes per index and per value
-    l.ring_idx = take((size_t)g.m * g.row_stride * esz);
-    l.ring_val = take((size_t)g.m * g.row_stride * esz);
+    l.ring_idx = take((size_t)g.m * g.row_stride * sizeof(uint16_t));
+    l.ring_val = take((size_t)g.m * g.row_stride * value_bytes(g));
     l.partial = take((size_t)g.sp_grid * g.m * sizeof(double2));
     // candidate lists exist for the global Top-k only
     l.cand_idx = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
@@ -259,7 +260,7 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     unsigned char *b = static_cast<unsigned char *>(ctx->ws);
     DevicePtrs &p = ctx->p;
     p.e = reinterpret_cast<float *>(b + l.e);
-    p.ring_idx = b + l.ring_idx;
+    p.ring_idx = reinterpret_cast<uint16_t *>(b + l.ring_idx);
     p.ring_val = b + l.ring_val;
     p.offT = reinterpret_cast<int32_t *>(b + l.offT);
     p.S = reinterpret_cast<double *>(b + l.S);
@@ -457,21 +458,10 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
     if (slot < 0 || slot >= filled) return fail(ctx, EFCP_EINVAL, "slot not filled");
     if (int rc = sync_last(ctx)) return rc;
     const size_t off = (size_t)slot * g.row_stride;
-    if (g.fmt == kFmtF32) {
-        if (hipMemcpy(idx_host, static_cast<int32_t *>(ctx->p.ring_idx) + off, (size_t)g.k * 4,
-                      hipMemcpyDeviceToHost) != hipSuccess ||
-            hipMemcpy(val_host, static_cast<float *>(ctx->p.ring_val) + off, (size_t)g.k * 4,
-                      hipMemcpyDeviceToHost) != hipSuccess)
-            return fail(ctx, EFCP_EHIP, "copy to host failed");
-        return EFCP_OK;
-    }
-    // bfloat16 format: 16-bit in-slice indices become absolute with the row's slice offsets
-    std::vector<uint16_t> i16((size_t)g.k), v16((size_t)g.k);
+    // 16-bit in-slice indices become absolute with the row's slice offsets
+    std::vector<uint16_t> i16((size_t)g.k);
     std::vector<int32_t> offs((size_t)g.n_slices + 1);
-    if (hipMemcpy(i16.data(), static_cast<uint16_t *>(ctx->p.ring_idx) + off, (size_t)g.k * 2,
-                  hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(v16.data(), static_cast<uint16_t *>(ctx->p.ring_val) + off, (size_t)g.k * 2,
-                  hipMemcpyDeviceToHost) != hipSuccess ||
+    if (hipMemcpy(i16.data(), ctx->p.ring_idx + off, (size_t)g.k * 2, hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy2D(offs.data(), sizeof(int32_t), ctx->p.offT + slot, (size_t)g.m * sizeof(int32_t),
                     sizeof(int32_t), (size_t)g.n_slices + 1, hipMemcpyDeviceToHost) != hipSuccess)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
@@ -479,6 +469,16 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
         const int32_t base = s << g.slice_log2;
         for (int32_t p = offs[s]; p < offs[s + 1]; p++) idx_host[p] = base + (int32_t)i16[(size_t)p];
     }
+    if (g.fmt == kFmtF32) {
+        if (hipMemcpy(val_host, static_cast<float *>(ctx->p.ring_val) + off, (size_t)g.k * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess)
+            return fail(ctx, EFCP_EHIP, "copy to host failed");
+        return EFCP_OK;
+    }
+    std::vector<uint16_t> v16((size_t)g.k);
+    if (hipMemcpy(v16.data(), static_cast<uint16_t *>(ctx->p.ring_val) + off, (size_t)g.k * 2,
+                  hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(ctx, EFCP_EHIP, "copy to host failed");
     for (int64_t p = 0; p < g.k; p++) {
         const uint32_t bits = (uint32_t)v16[(size_t)p] << 16;
         std::memcpy(&val_host[p], &bits, 4);
@@ -524,7 +524,7 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
 namespace {
 
 struct StateHeader {
-    uint64_t magic;          // "EFCPST02"
+    uint64_t magic;          // "EFCPST03"
     int64_t d, k, row_stride, t;
     int32_t m, ldm, slice, n_slices;
     double lambda;
@@ -532,14 +532,13 @@ struct StateHeader {
     int32_t filled, fmt;
     int32_t kb, ggt;
 };
-constexpr uint64_t kStateMagic = 0x3230545350434645ull;
+constexpr uint64_t kStateMagic = 0x3330545350434645ull;
 
 size_t state_bytes(const efcp_ctx *ctx)
 {
     const Geometry &g = ctx->g;
     const size_t filled = (size_t)(ctx->t < g.m ? ctx->t : g.m);
-    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
-    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * 2 * esz +
+    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * (2 + value_bytes(g)) +
            (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 +
            (g.ggt ? 0 : (size_t)g.m * g.ldm * 8) + (size_t)g.m * 4;
 }
@@ -570,7 +569,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     h.fmt = g.fmt;
     h.kb = g.kb;
     h.ggt = g.ggt;
-    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
+    const size_t vsz = value_bytes(g);
     unsigned char *o = static_cast<unsigned char *>(host_buf);
     std::memcpy(o, &h, sizeof h);
     o += sizeof h;
@@ -581,8 +580,8 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     };
     pull(p.e, (size_t)g.d * 4);
     for (int32_t r = 0; r < h.filled; r++) {
-        pull(static_cast<unsigned char *>(p.ring_idx) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
-        pull(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
+        pull(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 2);
+        pull(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * vsz, (size_t)g.k * vsz);
     }
     pull(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     pull(p.S, (size_t)g.m * g.m * 8);
@@ -612,7 +611,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     }
     if (hipDeviceSynchronize() != hipSuccess) { ctx->t = t_keep; return fail(ctx, EFCP_EHIP, "sync failed"); }
     const DevicePtrs &p = ctx->p;
-    const size_t esz = g.fmt == kFmtBf16 ? 2 : 4;
+    const size_t vsz = value_bytes(g);
     const unsigned char *o = static_cast<const unsigned char *>(host_buf) + sizeof h;
     hipError_t rc = hipSuccess;
     auto push = [&](void *dev, size_t n) {
@@ -621,8 +620,8 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     };
     push(p.e, (size_t)g.d * 4);
     for (int32_t r = 0; r < h.filled; r++) {
-        push(static_cast<unsigned char *>(p.ring_idx) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
-        push(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * esz, (size_t)g.k * esz);
+        push(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 2);
+        push(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * vsz, (size_t)g.k * vsz);
     }
     push(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     push(p.S, (size_t)g.m * g.m * 8);

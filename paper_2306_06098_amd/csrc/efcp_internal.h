@@ -2,11 +2,9 @@
 //
 // Data layout in device memory (one context):
 //   e         float  [d]                 error feedback xi (Algorithm 1)
-//   ring_idx  idx_t  [m][row_stride]     window indices I, ascending inside a row
-//   ring_val  val_t  [m][row_stride]     window values  V
-//                                        (int32 absolute index + fp32 value, or, in the
-//                                        bfloat16 format, uint16 index inside the slice
-//                                        + bf16 value: 4 bytes per entry instead of 8)
+//   ring_idx  uint16 [m][row_stride]     window indices I, ascending inside a row, each
+//                                        stored as its position inside its d-slice
+//   ring_val  val_t  [m][row_stride]     window values V, fp32 or bfloat16
 //   offT      int32  [n_slices+1][m]     offT[s][r] = first entry of row r whose
 //                                        index is >= s*slice (slice-major so one
 //                                        workgroup reads its m offsets contiguously)
@@ -40,30 +38,41 @@ constexpr int kHistPriv = 128;       // private histograms of the candidate pass
 constexpr int kGgtMaxM = 128;        // largest window of the Sparse GGT path (its matrix lives in LDS)
 constexpr int kGgtMaxSweeps = 30;    // Jacobi sweeps at most (a sweep without rotations ends earlier)
 
-// Window entry formats.  EPL = entries one 16-byte load brings per array; a chunk is what
-// a 16-lane group reads with one load per array; kBatch = chunks a lane keeps in flight.
+// Window entry formats.  Indices are always stored as 16-bit positions inside the d-slice the
+// entry falls in (the slice follows from the row's offset table), values as fp32 or bfloat16:
+// 6 or 4 bytes per entry where an absolute int32 index next to an fp32 value would need 8.
+// EPL = entries one lane takes per chunk (one load per array: iraw_t of indices, vraw_t of
+// values); a chunk is what a 16-lane group reads with these; kBatch = chunks a lane keeps in
+// flight.
 enum : int { kFmtF32 = 0, kFmtBf16 = 1 };
 
 template <int FMT> struct Fmt;
 template <> struct Fmt<kFmtF32> {
-    using idx_t = int32_t;
+    using idx_t = uint16_t;
     using val_t = float;
+    using iraw_t = int2;     // 4 x uint16
+    using vraw_t = int4;     // 4 x fp32
     static constexpr int EPL = 4, kChunk = 64, kBatch = 3;
 };
 template <> struct Fmt<kFmtBf16> {
     using idx_t = uint16_t;
     using val_t = uint16_t;
+    using iraw_t = int4;     // 8 x uint16
+    using vraw_t = int4;     // 8 x bf16
     static constexpr int EPL = 8, kChunk = 128, kBatch = 2;
 };
 
-// Entry c (0..EPL-1) of a 16-byte load: position inside the slice and value.
+// Entry c (0..EPL-1) of a lane's loads: position inside the slice and value.
 template <int FMT>
-__device__ __forceinline__ int32_t entry_pos(const int4 &raw, int c, int32_t base, int32_t mask)
+__device__ __forceinline__ int32_t entry_pos(const typename Fmt<FMT>::iraw_t &raw, int c, int32_t mask)
 {
-    const int32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-    // base is a multiple of the slice width, so masking alone removes it
-    if constexpr (FMT == kFmtF32) return w[c] & mask;
-    else return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
+    if constexpr (FMT == kFmtF32) {
+        const int32_t w[2] = {raw.x, raw.y};
+        return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
+    } else {
+        const int32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
+    }
 }
 
 template <int FMT>
@@ -77,8 +86,7 @@ __device__ __forceinline__ float entry_val(const int4 &raw, int c)
 // A single stored entry as (position in its slice, fp32 value).
 __device__ __forceinline__ float stored_val(float v) { return v; }
 __device__ __forceinline__ float stored_val(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
-__device__ __forceinline__ int32_t stored_pos(int32_t i, int32_t base, int32_t mask) { return (i - base) & mask; }
-__device__ __forceinline__ int32_t stored_pos(uint16_t i, int32_t, int32_t mask) { return (int32_t)i & mask; }
+__device__ __forceinline__ int32_t stored_pos(uint16_t i, int32_t mask) { return (int32_t)i & mask; }
 
 // fp32 -> bfloat16 bits, round to nearest even (inputs are finite).
 __device__ __forceinline__ uint32_t bf16_bits(float a)
@@ -115,7 +123,7 @@ struct Geometry {
 
 struct DevicePtrs {
     float *e;
-    void *ring_idx;          // Fmt<fmt>::idx_t [m][row_stride]
+    uint16_t *ring_idx;      // [m][row_stride]
     void *ring_val;          // Fmt<fmt>::val_t [m][row_stride]
     int32_t *offT;
     double *S, *W;

@@ -23,7 +23,7 @@ namespace efcp {
 // loop has a single shape and the number of loads in flight is always known.
 template <int FMT>
 struct LcgBatch {
-    int4 iv[Fmt<FMT>::kBatch];
+    typename Fmt<FMT>::iraw_t iv[Fmt<FMT>::kBatch];
     int4 vv[Fmt<FMT>::kBatch];
     int32_t r;          // row (may be >= n_filled: then nothing is valid)
     int32_t pcs;        // position of chunk 0, lane 0 (multiple of EPL)
@@ -34,8 +34,8 @@ struct LcgBatch {
 // round(c*v / unit) as an integer: the magic constant puts the product's
 // units digit at the last mantissa bit; integer LDS atomics add it.
 template <int FMT>
-__device__ __forceinline__ void lcg_scatter(const int4 &iv, const int4 &vv, int32_t pc, int32_t p0,
-                                            int32_t p1, int32_t base, int32_t mask, double c,
+__device__ __forceinline__ void lcg_scatter(const typename Fmt<FMT>::iraw_t &iv, const int4 &vv, int32_t pc,
+                                            int32_t p0, int32_t p1, int32_t mask, double c,
                                             double magic, long long magic_bits,
                                             unsigned long long *__restrict__ acc)
 {
@@ -48,7 +48,7 @@ __device__ __forceinline__ void lcg_scatter(const int4 &iv, const int4 &vv, int3
         // chunk overlap; lanes outside the run only sit out the atomic (LDS atomic throughput
         // is what this kernel runs out of next to HBM, so they must not issue one).
         const bool ok = rel + (uint32_t)q < len;
-        const int32_t li = entry_pos<FMT>(iv, q, base, mask);
+        const int32_t li = entry_pos<FMT>(iv, q, mask);
         const double t = fma(c, (double)entry_val<FMT>(vv, q), magic);
         const uint32_t lo = (uint32_t)__double2loint(t);
         uint32_t hi = (uint32_t)(__double2hiint(t) - magic_hi);
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
             // always load (from the row start when the chunk lies past the run)
             const int32_t pc = b.pcs + gl * EPL + q * kChunk;
             const int32_t pcl = pc < b.p1 ? pc : 0;
-            b.iv[q] = *reinterpret_cast<const int4 *>(ir + pcl);
+            b.iv[q] = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(ir + pcl);
             b.vv[q] = *reinterpret_cast<const int4 *>(vr + pcl);
         }
     };
@@ -176,15 +176,14 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     auto do_slice = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         const int64_t base64 = (int64_t)s << slice_log2;
-        const int32_t base = (int32_t)base64;
         const int32_t len = FULL ? slice : (int32_t)(d - base64);
         const int32_t snx = it + 1 < sl.count ? sl.at(it + 1) : s;     // this workgroup's next slice
         auto consume = [&](const LcgBatch<FMT> &b) {
             const int32_t hi = b.r < n_filled ? b.p1 : b.p0;       // rows past the end: an empty run
 #pragma unroll
             for (int q = 0; q < kBatch; q++)
-                lcg_scatter<FMT>(b.iv[q], b.vv[q], b.pcs + gl * EPL + q * kChunk, b.p0, hi, base, mask, b.c,
-                                 magic, magic_bits, acc);
+                lcg_scatter<FMT>(b.iv[q], b.vv[q], b.pcs + gl * EPL + q * kChunk, b.p0, hi, mask, b.c, magic,
+                                 magic_bits, acc);
         };
 
         // on their way while the rows stream: x of this slice (for the epilogue) and the row
@@ -296,11 +295,10 @@ template <int FMT, bool XDENSE, bool UPDATE>
 void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float *out, int32_t n_filled,
                    double lambda, const LcgMode &md, hipStream_t stream)
 {
-    using idx_t = typename Fmt<FMT>::idx_t;
     using val_t = typename Fmt<FMT>::val_t;
     hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
                        g.d, g.m, n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                       static_cast<const idx_t *>(p.ring_idx), static_cast<const val_t *>(p.ring_val), p.offT,
+                       p.ring_idx, static_cast<const val_t *>(p.ring_val), p.offT,
                        p.coef, p.rowmax, p.status, 1.0 / lambda, md.x_row, md.decay, md.lr);
 }
 

@@ -421,12 +421,11 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
             if (take) {
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
                 float rem = 0.0f;
+                row_idx[pos] = (uint16_t)(j - seg_first);          // position inside the slice
                 if constexpr (FMT == kFmtF32) {
-                    row_idx[pos] = j;
                     row_val[pos] = v;
                 } else {
                     const uint32_t hb = bf16_bits(v);
-                    row_idx[pos] = (typename Fmt<FMT>::idx_t)(j - seg_first);
                     row_val[pos] = (typename Fmt<FMT>::val_t)hb;
                     rem = v - __uint_as_float(hb << 16);
                 }
@@ -475,12 +474,12 @@ hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, 
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
-                           p.eq_before, static_cast<uint16_t *>(p.ring_idx) + (int64_t)slot * g.row_stride,
+                           p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
                            static_cast<uint16_t *>(p.ring_val) + (int64_t)slot * g.row_stride);
     else
         hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
-                           p.eq_before, static_cast<int32_t *>(p.ring_idx) + (int64_t)slot * g.row_stride,
+                           p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
                            static_cast<float *>(p.ring_val) + (int64_t)slot * g.row_stride);
     return hipGetLastError();
 }

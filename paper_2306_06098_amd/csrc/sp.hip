@@ -27,7 +27,7 @@ namespace efcp {
 // and the number of loads in flight is always known.
 template <int FMT>
 struct RunBatch {
-    int4 iv[Fmt<FMT>::kBatch];
+    typename Fmt<FMT>::iraw_t iv[Fmt<FMT>::kBatch];
     int4 vv[Fmt<FMT>::kBatch];
     int32_t r;          // row (may be >= n_filled: then nothing is valid)
     int32_t pcs;        // position of chunk 0, lane 0 (multiple of EPL)
@@ -35,8 +35,8 @@ struct RunBatch {
 };
 
 template <int FMT>
-__device__ __forceinline__ void sp_accumulate(const int4 &iv, const int4 &vv, int32_t pc, int32_t p0,
-                                              int32_t p1, int32_t base, int32_t mask,
+__device__ __forceinline__ void sp_accumulate(const typename Fmt<FMT>::iraw_t &iv, const int4 &vv,
+                                              int32_t pc, int32_t p0, int32_t p1, int32_t mask,
                                               const float2 *__restrict__ xc, double &aq, double &ag)
 {
     // entry pc+c belongs to the run iff 0 <= pc+c-p0 < p1-p0 (one unsigned compare); an entry
@@ -46,7 +46,7 @@ __device__ __forceinline__ void sp_accumulate(const int4 &iv, const int4 &vv, in
 #pragma unroll
     for (int c = 0; c < Fmt<FMT>::EPL; c++) {
         const bool ok = rel + (uint32_t)c < len;
-        const int32_t li = ok ? entry_pos<FMT>(iv, c, base, mask) : mask + 1;
+        const int32_t li = ok ? entry_pos<FMT>(iv, c, mask) : mask + 1;
         const double v = (double)entry_val<FMT>(vv, c);
         const float2 t = xc[li];
         aq = fma(v, (double)t.x, aq);
@@ -187,14 +187,13 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
             // always load (from the row start when the chunk lies past the run)
             const int32_t pc = b.pcs + gl * EPL + c * kChunk;
             const int32_t pcl = pc < b.p1 ? pc : 0;
-            b.iv[c] = *reinterpret_cast<const int4 *>(ir + pcl);
+            b.iv[c] = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(ir + pcl);
             b.vv[c] = *reinterpret_cast<const int4 *>(vr + pcl);
         }
     };
 
     for (; it < sl.count; it++) {
         s = sl.at(it);
-        const int32_t base = (int32_t)((int64_t)s << slice_log2);
         // ---- switch to slice s: everything comes from registers ----
         __syncthreads();            // previous slice fully consumed
 #pragma unroll
@@ -214,8 +213,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         if (XM != kXOnly) {
             auto put = [&](idx_t i, val_t v) {                     // newest row next to x (or as x)
                 const float f = stored_val(v);
-                if (XM == kXNewest) xc[stored_pos(i, base, mask)] = make_float2(f, f);
-                else xc[stored_pos(i, base, mask)].y = f;
+                if (XM == kXNewest) xc[stored_pos(i, mask)] = make_float2(f, f);
+                else xc[stored_pos(i, mask)].y = f;
             };
             if (q0 + tid < q1) put(di, dv);
             for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)   // runs longer than 1024 entries
@@ -236,8 +235,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
             const int32_t hi = b.r < n_filled ? b.p1 : b.p0;       // rows past the end: an empty run
 #pragma unroll
             for (int c = 0; c < kBatch; c++)
-                sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, base, mask,
-                                   xc, aq, ag);
+                sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, mask, xc, aq, ag);
 #pragma unroll
             for (int o = 8; o > 0; o >>= 1) {
                 aq += __shfl_xor(aq, o, 16);
@@ -301,11 +299,10 @@ template <int FMT, int XM>
 void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled, int32_t slot,
                   hipStream_t stream)
 {
-    using idx_t = typename Fmt<FMT>::idx_t;
     using val_t = typename Fmt<FMT>::val_t;
     hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled,
                        slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                       static_cast<const idx_t *>(p.ring_idx), static_cast<const val_t *>(p.ring_val), p.offT,
+                       p.ring_idx, static_cast<const val_t *>(p.ring_val), p.offT,
                        p.partial);
 }
 

@@ -117,7 +117,7 @@ def _check_block_topk_and_error(a, e_gpu, kb, B, idx, val):
 
 
 def _check_mfac(ctx, n, newest, x, out, lam, m, ranges):
-    """Rows are fetched one at a time (a full window is 9-28 GB)."""
+    """Rows are fetched one at a time (a full window is 7-21 GB)."""
     sm = ctx.get_small()
     xd = x.astype(np.float64)
     inew, vnew = ctx.get_row(newest)
