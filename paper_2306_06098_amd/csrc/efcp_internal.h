@@ -230,6 +230,25 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v)
     return v;
 }
 
+// Sum of a double over each aligned group of 16 lanes, result in all 16 (rotations inside a DPP
+// row: no LDS traffic, fixed order).
+template <int CTRL>
+__device__ __forceinline__ double dpp_rotated(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double row16_sum_f64(double v)
+{
+    v += dpp_rotated<0x128>(v);      // row_ror:8
+    v += dpp_rotated<0x124>(v);      // row_ror:4
+    v += dpp_rotated<0x122>(v);      // row_ror:2
+    v += dpp_rotated<0x121>(v);      // row_ror:1
+    return v;
+}
+
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 {
 #pragma unroll

@@ -154,13 +154,14 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     };
     auto load = [&](LcgBatch<FMT> &b) {
         const int32_t rc = min(b.r, n_filled - 1);
-        const idx_t *ir = ring_idx + (int64_t)rc * row_stride;
-        const val_t *vr = ring_val + (int64_t)rc * row_stride;
+        const uint64_t row_at = (uint64_t)(uint32_t)rc * (uint32_t)row_stride;   // both below 2^31
+        const idx_t *ir = ring_idx + row_at;
+        const val_t *vr = ring_val + row_at;
 #pragma unroll
         for (int q = 0; q < kBatch; q++) {
             // always load (from the row start when the chunk lies past the run)
             const int32_t pc = b.pcs + gl * EPL + q * kChunk;
-            const int32_t pcl = pc < b.p1 ? pc : 0;
+            const uint32_t pcl = pc < b.p1 ? (uint32_t)pc : 0u;
             b.iv[q] = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(ir + pcl);
             b.vv[q] = *reinterpret_cast<const int4 *>(vr + pcl);
         }

@@ -180,13 +180,14 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     };
     auto load = [&](RunBatch<FMT> &b) {
         const int32_t rc = min(b.r, n_filled - 1);
-        const idx_t *ir = ring_idx + (int64_t)rc * row_stride;
-        const val_t *vr = ring_val + (int64_t)rc * row_stride;
+        const uint64_t row_at = (uint64_t)(uint32_t)rc * (uint32_t)row_stride;   // both below 2^31
+        const idx_t *ir = ring_idx + row_at;
+        const val_t *vr = ring_val + row_at;
 #pragma unroll
         for (int c = 0; c < kBatch; c++) {
             // always load (from the row start when the chunk lies past the run)
             const int32_t pc = b.pcs + gl * EPL + c * kChunk;
-            const int32_t pcl = pc < b.p1 ? pc : 0;
+            const uint32_t pcl = pc < b.p1 ? (uint32_t)pc : 0u;
             b.iv[c] = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(ir + pcl);
             b.vv[c] = *reinterpret_cast<const int4 *>(vr + pcl);
         }
@@ -236,11 +237,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 #pragma unroll
             for (int c = 0; c < kBatch; c++)
                 sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, mask, xc, aq, ag);
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) {
-                aq += __shfl_xor(aq, o, 16);
-                ag += __shfl_xor(ag, o, 16);
-            }
+            aq = row16_sum_f64(aq);
+            ag = row16_sum_f64(ag);
             if (gl == 0 && b.r < n_filled) {   // row r belongs to this group only: no race on racc[r]
                 double2 t = racc[b.r];
                 t.x += aq;
