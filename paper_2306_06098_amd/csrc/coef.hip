@@ -178,7 +178,10 @@ __global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, int32_t slo
 }
 
 // ------------------------------------------------------------------
-// Block b owns columns [64b, 64b+64); its 16 waves split the rows.
+// Block b owns the kBwdCols columns [16b, 16b+16); thread (rg, cl) adds rows rg, rg+64, ... of
+// column cl, so 64 blocks share the one pass over W and a thread waits for 16 loads, not 64.
+constexpr int kBwdCols = 16;
+
 __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t slot, double lambda,
                                               double *__restrict__ W,
                                               const double2 *__restrict__ sq,
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t sl
 {
     __shared__ double s_z[kMaxM], s_r[kMaxM];
     __shared__ double buf[16];
-    __shared__ double2 red[16][64];
+    __shared__ double2 red[64][kBwdCols];
 
     const int tid = threadIdx.x;
     double z = 0.0, w = 0.0;
@@ -214,30 +217,28 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t sl
     s_r[tid] = (tid < m && tid != slot) ? (w - z * f) : 0.0;
     __syncthreads();
 
-    const int lane = tid & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int col = blockIdx.x * 64 + lane;
+    const int cl = tid & (kBwdCols - 1), rg = tid >> 4;          // 16 columns x 64 row groups
+    const int col = blockIdx.x * kBwdCols + cl;
     const int colc = min(col, m - 1);
     double ac = 0.0, ay = 0.0;
     // row `slot` needs no skip: s_r[slot] = s_z[slot] = 0 and the row holds finite values
-    for (int i = wv; i < m; i += 16) {
+    for (int i = rg; i < m; i += 64) {
         const double v = W[(int64_t)i * ldm + colc];
         ac = fma(v, s_r[i], ac);
         ay = fma(v, s_z[i], ay);
     }
-    red[wv][lane] = make_double2(ac, ay);
+    red[rg][cl] = make_double2(ac, ay);
     __syncthreads();
     if (col < m && col == slot) {
         // column of the slot that was rewritten: nothing older may refer to it
-        for (int i = wv; i < m; i += 16)
+        for (int i = rg; i < m; i += 64)
             if (i != slot) W[(int64_t)i * ldm + col] = 0.0;
     }
-    if (wv == 0 && col < m) {
+    if (rg == 0 && col < m) {
         double c = 0.0, y = 0.0;
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-            c += red[i][lane].x;
-            y += red[i][lane].y;
+        for (int i = 0; i < 64; i++) {               // fixed order
+            c += red[i][cl].x;
+            y += red[i][cl].y;
         }
         const double2 sqc = sq[col];
         double coef;
@@ -298,7 +299,7 @@ hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled,
 {
     hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, slot, p.W, p.sq,
                        p.zw);
-    hipLaunchKernelGGL(k_bwd, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, lambda,
+    hipLaunchKernelGGL(k_bwd, dim3((g.m + kBwdCols - 1) / kBwdCols), dim3(1024), 0, stream, g.m, g.ldm, slot, lambda,
                        p.W, p.sq, p.zw, p.S, p.q, p.coef, p.status);
     return hipGetLastError();
 }

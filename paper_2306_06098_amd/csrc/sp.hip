@@ -7,9 +7,10 @@
 // gather serves both products), then streams the index/value runs of all
 // filled rows that fall in the slice.  x is read from HBM once and every
 // gather is an LDS access.  A 16-lane group owns one row at a time and reads
-// its run with 16-byte loads, three chunks of the current row and three of
-// the next row in flight at once; products of two fp32 values are exact in
-// fp64 and are accumulated in fp64.
+// its run chunk by chunk (per lane four 16-bit positions and four fp32 values,
+// or eight and eight in the bfloat16 format), one batch of chunks being
+// consumed while the next is in flight; products of two fp32 values are exact
+// in fp64 and are accumulated in fp64.
 //
 // Workgroups are persistent: each walks a fixed list of slices and keeps one
 // (q, Gram) accumulator per row in LDS, so the partial sums that reach memory
