@@ -196,7 +196,8 @@ int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, double *coef_h
 /* Bytes efcp_export_state writes now (grows with the rows filled); 0 if ctx is NULL. */
 size_t efcp_state_bytes(efcp_ctx *ctx);
 
-/* host_buf: at least efcp_state_bytes(ctx) bytes (EFCP_ENOMEM if `bytes` is smaller). */
+/* host_buf: at least efcp_state_bytes(ctx) bytes (EFCP_ENOMEM if `bytes` is smaller), 8-byte
+ * aligned (EFCP_EINVAL otherwise). */
 int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes);
 
 /* ctx must have been created with the same d, m, k and lambda as the exporter

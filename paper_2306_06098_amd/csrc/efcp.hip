@@ -133,6 +133,9 @@ struct efcp_ctx {
     size_t ws_bytes;
     bool own_ws;
     int64_t t;
+    // Global Top-k: the slot whose row still has to be taken out of e (the next step's first
+    // pass does it; read-outs do it on the host); -1: e is final.
+    int32_t pending_slot;
     hipStream_t last_stream;
     // The eviction update of the inverse factor depends on the previous step only; it runs on
     // this stream next to the d-sized passes of the step and is joined before k_fwd.
@@ -234,6 +237,7 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     ctx->g = g;
     ctx->lambda = lambda;
     ctx->t = 0;
+    ctx->pending_slot = -1;
     ctx->last_stream = nullptr;
     ctx->err = "no error";
     ctx->prof_on = false;
@@ -367,7 +371,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
         mark(1);
         mark(2);
     } else {
-        if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
+        if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, ctx->pending_slot, stream);
         mark(1);
         if (rc == hipSuccess) rc = launch_select(g, p, slot, stream);
         mark(2);
@@ -393,6 +397,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     mark(6);
 
     ctx->t = t;
+    ctx->pending_slot = g.kb ? -1 : slot;
     ctx->last_stream = stream;
     if (ctx->prof_on) ctx->prof_count++;
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
@@ -486,13 +491,28 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
     return EFCP_OK;
 }
 
+// e = a - c for a copy of the device buffer that still holds a at the entries of the newest row.
+static int settle_error(efcp_ctx *ctx, float *e_host)
+{
+    if (ctx->pending_slot < 0) return EFCP_OK;
+    const Geometry &g = ctx->g;
+    std::vector<int32_t> idx((size_t)g.k);
+    std::vector<float> val((size_t)g.k);
+    if (int rc = efcp_get_row(ctx, ctx->pending_slot, idx.data(), val.data())) return rc;
+    for (int64_t p = 0; p < g.k; p++) {
+        float &ej = e_host[idx[(size_t)p]];
+        ej = g.fmt == kFmtBf16 ? ej - val[(size_t)p] : 0.0f;     // val is bf16(a) there, ej is a
+    }
+    return EFCP_OK;
+}
+
 extern "C" int efcp_get_error(efcp_ctx *ctx, float *e_host)
 {
     if (!ctx || !e_host) return EFCP_EINVAL;
     if (int rc = sync_last(ctx)) return rc;
     if (hipMemcpy(e_host, ctx->p.e, (size_t)ctx->g.d * 4, hipMemcpyDeviceToHost) != hipSuccess)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
-    return EFCP_OK;
+    return settle_error(ctx, e_host);
 }
 
 extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, double *coef_host,
@@ -551,6 +571,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
 {
     if (!ctx || !host_buf) return EFCP_EINVAL;
     if (bytes < state_bytes(ctx)) return fail(ctx, EFCP_ENOMEM, "state buffer too small");
+    if (reinterpret_cast<uintptr_t>(host_buf) & 7) return fail(ctx, EFCP_EINVAL, "state buffer not 8-byte aligned");
     if (int rc = sync_last(ctx)) return rc;
     const Geometry &g = ctx->g;
     const DevicePtrs &p = ctx->p;
@@ -578,7 +599,9 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
         if (rc == hipSuccess) rc = hipMemcpy(o, dev, n, hipMemcpyDeviceToHost);
         o += n;
     };
+    float *e_blob = reinterpret_cast<float *>(o);
     pull(p.e, (size_t)g.d * 4);
+    if (rc == hipSuccess && settle_error(ctx, e_blob) != EFCP_OK) return EFCP_EHIP;
     for (int32_t r = 0; r < h.filled; r++) {
         pull(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 2);
         pull(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * vsz, (size_t)g.k * vsz);
@@ -638,6 +661,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     if (rc == hipSuccess && g.ggt && h.filled > 0) rc = launch_ggt_refresh(g, p, h.filled, nullptr);
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
+    ctx->pending_slot = -1;                          // an exported e is final
     return EFCP_OK;
 }
 

@@ -1,7 +1,10 @@
 // efcp_internal.h -- shared declarations of the libefcp HIP sources (gfx950 only).
 //
 // Data layout in device memory (one context):
-//   e         float  [d]                 error feedback xi (Algorithm 1)
+//   e         float  [d]                 error feedback xi (Algorithm 1); with the global
+//                                        Top-k it holds the accumulator a between steps and
+//                                        the entries of the newest row are dropped by the
+//                                        next step's first pass (or by the host on read-out)
 //   ring_idx  uint16 [m][row_stride]     window indices I, ascending inside a row, each
 //                                        stored as its position inside its d-slice
 //   ring_val  val_t  [m][row_stride]     window values V, fp32 or bfloat16
@@ -145,7 +148,8 @@ struct DevicePtrs {
 };
 
 // Launchers (each enqueues on `stream` and returns hipGetLastError()).
-hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
+hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t pending_slot,
+                          hipStream_t stream);
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
 // x_source: 0 = dense x next to the newest row, 1 = the newest row is x, 2 = dense x only

@@ -10,9 +10,13 @@
 // the histogram of the first digit, it also copies every element whose key is
 // at least t_lo -- a bin edge two bins below the previous step's threshold --
 // to a candidate list, in index order, one segment per block of 16,384
-// coordinates.  All later passes (two digit histograms, per-block counts, the
-// ordered compaction into the ring and the zeroing of the selected entries of
-// e) read the candidates only: a few percent of d.  The first-digit histogram
+// coordinates.  All later passes (two digit histograms, per-block counts and
+// the ordered compaction into the ring) read the candidates only: a few
+// percent of d.  e = a - c is not finished by this step: clearing k scattered
+// entries costs a partial HBM write each, so the buffer keeps a, and the NEXT
+// step's first pass, which rewrites e anyway, drops the entries of the row
+// inserted last (a bitmap in LDS per block of 16,384 coordinates).  Host code
+// that reads e in between applies the same rule.  The first-digit histogram
 // is exact, so it tells whether the threshold bin lies at or above t_lo; if it
 // does not (the threshold dropped by more than two bins in one step), one
 // extra pass over a rebuilds the candidates from the now known bin.  The
@@ -63,17 +67,23 @@ __device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t
 // REDO = true: the pass that rebuilds the candidates from a (already in e)
 // with the threshold bin found by the first digit; it exits at once unless
 // the select state asks for it.
-template <bool REDO>
+// PEND (first pass only): `e` still holds the previous step's accumulator; the entries of the
+// row inserted then (pend_idx, the run of this block given by two entries of its offset column)
+// count as +0, or as the rounding remainder a - bf16(a) when the window keeps bfloat16 values.
+template <bool REDO, int PEND>
 __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict__ g,
                                                          float *__restrict__ e, int64_t d,
                                                          uint32_t *__restrict__ hist,
                                                          const SelState *__restrict__ sel,
                                                          int32_t *__restrict__ cand_idx,
                                                          float *__restrict__ cand_val,
-                                                         uint32_t *__restrict__ cand_cnt)
+                                                         uint32_t *__restrict__ cand_cnt,
+                                                         const uint16_t *__restrict__ pend_idx,
+                                                         const int32_t *__restrict__ pend_off, int32_t m)
 {
     __shared__ uint32_t lh[REDO ? 1 : kBins1];
     __shared__ uint32_t s_cnt[2][4];
+    __shared__ uint32_t pend[PEND ? kCandBlock / 32 : 1];       // one bit per coordinate of the block
     uint32_t t_lo;
     if (REDO) {
         if (!sel->redo) return;
@@ -81,8 +91,22 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
     } else {
         t_lo = sel->t_lo;
         for (int i = threadIdx.x; i < kBins1; i += kSelThreads) lh[i] = 0;
+        if (PEND) {
+            for (int i = threadIdx.x; i < kCandBlock / 32; i += kSelThreads) pend[i] = 0;
+            __syncthreads();
+            const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
+            for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kSelThreads) {
+                const uint32_t pos = pend_idx[p];
+                atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
+            }
+        }
         __syncthreads();
     }
+    // value of e at a coordinate whose pending bit is set
+    auto settled = [](float a) {
+        if (PEND == 2) return a - __uint_as_float(bf16_bits(a) << 16);
+        return 0.0f;
+    };
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t block_first = (int64_t)blockIdx.x * kCandBlock;
     int32_t *seg_idx = cand_idx + block_first;
@@ -103,6 +127,15 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
             }
 #pragma unroll
             for (int it = 0; it < 4; it++) {
+                if (PEND) {
+                    // the four coordinates of this load share one word of the bitmap
+                    const uint32_t q = (uint32_t)(cch * kSelChunk + w * 1024 + it * 256 + lane * 4);
+                    const uint32_t bits4 = (pend[q >> 5] >> (q & 31u)) & 15u;
+                    if (bits4 & 1u) ev[it].x = settled(ev[it].x);
+                    if (bits4 & 2u) ev[it].y = settled(ev[it].y);
+                    if (bits4 & 4u) ev[it].z = settled(ev[it].z);
+                    if (bits4 & 8u) ev[it].w = settled(ev[it].w);
+                }
                 if (REDO) {
                     a[it][0] = ev[it].x; a[it][1] = ev[it].y; a[it][2] = ev[it].z; a[it][3] = ev[it].w;
                 } else {
@@ -122,7 +155,12 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                     const int64_t j = wave_base + it * 256 + c;
                     float t = 0.0f;
                     if (j < d) {
-                        t = REDO ? e[j] : e[j] + g[j];
+                        float ej = e[j];
+                        if (PEND) {
+                            const uint32_t q = (uint32_t)(j - block_first);
+                            if ((pend[q >> 5] >> (q & 31u)) & 1u) ej = settled(ej);
+                        }
+                        t = REDO ? ej : ej + g[j];
                         if (!REDO) e[j] = t;
                     }
                     a[it][c] = t;
@@ -373,15 +411,14 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
 
 // ------------------------------------------------------------------
 // Ordered compaction of the selected candidates of segment b into the ring
-// row, and e = a - c: selected entries of the error buffer become +0 (fp32
-// window) or the rounding remainder a - bf16(a) (bfloat16 window, whose
-// entries also keep only the index inside the segment = slice).
+// row (16-bit positions inside the segment = slice; fp32 or bfloat16 values).
+// The error buffer is left as it is: see the top of this file.
 // One wave per segment; candidates are already in index order.
 template <int FMT>
 __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__restrict__ cand_idx,
                                                               const float *__restrict__ cand_val,
                                                               const uint32_t *__restrict__ cand_cnt,
-                                                              int32_t nb, float *__restrict__ e,
+                                                              int32_t nb,
                                                               const SelState *__restrict__ sel,
                                                               const uint32_t *__restrict__ sel_off,
                                                               const uint32_t *__restrict__ eq_before,
@@ -420,16 +457,9 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
             const uint64_t take_mask = __ballot(take);
             if (take) {
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
-                float rem = 0.0f;
                 row_idx[pos] = (uint16_t)(j - seg_first);          // position inside the slice
-                if constexpr (FMT == kFmtF32) {
-                    row_val[pos] = v;
-                } else {
-                    const uint32_t hb = bf16_bits(v);
-                    row_val[pos] = (typename Fmt<FMT>::val_t)hb;
-                    rem = v - __uint_as_float(hb << 16);
-                }
-                __builtin_nontemporal_store(rem, &e[j]);       // scattered, not read again this step
+                if constexpr (FMT == kFmtF32) row_val[pos] = v;
+                else row_val[pos] = (typename Fmt<FMT>::val_t)bf16_bits(v);
             }
             eq_run += __popcll(eq_mask);
             out_run += __popcll(take_mask);
@@ -439,10 +469,22 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
 
 // ------------------------------------------------------------------
 
-hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream)
+// pending_slot >= 0: the row in that slot was inserted by the previous step and its entries are
+// still to be taken out of e.
+hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t pending_slot,
+                          hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ef_hist<false>, dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
-                       g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt);
+    const uint16_t *pidx = pending_slot >= 0 ? p.ring_idx + (int64_t)pending_slot * g.row_stride : nullptr;
+    const int32_t *poff = pending_slot >= 0 ? p.offT + pending_slot : nullptr;
+    if (pending_slot < 0)
+        hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m);
+    else if (g.fmt == kFmtBf16)
+        hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m);
+    else
+        hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m);
     return hipGetLastError();
 }
 
@@ -451,8 +493,9 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, h
     const int32_t nb = g.n_sel_blocks;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
                        (uint32_t)g.k, p.rowmax + slot);
-    hipLaunchKernelGGL(k_ef_hist<true>, dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
-                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt);
+    hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
+                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint16_t *)nullptr,
+                       (const int32_t *)nullptr, g.m);
     hipLaunchKernelGGL(k_cand_hist, dim3(kHistGroups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
                        p.sel, p.hist2, 20, 10);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
@@ -473,12 +516,12 @@ hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, 
 {
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
-                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
+                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.sel, p.sel_off,
                            p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
                            static_cast<uint16_t *>(p.ring_val) + (int64_t)slot * g.row_stride);
     else
         hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
-                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.e, p.sel, p.sel_off,
+                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.sel, p.sel_off,
                            p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
                            static_cast<float *>(p.ring_val) + (int64_t)slot * g.row_stride);
     return hipGetLastError();
