@@ -80,7 +80,7 @@ size_t value_bytes(const Geometry &g) { return g.fmt == kFmtBf16 ? 2 : 4; }
 struct Layout {
     size_t e, ring_idx, ring_val, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
         cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
-        n_stages, total;
+        n_stages, col, total;
     size_t small_begin;      // everything from here on is small and zero-initialised
 };
 
@@ -117,12 +117,21 @@ Layout make_layout(const Geometry &g)
     l.lam = take(g.ggt ? (size_t)g.m * sizeof(double) : 0);
     l.rot = take(g.ggt ? (size_t)kGgtMaxSweeps * (kGgtMaxM - 1) * 64 * sizeof(double2) : 0);
     l.n_stages = take(g.ggt ? 256 : 0);
+    l.col = take(((size_t)g.n_slices + 1) * sizeof(int32_t));
     l.status = take(256);
     l.total = o;
     return l;
 }
 
 }  // namespace
+
+// One column of the slice-major offset table, made contiguous for a copy to the host.
+__global__ void k_offset_column(const int32_t *__restrict__ offT, int32_t m, int32_t slot, int32_t n,
+                                int32_t *__restrict__ out)
+{
+    const int32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < n) out[s] = offT[(int64_t)s * m + slot];
+}
 
 struct efcp_ctx {
     Geometry g;
@@ -291,6 +300,7 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     p.lam = reinterpret_cast<double *>(b + l.lam);
     p.rot = reinterpret_cast<double2 *>(b + l.rot);
     p.n_stages = reinterpret_cast<int32_t *>(b + l.n_stages);
+    p.col = reinterpret_cast<int32_t *>(b + l.col);
     p.status = reinterpret_cast<uint32_t *>(b + l.status);
 
     // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.
@@ -466,9 +476,12 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
     // 16-bit in-slice indices become absolute with the row's slice offsets
     std::vector<uint16_t> i16((size_t)g.k);
     std::vector<int32_t> offs((size_t)g.n_slices + 1);
-    if (hipMemcpy(i16.data(), ctx->p.ring_idx + off, (size_t)g.k * 2, hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy2D(offs.data(), sizeof(int32_t), ctx->p.offT + slot, (size_t)g.m * sizeof(int32_t),
-                    sizeof(int32_t), (size_t)g.n_slices + 1, hipMemcpyDeviceToHost) != hipSuccess)
+    hipLaunchKernelGGL(k_offset_column, dim3((g.n_slices + 1 + 255) / 256), dim3(256), 0, ctx->last_stream,
+                       ctx->p.offT, g.m, slot, g.n_slices + 1, ctx->p.col);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(ctx->last_stream) != hipSuccess ||
+        hipMemcpy(i16.data(), ctx->p.ring_idx + off, (size_t)g.k * 2, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(offs.data(), ctx->p.col, ((size_t)g.n_slices + 1) * sizeof(int32_t),
+                  hipMemcpyDeviceToHost) != hipSuccess)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
     for (int32_t s = 0; s < g.n_slices; s++) {
         const int32_t base = s << g.slice_log2;

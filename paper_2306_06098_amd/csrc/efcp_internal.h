@@ -144,6 +144,7 @@ struct DevicePtrs {
     double *lam;             // [m] eigenvalues of S                      (Sparse GGT only)
     double2 *rot;            // [kGgtMaxSweeps*(kGgtMaxM-1)][64] logged rotations (c, s)
     int32_t *n_stages;       // stages logged by the last decomposition
+    int32_t *col;            // [n_slices+1] one column of offT, gathered for read-outs
     uint32_t *status;
 };
 

@@ -65,7 +65,7 @@ def test_bert_base_blockwise_first_steps_vs_oracle(env, capsys):
     """Top-k applied in blocks at d = 110M (6,713 full blocks and a ragged one), 164 entries
     per block, bfloat16 window on the last two steps' twin run; apply() after every step."""
     torch, _, binding = env
-    _first_steps_vs_oracle(env, capsys, "bert_base", 3, k=164, topk_block=binding.TOPK_BLOCK, apply_every=1)
+    _first_steps_vs_oracle(env, capsys, "bert_base", 2, k=164, topk_block=binding.TOPK_BLOCK, apply_every=1)
     _first_steps_vs_oracle(env, capsys, "bert_base", 2, k=164, topk_block=binding.TOPK_BLOCK, bf16=True)
 
 
