@@ -19,6 +19,8 @@ Prints one JSON line:
                         launch / HIP-event time per launch, against the HBM peak; `traffic` is the
                         measured HBM bytes per launch from rocprofv3 counters (full window only);
                         stored_bytes_per_launch / frac_stored: the same with the stored entry size
+  device_copy_GBps      a plain torch device copy of d floats on the same box (bytes read + written / time):
+                        what a simple streaming kernel reaches here, for context
   cpu_baseline          the CPU oracle timed on this host on a bounded sample (see its `sample`)
 """
 from __future__ import annotations
@@ -212,7 +214,18 @@ def main():
                      "frac_stored": st[dom] / (per_launch[dom] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     ctx.destroy()
-    del pool, out, stream
+    # practical ceiling of this machine for context: a plain device copy of d floats (read d, write d)
+    src = pool[0]
+    for _ in range(3):
+        out.copy_(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(20):
+        out.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    result["device_copy_GBps"] = 20 * 8 * wl.d / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del pool, out, stream, src
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline and not ggt:
         result["cpu_baseline"] = cpu_baseline(wl, bf16)
