@@ -124,7 +124,10 @@ size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_f
  *   stream  hipStream_t (NULL = the default stream)
  * Asynchronous: enqueues kernels on `stream` and returns; no host
  * synchronisation and no allocation.  Steps of one context must be issued in
- * order on one stream, or on streams ordered by the caller. */
+ * order on one stream, or on streams ordered by the caller, with the device of
+ * efcp_create current.  EFCP_EINVAL leaves the context untouched; after
+ * EFCP_EHIP (a launch failed part-way) its state is undefined and it can only
+ * be destroyed or overwritten by efcp_import_state. */
 int efcp_step(efcp_ctx *ctx, const float *grad, float *out, void *stream);
 
 /* Which vector the step preconditions (Algorithm 1, line 8). */
