@@ -612,3 +612,65 @@ def test_sparse_ggt_duplicate_rows_checkpoint_and_limits(env):
             binding.Efcp(d, 129, 60, eps, ggt=True)
     finally:
         a.destroy(); b.destroy(); c.destroy()
+
+
+# ---------------------------------------------------------------------------
+# HIP graphs: the entry points enqueue kernels only (no allocation, no host
+# synchronisation, no memset nodes), so a caller may capture them
+
+def test_step_and_apply_under_hip_graph_capture(env):
+    """A step (with the eviction update forked to the library's second stream)
+    captured into a graph and launched once equals the eager step of a twin
+    context; efcp_apply captured once and replayed with new x contents equals
+    the eager call every time (eager work and synchronisations in between)."""
+    torch, _, binding = env
+    dev = torch.device("cuda:0")
+    d, m, k, lam = 200_003, 4, 1500, 1e-3
+    for values in (binding.VALUES_FP32, binding.VALUES_BF16):
+        a = binding.Efcp(d, m, k, lam, values=values)
+        b = binding.Efcp(d, m, k, lam, values=values)
+        try:
+            s = torch.cuda.Stream()
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(7)
+            g = torch.empty(d, device=dev)
+            oa, ob = torch.empty(d, device=dev), torch.empty(d, device=dev)
+            for t in range(m + 3):                       # past the point where steps evict
+                g.normal_(generator=gen)
+                torch.cuda.synchronize()                 # g is written on torch's stream, read on s
+                a.step(g, oa, stream=s)
+                b.step(g, ob, stream=s)
+                s.synchronize()
+            assert torch.equal(oa, ob)
+            for rep in range(3):                         # b's next steps: one fresh graph each
+                g.normal_(generator=gen)
+                torch.cuda.synchronize()
+                a.step(g, oa, stream=s)
+                s.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=s):
+                    b.step(g, ob, stream=s)
+                ob.zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(oa, ob), f"captured step {rep} differs from the eager one"
+                assert np.array_equal(bits(a.get_error()), bits(b.get_error()))
+            x = torch.empty(d, device=dev)
+            y, y_ref = torch.empty(d, device=dev), torch.empty(d, device=dev)
+            x.normal_(generator=gen)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s):
+                a.apply(x, y, stream=s)
+            for rep in range(4):
+                x.normal_(generator=gen)                 # new contents, same buffer
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                a.apply(x, y_ref, stream=s)
+                s.synchronize()
+                assert torch.equal(y, y_ref), f"replay {rep} of the captured apply differs"
+        finally:
+            a.destroy()
+            b.destroy()
