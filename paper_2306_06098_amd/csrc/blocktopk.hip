@@ -53,11 +53,8 @@ template <int FMT>
 __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
     const float *__restrict__ g, float *__restrict__ e, int64_t d, int32_t m, int32_t slot,
     int64_t row_stride, int64_t k, int32_t kb, int32_t nsl,
-    typename Fmt<FMT>::idx_t *__restrict__ ring_idx, typename Fmt<FMT>::val_t *__restrict__ ring_val,
-    int32_t *__restrict__ offT, uint32_t *__restrict__ blk_max, uint32_t *__restrict__ blk_tlo)
+    uint8_t *__restrict__ ring, int32_t *__restrict__ offT, uint32_t *__restrict__ blk_max, uint32_t *__restrict__ blk_tlo)
 {
-    using idx_t = typename Fmt<FMT>::idx_t;
-    using val_t = typename Fmt<FMT>::val_t;
     __shared__ uint32_t hist[kBins1];
     __shared__ uint32_t tmp[40];
     __shared__ uint32_t res[4];
@@ -184,8 +181,8 @@ __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
     }
     __syncthreads();
 
-    idx_t *irow = ring_idx + (int64_t)slot * row_stride + (int64_t)s * kb;
-    val_t *vrow = ring_val + (int64_t)slot * row_stride + (int64_t)s * kb;
+    uint8_t *row = ring + (int64_t)slot * row_stride * Fmt<FMT>::kEntryBytes;
+    const uint32_t run_first = (uint32_t)s * (uint32_t)kb;           // this block's entries start here
 #pragma unroll
     for (int u = 0; u < 4; u++) {
         uint32_t before = wbase[u * 16 + wv] + incl[u] - packed[u];
@@ -200,14 +197,14 @@ __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
             const int32_t i = u * 4096 + tid * 4 + c;
             float rest = av;
             if (sel) {
-                const uint32_t pos = gtb + min(eqb, quota);
-                irow[pos] = (uint16_t)i;                           // position inside the slice
+                const uint32_t pos = run_first + gtb + min(eqb, quota);
+                *entry_idx_ptr<FMT>(row, pos) = (uint16_t)i;       // position inside the slice
                 if constexpr (FMT == kFmtF32) {
-                    vrow[pos] = av;
+                    *entry_val_ptr<FMT>(row, pos) = av;
                     rest = 0.0f;
                 } else {
                     const uint32_t hb = bf16_bits(av);
-                    vrow[pos] = (uint16_t)hb;
+                    *entry_val_ptr<FMT>(row, pos) = (uint16_t)hb;
                     rest = av - __uint_as_float(hb << 16);       // e keeps the rounding remainder
                 }
             }
@@ -256,12 +253,12 @@ hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_block_topk<kFmtBf16>, dim3(g.n_slices), dim3(kBlkThreads), 0, stream, grad, p.e,
                            g.d, g.m, slot, g.row_stride, g.k, g.kb, g.n_slices,
-                           p.ring_idx, static_cast<uint16_t *>(p.ring_val), p.offT,
+                           p.ring, p.offT,
                            p.blk_max, p.blk_tlo);
     else
         hipLaunchKernelGGL(k_block_topk<kFmtF32>, dim3(g.n_slices), dim3(kBlkThreads), 0, stream, grad, p.e,
                            g.d, g.m, slot, g.row_stride, g.k, g.kb, g.n_slices,
-                           p.ring_idx, static_cast<float *>(p.ring_val), p.offT,
+                           p.ring, p.offT,
                            p.blk_max, p.blk_tlo);
     hipLaunchKernelGGL(k_block_finish, dim3(1), dim3(1024), 0, stream, p.blk_max, g.n_slices,
                        p.rowmax + slot, p.sel);

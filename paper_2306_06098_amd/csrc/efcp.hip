@@ -54,6 +54,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
     }
     g.d = d; g.k = k; g.m = m; g.fmt = fmt;
     g.row_stride = (int64_t)align_up((size_t)k, 64);
+    g.row_bytes = g.row_stride * (fmt == kFmtBf16 ? 4 : 6);
     g.ldm = (int32_t)align_up((size_t)m, 8);
     const size_t fixed_sp = 16 + 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2) + 2 * 512 * sizeof(int32_t);
     const size_t fixed_lcg = 4 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
@@ -76,12 +77,18 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
 }
 
 size_t value_bytes(const Geometry &g) { return g.fmt == kFmtBf16 ? 2 : 4; }
+int group_entries(const Geometry &g) { return g.fmt == kFmtBf16 ? 8 : 4; }
+// Bytes of a row that hold its k entries (whole groups).
+size_t row_payload_bytes(const Geometry &g)
+{
+    const size_t ge = (size_t)group_entries(g);
+    return ((size_t)g.k + ge - 1) / ge * ge * (2 + value_bytes(g));
+}
 
 struct Layout {
-    size_t e, ring_idx, ring_val, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
+    size_t e, ring, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
         cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
         n_stages, col, total;
-    size_t small_begin;      // everything from here on is small and zero-initialised
 };
 
 Layout make_layout(const Geometry &g)
@@ -89,13 +96,11 @@ Layout make_layout(const Geometry &g)
     Layout l{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    l.ring_idx = take((size_t)g.m * g.row_stride * sizeof(uint16_t));
-    l.ring_val = take((size_t)g.m * g.row_stride * value_bytes(g));
+    l.ring = take((size_t)g.m * (size_t)g.row_bytes);
     l.partial = take((size_t)g.sp_grid * g.m * sizeof(double2));
     // candidate lists exist for the global Top-k only
     l.cand_idx = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
     l.cand_val = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(float));
-    l.small_begin = o;
     l.e = take((size_t)g.d * sizeof(float));
     l.offT = take((size_t)(g.n_slices + 1) * g.m * sizeof(int32_t));
     l.S = take((size_t)g.m * g.m * sizeof(double));
@@ -273,8 +278,7 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     unsigned char *b = static_cast<unsigned char *>(ctx->ws);
     DevicePtrs &p = ctx->p;
     p.e = reinterpret_cast<float *>(b + l.e);
-    p.ring_idx = reinterpret_cast<uint16_t *>(b + l.ring_idx);
-    p.ring_val = b + l.ring_val;
+    p.ring = b + l.ring;
     p.offT = reinterpret_cast<int32_t *>(b + l.offT);
     p.S = reinterpret_cast<double *>(b + l.S);
     p.W = reinterpret_cast<double *>(b + l.W);
@@ -303,9 +307,11 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     p.col = reinterpret_cast<int32_t *>(b + l.col);
     p.status = reinterpret_cast<uint32_t *>(b + l.status);
 
-    // e = 0, offsets, Gram matrix, factor, histograms, counters: all zero.
-    // The ring rows and the per-slice partial sums are written before they are read.
-    hipError_t rc = hipMemset(b + l.small_begin, 0, l.total - l.small_begin);
+    // Everything starts as zero bytes: e = 0, offsets, Gram matrix, factor, histograms, counters,
+    // and the ring too: the SP pass multiplies entries that lie outside a run (other slices' entries,
+    // or the unused tail of a row's last group) by zero, so they must be finite numbers, never
+    // whatever the memory held before.
+    hipError_t rc = hipMemset(b, 0, l.total);
     ctx->side = nullptr;
     ctx->ev_fork = ctx->ev_join = nullptr;
     if (rc == hipSuccess) rc = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
@@ -472,34 +478,38 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
     const int64_t filled = ctx->t < g.m ? ctx->t : g.m;
     if (slot < 0 || slot >= filled) return fail(ctx, EFCP_EINVAL, "slot not filled");
     if (int rc = sync_last(ctx)) return rc;
-    const size_t off = (size_t)slot * g.row_stride;
-    // 16-bit in-slice indices become absolute with the row's slice offsets
-    std::vector<uint16_t> i16((size_t)g.k);
+    // the row's groups ([indices][values]) and its slice offsets; 16-bit in-slice indices become
+    // absolute with the offsets
+    const size_t ge = (size_t)group_entries(g), vb = value_bytes(g), gb = ge * (2 + vb);
+    std::vector<unsigned char> raw(row_payload_bytes(g));
     std::vector<int32_t> offs((size_t)g.n_slices + 1);
     hipLaunchKernelGGL(k_offset_column, dim3((g.n_slices + 1 + 255) / 256), dim3(256), 0, ctx->last_stream,
                        ctx->p.offT, g.m, slot, g.n_slices + 1, ctx->p.col);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(ctx->last_stream) != hipSuccess ||
-        hipMemcpy(i16.data(), ctx->p.ring_idx + off, (size_t)g.k * 2, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(raw.data(), ctx->p.ring + (size_t)slot * (size_t)g.row_bytes, raw.size(),
+                  hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy(offs.data(), ctx->p.col, ((size_t)g.n_slices + 1) * sizeof(int32_t),
                   hipMemcpyDeviceToHost) != hipSuccess)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
+    auto stored_index = [&](int64_t p) {
+        uint16_t v;
+        std::memcpy(&v, raw.data() + (size_t)(p / (int64_t)ge) * gb + 2 * (size_t)(p % (int64_t)ge), 2);
+        return (int32_t)v;
+    };
     for (int32_t s = 0; s < g.n_slices; s++) {
         const int32_t base = s << g.slice_log2;
-        for (int32_t p = offs[s]; p < offs[s + 1]; p++) idx_host[p] = base + (int32_t)i16[(size_t)p];
+        for (int32_t p = offs[s]; p < offs[s + 1]; p++) idx_host[p] = base + stored_index(p);
     }
-    if (g.fmt == kFmtF32) {
-        if (hipMemcpy(val_host, static_cast<float *>(ctx->p.ring_val) + off, (size_t)g.k * 4,
-                      hipMemcpyDeviceToHost) != hipSuccess)
-            return fail(ctx, EFCP_EHIP, "copy to host failed");
-        return EFCP_OK;
-    }
-    std::vector<uint16_t> v16((size_t)g.k);
-    if (hipMemcpy(v16.data(), static_cast<uint16_t *>(ctx->p.ring_val) + off, (size_t)g.k * 2,
-                  hipMemcpyDeviceToHost) != hipSuccess)
-        return fail(ctx, EFCP_EHIP, "copy to host failed");
     for (int64_t p = 0; p < g.k; p++) {
-        const uint32_t bits = (uint32_t)v16[(size_t)p] << 16;
-        std::memcpy(&val_host[p], &bits, 4);
+        const unsigned char *at = raw.data() + (size_t)(p / (int64_t)ge) * gb + 2 * ge + vb * (size_t)(p % (int64_t)ge);
+        if (g.fmt == kFmtF32) {
+            std::memcpy(&val_host[p], at, 4);
+        } else {
+            uint16_t hb;
+            std::memcpy(&hb, at, 2);
+            const uint32_t bits = (uint32_t)hb << 16;
+            std::memcpy(&val_host[p], &bits, 4);
+        }
     }
     return EFCP_OK;
 }
@@ -557,7 +567,7 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
 namespace {
 
 struct StateHeader {
-    uint64_t magic;          // "EFCPST03"
+    uint64_t magic;          // "EFCPST04"
     int64_t d, k, row_stride, t;
     int32_t m, ldm, slice, n_slices;
     double lambda;
@@ -565,13 +575,13 @@ struct StateHeader {
     int32_t filled, fmt;
     int32_t kb, ggt;
 };
-constexpr uint64_t kStateMagic = 0x3330545350434645ull;
+constexpr uint64_t kStateMagic = 0x3430545350434645ull;
 
 size_t state_bytes(const efcp_ctx *ctx)
 {
     const Geometry &g = ctx->g;
     const size_t filled = (size_t)(ctx->t < g.m ? ctx->t : g.m);
-    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * (size_t)g.k * (2 + value_bytes(g)) +
+    return sizeof(StateHeader) + (size_t)g.d * 4 + filled * row_payload_bytes(g) +
            (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 +
            (g.ggt ? 0 : (size_t)g.m * g.ldm * 8) + (size_t)g.m * 4;
 }
@@ -603,7 +613,6 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     h.fmt = g.fmt;
     h.kb = g.kb;
     h.ggt = g.ggt;
-    const size_t vsz = value_bytes(g);
     unsigned char *o = static_cast<unsigned char *>(host_buf);
     std::memcpy(o, &h, sizeof h);
     o += sizeof h;
@@ -616,8 +625,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
     pull(p.e, (size_t)g.d * 4);
     if (rc == hipSuccess && settle_error(ctx, e_blob) != EFCP_OK) return EFCP_EHIP;
     for (int32_t r = 0; r < h.filled; r++) {
-        pull(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 2);
-        pull(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * vsz, (size_t)g.k * vsz);
+        pull(p.ring + (size_t)r * (size_t)g.row_bytes, row_payload_bytes(g));
     }
     pull(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     pull(p.S, (size_t)g.m * g.m * 8);
@@ -647,7 +655,6 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     }
     if (hipDeviceSynchronize() != hipSuccess) { ctx->t = t_keep; return fail(ctx, EFCP_EHIP, "sync failed"); }
     const DevicePtrs &p = ctx->p;
-    const size_t vsz = value_bytes(g);
     const unsigned char *o = static_cast<const unsigned char *>(host_buf) + sizeof h;
     hipError_t rc = hipSuccess;
     auto push = [&](void *dev, size_t n) {
@@ -656,8 +663,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     };
     push(p.e, (size_t)g.d * 4);
     for (int32_t r = 0; r < h.filled; r++) {
-        push(p.ring_idx + (size_t)r * g.row_stride, (size_t)g.k * 2);
-        push(static_cast<unsigned char *>(p.ring_val) + (size_t)r * g.row_stride * vsz, (size_t)g.k * vsz);
+        push(p.ring + (size_t)r * (size_t)g.row_bytes, row_payload_bytes(g));
     }
     push(p.offT, (size_t)(g.n_slices + 1) * g.m * 4);
     push(p.S, (size_t)g.m * g.m * 8);

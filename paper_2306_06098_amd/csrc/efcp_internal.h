@@ -5,9 +5,12 @@
 //                                        Top-k it holds the accumulator a between steps and
 //                                        the entries of the newest row are dropped by the
 //                                        next step's first pass (or by the host on read-out)
-//   ring_idx  uint16 [m][row_stride]     window indices I, ascending inside a row, each
-//                                        stored as its position inside its d-slice
-//   ring_val  val_t  [m][row_stride]     window values V, fp32 or bfloat16
+//   ring      bytes  [m][row_stride*E]   window G = (I, V), one row per slot, entries in
+//                                        ascending index order, stored in groups of EPL
+//                                        entries: the EPL indices (each a 16-bit position
+//                                        inside its d-slice), then the EPL values (fp32 or
+//                                        bfloat16).  E = 6 or 4 bytes per entry; the run of a
+//                                        row inside one slice is one contiguous piece of memory
 //   offT      int32  [n_slices+1][m]     offT[s][r] = first entry of row r whose
 //                                        index is >= s*slice (slice-major so one
 //                                        workgroup reads its m offsets contiguously)
@@ -54,16 +57,46 @@ template <> struct Fmt<kFmtF32> {
     using idx_t = uint16_t;
     using val_t = float;
     using iraw_t = int2;     // 4 x uint16
-    using vraw_t = int4;     // 4 x fp32
-    static constexpr int EPL = 4, kChunk = 64, kBatch = 3;
+    static constexpr int EPL = 4, kChunk = 64, kBatch = 3, kEntryBytes = 6;
 };
 template <> struct Fmt<kFmtBf16> {
     using idx_t = uint16_t;
     using val_t = uint16_t;
     using iraw_t = int4;     // 8 x uint16
-    using vraw_t = int4;     // 8 x bf16
-    static constexpr int EPL = 8, kChunk = 128, kBatch = 2;
+    static constexpr int EPL = 8, kChunk = 128, kBatch = 2, kEntryBytes = 4;
 };
+
+// Entry p of a row lives in group p / EPL: [EPL x uint16 index][EPL x value].
+template <int FMT>
+__host__ __device__ __forceinline__ uint64_t group_offset(uint64_t p)
+{
+    return (p / Fmt<FMT>::EPL) * (uint64_t)(Fmt<FMT>::EPL * Fmt<FMT>::kEntryBytes);
+}
+template <int FMT>
+__device__ __forceinline__ uint16_t *entry_idx_ptr(uint8_t *row, uint32_t p)
+{
+    return reinterpret_cast<uint16_t *>(row + group_offset<FMT>(p)) + (p % Fmt<FMT>::EPL);
+}
+template <int FMT>
+__device__ __forceinline__ typename Fmt<FMT>::val_t *entry_val_ptr(uint8_t *row, uint32_t p)
+{
+    return reinterpret_cast<typename Fmt<FMT>::val_t *>(row + group_offset<FMT>(p) + 2 * Fmt<FMT>::EPL) +
+           (p % Fmt<FMT>::EPL);
+}
+// One lane's group of a chunk: p is a multiple of EPL.  All loads are naturally aligned (the fp32
+// values of a group start 8 bytes into it, so they come as two 8-byte loads).
+template <int FMT>
+__device__ __forceinline__ void load_group(const uint8_t *row, uint32_t p, typename Fmt<FMT>::iraw_t &iv, int4 &vv)
+{
+    const uint8_t *g = row + (uint64_t)p * Fmt<FMT>::kEntryBytes;
+    iv = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(g);
+    if constexpr (FMT == kFmtF32) {
+        const int2 lo = *reinterpret_cast<const int2 *>(g + 8), hi = *reinterpret_cast<const int2 *>(g + 16);
+        vv = make_int4(lo.x, lo.y, hi.x, hi.y);
+    } else {
+        vv = *reinterpret_cast<const int4 *>(g + 16);
+    }
+}
 
 // Entry c (0..EPL-1) of a lane's loads: position inside the slice and value.
 template <int FMT>
@@ -113,7 +146,8 @@ struct SelState {
 enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
 
 struct Geometry {
-    int64_t d, k, row_stride;
+    int64_t d, k, row_stride;    // row_stride: entries per row of the ring (k rounded up to 64)
+    int64_t row_bytes;           // row_stride * bytes per entry
     int32_t kb;              // 0: global Top-k; > 0: Top-k in blocks, entries kept per full block
     int32_t ggt;             // 0: Sparse M-FAC coefficients; 1: Sparse GGT
     int32_t m, ldm;
@@ -126,8 +160,7 @@ struct Geometry {
 
 struct DevicePtrs {
     float *e;
-    uint16_t *ring_idx;      // [m][row_stride]
-    void *ring_val;          // Fmt<fmt>::val_t [m][row_stride]
+    uint8_t *ring;           // [m][row_stride * bytes per entry], see the top of this file
     int32_t *offT;
     double *S, *W;
     double2 *partial, *sq, *zw;

@@ -72,16 +72,13 @@ template <int FMT, bool XDENSE, bool UPDATE>
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
                                               int64_t d, int32_t m, int32_t n_filled, int64_t row_stride,
                                               int32_t slice_log2, int32_t nsl, int32_t cpx,
-                                              const typename Fmt<FMT>::idx_t *__restrict__ ring_idx,
-                                              const typename Fmt<FMT>::val_t *__restrict__ ring_val,
+                                              const uint8_t *__restrict__ ring,
                                               const int32_t *__restrict__ offT,
                                               const double *__restrict__ coef,
                                               const uint32_t *__restrict__ rowmax,
                                               uint32_t *__restrict__ status, double inv_lambda,
                                               int32_t x_row, double decay, double lr)
 {
-    using idx_t = typename Fmt<FMT>::idx_t;
-    using val_t = typename Fmt<FMT>::val_t;
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t slice = 1 << slice_log2;
@@ -154,16 +151,14 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     };
     auto load = [&](LcgBatch<FMT> &b) {
         const int32_t rc = min(b.r, n_filled - 1);
-        const uint64_t row_at = (uint64_t)(uint32_t)rc * (uint32_t)row_stride;   // both below 2^31
-        const idx_t *ir = ring_idx + row_at;
-        const val_t *vr = ring_val + row_at;
+        const uint8_t *row =
+            ring + (uint64_t)(uint32_t)rc * (uint32_t)row_stride * (uint64_t)Fmt<FMT>::kEntryBytes;
 #pragma unroll
         for (int q = 0; q < kBatch; q++) {
             // always load (from the row start when the chunk lies past the run)
             const int32_t pc = b.pcs + gl * EPL + q * kChunk;
             const uint32_t pcl = pc < b.p1 ? (uint32_t)pc : 0u;
-            b.iv[q] = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(ir + pcl);
-            b.vv[q] = *reinterpret_cast<const int4 *>(vr + pcl);
+            load_group<FMT>(row, pcl, b.iv[q], b.vv[q]);
         }
     };
 
@@ -296,10 +291,9 @@ template <int FMT, bool XDENSE, bool UPDATE>
 void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float *out, int32_t n_filled,
                    double lambda, const LcgMode &md, hipStream_t stream)
 {
-    using val_t = typename Fmt<FMT>::val_t;
     hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
                        g.d, g.m, n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                       p.ring_idx, static_cast<const val_t *>(p.ring_val), p.offT,
+                       p.ring, p.offT,
                        p.coef, p.rowmax, p.status, 1.0 / lambda, md.x_row, md.decay, md.lr);
 }
 

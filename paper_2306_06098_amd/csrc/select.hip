@@ -68,7 +68,7 @@ __device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t
 // with the threshold bin found by the first digit; it exits at once unless
 // the select state asks for it.
 // PEND (first pass only): `e` still holds the previous step's accumulator; the entries of the
-// row inserted then (pend_idx, the run of this block given by two entries of its offset column)
+// row inserted then (pend_row, the run of this block given by two entries of its offset column)
 // count as +0, or as the rounding remainder a - bf16(a) when the window keeps bfloat16 values.
 template <bool REDO, int PEND>
 __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict__ g,
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                                                          int32_t *__restrict__ cand_idx,
                                                          float *__restrict__ cand_val,
                                                          uint32_t *__restrict__ cand_cnt,
-                                                         const uint16_t *__restrict__ pend_idx,
+                                                         const uint8_t *__restrict__ pend_row,
                                                          const int32_t *__restrict__ pend_off, int32_t m)
 {
     __shared__ uint32_t lh[REDO ? 1 : kBins1];
@@ -96,7 +96,8 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
             __syncthreads();
             const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
             for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kSelThreads) {
-                const uint32_t pos = pend_idx[p];
+                constexpr int PF = PEND == 2 ? kFmtBf16 : kFmtF32;
+                const uint32_t pos = *entry_idx_ptr<PF>(const_cast<uint8_t *>(pend_row), (uint32_t)p);
                 atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
             }
         }
@@ -422,8 +423,7 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
                                                               const SelState *__restrict__ sel,
                                                               const uint32_t *__restrict__ sel_off,
                                                               const uint32_t *__restrict__ eq_before,
-                                                              typename Fmt<FMT>::idx_t *__restrict__ row_idx,
-                                                              typename Fmt<FMT>::val_t *__restrict__ row_val)
+                                                              uint8_t *__restrict__ row)
 {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int32_t b = blockIdx.x * 4 + w;
@@ -457,9 +457,9 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
             const uint64_t take_mask = __ballot(take);
             if (take) {
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
-                row_idx[pos] = (uint16_t)(j - seg_first);          // position inside the slice
-                if constexpr (FMT == kFmtF32) row_val[pos] = v;
-                else row_val[pos] = (typename Fmt<FMT>::val_t)bf16_bits(v);
+                *entry_idx_ptr<FMT>(row, pos) = (uint16_t)(j - seg_first);     // position inside the slice
+                if constexpr (FMT == kFmtF32) *entry_val_ptr<FMT>(row, pos) = v;
+                else *entry_val_ptr<FMT>(row, pos) = (uint16_t)bf16_bits(v);
             }
             eq_run += __popcll(eq_mask);
             out_run += __popcll(take_mask);
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
 hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t pending_slot,
                           hipStream_t stream)
 {
-    const uint16_t *pidx = pending_slot >= 0 ? p.ring_idx + (int64_t)pending_slot * g.row_stride : nullptr;
+    const uint8_t *pidx = pending_slot >= 0 ? p.ring + (int64_t)pending_slot * g.row_bytes : nullptr;
     const int32_t *poff = pending_slot >= 0 ? p.offT + pending_slot : nullptr;
     if (pending_slot < 0)
         hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
@@ -494,7 +494,7 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, h
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
                        (uint32_t)g.k, p.rowmax + slot);
     hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
-                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint16_t *)nullptr,
+                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint8_t *)nullptr,
                        (const int32_t *)nullptr, g.m);
     hipLaunchKernelGGL(k_cand_hist, dim3(kHistGroups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
                        p.sel, p.hist2, 20, 10);
@@ -517,13 +517,11 @@ hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, 
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.sel, p.sel_off,
-                           p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
-                           static_cast<uint16_t *>(p.ring_val) + (int64_t)slot * g.row_stride);
+                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes);
     else
         hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.sel, p.sel_off,
-                           p.eq_before, p.ring_idx + (int64_t)slot * g.row_stride,
-                           static_cast<float *>(p.ring_val) + (int64_t)slot * g.row_stride);
+                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes);
     return hipGetLastError();
 }
 

@@ -79,8 +79,7 @@ template <int FMT, int XM>
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              int32_t n_filled, int32_t slot, int64_t row_stride,
                                              int64_t k, int32_t slice_log2, int32_t nsl, int32_t cpx,
-                                             const typename Fmt<FMT>::idx_t *__restrict__ ring_idx,
-                                             const typename Fmt<FMT>::val_t *__restrict__ ring_val,
+                                             const uint8_t *__restrict__ ring,
                                              const int32_t *__restrict__ offT,
                                              double2 *__restrict__ partial)
 {
@@ -103,8 +102,10 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
     const int32_t mask = slice - 1;
     const int32_t trow = min(tid, m - 1);
-    const idx_t *nidx = ring_idx + (int64_t)slot * row_stride;     // newest row
-    const val_t *nval = ring_val + (int64_t)slot * row_stride;
+    constexpr int64_t kEntryBytes = Fmt<FMT>::kEntryBytes;
+    uint8_t *nrow = const_cast<uint8_t *>(ring) + (int64_t)slot * row_stride * kEntryBytes;   // newest row (read only)
+    auto nidx = [&](int32_t p) { return *entry_idx_ptr<FMT>(nrow, (uint32_t)p); };
+    auto nval = [&](int32_t p) { return *entry_val_ptr<FMT>(nrow, (uint32_t)p); };
     const int32_t klast = (int32_t)(k - 1);
 
     racc[tid] = make_double2(0.0, 0.0);
@@ -153,8 +154,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         o1 = offT[(int64_t)(sp + 1) * m + trow];
         if (XM != kXOnly) {
             const int32_t p = min(np0[ip] + tid, klast);     // clamped: always a valid entry
-            di = nidx[p];
-            dv = nval[p];
+            di = nidx(p);
+            dv = nval(p);
         }
     };
 
@@ -181,16 +182,13 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     };
     auto load = [&](RunBatch<FMT> &b) {
         const int32_t rc = min(b.r, n_filled - 1);
-        const uint64_t row_at = (uint64_t)(uint32_t)rc * (uint32_t)row_stride;   // both below 2^31
-        const idx_t *ir = ring_idx + row_at;
-        const val_t *vr = ring_val + row_at;
+        const uint8_t *row = ring + (uint64_t)(uint32_t)rc * (uint32_t)row_stride * (uint64_t)kEntryBytes;
 #pragma unroll
         for (int c = 0; c < kBatch; c++) {
             // always load (from the row start when the chunk lies past the run)
             const int32_t pc = b.pcs + gl * EPL + c * kChunk;
             const uint32_t pcl = pc < b.p1 ? (uint32_t)pc : 0u;
-            b.iv[c] = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(ir + pcl);
-            b.vv[c] = *reinterpret_cast<const int4 *>(vr + pcl);
+            load_group<FMT>(row, pcl, b.iv[c], b.vv[c]);
         }
     };
 
@@ -220,7 +218,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
             };
             if (q0 + tid < q1) put(di, dv);
             for (int32_t p = q0 + 1024 + tid; p < q1; p += 1024)   // runs longer than 1024 entries
-                put(nidx[p], nval[p]);
+                put(nidx(p), nval(p));
         }
         __syncthreads();
 
@@ -298,11 +296,9 @@ template <int FMT, int XM>
 void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled, int32_t slot,
                   hipStream_t stream)
 {
-    using val_t = typename Fmt<FMT>::val_t;
     hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled,
                        slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
-                       p.ring_idx, static_cast<const val_t *>(p.ring_val), p.offT,
-                       p.partial);
+                       p.ring, p.offT, p.partial);
 }
 
 template <int FMT>

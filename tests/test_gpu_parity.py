@@ -674,3 +674,34 @@ def test_step_and_apply_under_hip_graph_capture(env):
         finally:
             a.destroy()
             b.destroy()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_caller_workspace_full_of_nan_patterns(env, bf16):
+    """The library must not depend on what a workspace held before: entries outside
+    a run (the unused tail of a row's last group, rows not inserted yet) are multiplied
+    by zero in the SP pass, so they have to be finite from the start.  Here the caller's
+    workspace is all 0xFF bytes (NaN in every format) before efcp_create."""
+    torch, oracle_mod, binding = env
+    dev = torch.device("cuda:0")
+    d, m, k, lam = 20_001, 8, 201, 1e-3                  # k is not a multiple of the group size
+    values = binding.VALUES_BF16 if bf16 else binding.VALUES_FP32
+    nbytes = binding.efcp_workspace_bytes(d, m, k, values)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=dev)
+    ctx = binding.Efcp(d, m, k, lam, workspace=ws, values=values)
+    o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16)
+    try:
+        g_d = torch.empty(d, device=dev)
+        out_d = torch.empty(d, device=dev)
+        for t, g in enumerate(_edge_grads(d, 12, 3), 1):
+            y = o.step(g)
+            g_d.copy_(torch.from_numpy(g))
+            ctx.step(g_d, out_d)
+            torch.cuda.synchronize()
+            out = out_d.cpu().numpy()
+            assert np.isfinite(out).all()
+            assert rel_l2(out, y) <= 1e-3, f"step {t}"
+            assert np.array_equal(bits(ctx.get_error()), bits(o.error))
+    finally:
+        ctx.destroy()
+        o.close()
