@@ -83,16 +83,16 @@ __device__ __forceinline__ typename Fmt<FMT>::val_t *entry_val_ptr(uint8_t *row,
     return reinterpret_cast<typename Fmt<FMT>::val_t *>(row + group_offset<FMT>(p) + 2 * Fmt<FMT>::EPL) +
            (p % Fmt<FMT>::EPL);
 }
-// One lane's group of a chunk: p is a multiple of EPL.  All loads are naturally aligned (the fp32
-// values of a group start 8 bytes into it, so they come as two 8-byte loads).
+// One lane's group of a chunk: p is a multiple of EPL.  The fp32 values of a group start 8 bytes
+// into it.
 template <int FMT>
 __device__ __forceinline__ void load_group(const uint8_t *row, uint32_t p, typename Fmt<FMT>::iraw_t &iv, int4 &vv)
 {
     const uint8_t *g = row + (uint64_t)p * Fmt<FMT>::kEntryBytes;
     iv = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(g);
     if constexpr (FMT == kFmtF32) {
-        const int2 lo = *reinterpret_cast<const int2 *>(g + 8), hi = *reinterpret_cast<const int2 *>(g + 16);
-        vv = make_int4(lo.x, lo.y, hi.x, hi.y);
+        // 16 bytes at an 8-byte boundary: the compiler picks the widest load the target allows
+        __builtin_memcpy(&vv, __builtin_assume_aligned(g + 8, 8), 16);
     } else {
         vv = *reinterpret_cast<const int4 *>(g + 16);
     }
