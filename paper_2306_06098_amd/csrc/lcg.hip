@@ -125,8 +125,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     } else if (bound != 0.0) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(status, kStatusRange);
     }
-    const double unit = ldexp(1.0, ex - 50);
-    const double magic = ldexp(1.5, ex + 2);          // 1.5 * 2^52 * unit
+    const double magic = ldexp(1.5, ex + 2);          // 1.5 * 2^52 * unit, unit = 2^(ex-50)
     const long long magic_bits = __double_as_longlong(magic);
 
     // Batches: two register sets used alternately (no copies between them): while one batch
@@ -230,7 +229,9 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
 
         // out = x/lambda - sum (or the parameter update); accumulators back to zero for the next slice
         auto result = [&](float xj, float thj, unsigned long long a) {
-            const double sum = (double)(long long)a * unit;
+            // a units of `unit`, exactly: magic + a*unit is the double whose bits are bits(magic) + a
+            // (the sum stays inside magic's binade), and subtracting magic from it is exact
+            const double sum = __longlong_as_double((long long)a + magic_bits) - magic;
             const double y = XDENSE ? (double)xj * inv_lambda - sum : -sum;
             return UPDATE ? (float)((double)thj * decay - lr * y) : (float)y;
         };
