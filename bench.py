@@ -38,7 +38,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a torch kernel of known
 # size), full 1024-row window of the bert_base workload:
 # profiles/k_sp_k_lcg_k_ef_hist_bert_base_hbm_counters.txt
-MEASURED_TRAFFIC = {("bert_base", "lcg"): 7.92e9, ("bert_base", "sp"): 7.53e9}
+MEASURED_TRAFFIC = {("bert_base", "lcg"): 7.87e9, ("bert_base", "sp"): 7.48e9}
 METRIC = "Sparse M-FAC EFCP steps/s + achieved HBM GB/s (d=110M, m=1024, 1% density)"
 
 
