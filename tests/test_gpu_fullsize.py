@@ -11,6 +11,8 @@
   e = a - c, q and the Gram row as fp64 dot products over the exported rows,
   coef against a LAPACK solve, out = x/lambda - sum coef_r c_r on whole ranges
   of coordinates (first, middle, ragged last).
+* d = 2^31 - 1, the largest dimension the interface admits, with a two-row
+  window: the same definitions evaluated on the GPU with torch in chunks.
 """
 import time
 
@@ -336,3 +338,109 @@ def test_bert_large_700_rows_properties(env, capsys):
     worst = _check_mfac(ctx, n, n - 1, x, out.cpu().numpy(), wl.lam, wl.m, ranges)
     _say(capsys, f"bert_large: q, Gram row, coef, out ok (worst rel L2 on a range {worst:.2e})")
     ctx.destroy()
+
+
+def test_largest_dimension_properties(env, capsys):
+    """d = 2^31 - 1, the largest dimension the interface admits (131,072 slices, the last one
+    ragged): two steps with a small window, global and block-wise selection, checked on the GPU
+    itself with torch in chunks against the definitions: the selected set is exactly the k largest
+    |a_j| (threshold, strict part, lowest-index ties), stored values are a at the indices,
+    e = a - c, and F^-1 g equals g/lambda - sum coef_r c_r formed in fp64 from the exported rows."""
+    torch, _, binding = env
+    dev = torch.device("cuda:0")
+    d, m, lam = 2 ** 31 - 1, 2, 1e-2
+    chunk = 2 ** 27
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    g = torch.empty(d, dtype=torch.float32, device=dev)
+    out = torch.empty_like(g)
+
+    def fill(t):
+        for lo in range(0, d, chunk):
+            g[lo:lo + chunk].normal_(generator=gen)
+        g[d - 3:] = torch.tensor([9.0, -9.5, 10.0], device=dev) * (t + 1)      # the very last coordinates matter
+        g[:2] = torch.tensor([-8.0, 8.5], device=dev) * (t + 1)
+
+    def key_of(x):
+        return x.view(torch.int32) & 0x7FFFFFFF
+
+    for topk_block, k in ((0, 1000), (binding.TOPK_BLOCK, 1)):
+        ctx = binding.Efcp(d, m, k, lam, topk_block=topk_block)
+        kk = ctx.k
+        assert kk == (k if not topk_block else (d // 16384) + 1)
+        a_prev_e = None
+        for t in range(2):
+            fill(t)
+            a = g.clone() if t == 0 else None
+            if t == 1:                                       # a = e + g with the settled e of step 1
+                e1 = torch.from_numpy(ctx.get_error()).to(dev)
+                a = e1 + g
+                del e1
+            ctx.step(g, out)
+            torch.cuda.synchronize()
+            slot = t % m
+            idx_h, val_h = ctx.get_row(slot)
+            assert idx_h.size == kk and (np.diff(idx_h.astype(np.int64)) > 0).all()
+            assert idx_h[0] >= 0 and idx_h[-1] < d
+            if t == 0 or not topk_block:                     # the planted values at the very end are kept
+                assert idx_h[-1] == d - 1                    # (block-wise, step 2: e carries -9.5 - 19 at d-2)
+            idx = torch.from_numpy(idx_h.astype(np.int64)).to(dev)
+            val = torch.from_numpy(val_h).to(dev)
+            assert torch.equal(val.view(torch.int32), a[idx].view(torch.int32)), "stored values are not a[idx]"
+            sel_key = key_of(val)
+            if not topk_block:
+                tau = int(sel_key.min())
+                n_gt = n_eq = 0
+                first_unselected_tie = None
+                for lo in range(0, d, chunk):
+                    kc = key_of(a[lo:lo + chunk])
+                    n_gt += int((kc > tau).sum())
+                    n_eq += int((kc == tau).sum())
+                assert n_gt == int((sel_key > tau).sum()) and n_gt < kk <= n_gt + n_eq
+                # ties at the threshold: the selected ones are the lowest indices among them
+                n_sel_eq = kk - n_gt
+                tie_idx = torch.cat([(key_of(a[lo:lo + chunk]) == tau).nonzero().flatten() + lo
+                                     for lo in range(0, d, chunk)])
+                assert torch.equal(tie_idx[:n_sel_eq], idx[sel_key == tau])
+                assert ctx.get_small()["tau"] == tau
+            else:
+                # one entry per block: the block's largest magnitude, first one on ties
+                nb = d // 16384
+                blocks = key_of(a[:nb * 16384]).view(nb, 16384)
+                arg = blocks.argmax(dim=1)                    # first maximum
+                assert torch.equal(idx[:nb], arg + torch.arange(nb, device=dev) * 16384)
+                tail = key_of(a[nb * 16384:])
+                assert int(idx[nb]) == nb * 16384 + int(tail.argmax())
+                del blocks, arg, tail
+            # e = a - c
+            e_now = torch.from_numpy(ctx.get_error()).to(dev)
+            assert not e_now[idx].any()
+            a[idx] = 0.0
+            assert torch.equal(e_now.view(torch.int32), a.view(torch.int32)), "e != a - c"
+            del e_now, a
+            # F^-1 g from the rows and the library's coefficients, fp64, whole vector in chunks
+            sm = ctx.get_small()
+            n = t + 1
+            A = m * lam * np.eye(n) + sm["S"][:n, :n]
+            coef = np.linalg.solve(A, sm["q"][:n]) / lam
+            assert rel_l2(sm["coef"][:n], coef) < 1e-9
+            rows = [ctx.get_row(r) for r in range(n)]
+            num = den = 0.0
+            for lo in range(0, d, chunk):
+                hi = min(lo + chunk, d)
+                y = g[lo:hi].double() / lam
+                for (ri, rv), c in zip(rows, coef):
+                    a0, a1 = np.searchsorted(ri, [lo, hi])
+                    if a1 > a0:
+                        y[torch.from_numpy(ri[a0:a1].astype(np.int64) - lo).to(dev)] -= \
+                            c * torch.from_numpy(rv[a0:a1].astype(np.float64)).to(dev)
+                num += float(((out[lo:hi].double() - y) ** 2).sum())
+                den += float((y ** 2).sum())
+                del y
+            err = (num / den) ** 0.5
+            assert err <= 1e-3, f"out off by {err:.3e}"
+            _say(capsys, f"d = 2^31-1, {'block-wise' if topk_block else 'global'} Top-k, step {t + 1}: "
+                         f"selection, e and out ok (rel L2 {err:.2e})")
+        ctx.destroy()
+        del ctx
+        torch.cuda.empty_cache()
