@@ -40,3 +40,25 @@ def test_null_context_is_rejected_without_a_gpu():
     assert lib.efcp_destroy(None) == binding.EFCP_OK
     assert lib.efcp_step(None, None, None, None) == binding.EFCP_EINVAL
     assert lib.efcp_last_error(None) == b"null context"
+
+
+def test_row_length_arithmetic_matches_the_oracle(oracle_mod):
+    """efcp_row_length is host arithmetic only (no device needed): global Top-k keeps k, block-wise
+    Top-k keeps k per block of 16,384 and the same share, rounded up, of a ragged last block -- the
+    rule the oracle implements independently."""
+    lib = binding.load_library()
+    B = binding.TOPK_BLOCK
+    assert lib.efcp_row_length(1000, 10, 0) == 10
+    assert lib.efcp_row_length(1000, 1001, 0) == 0                       # k > d
+    assert lib.efcp_row_length(1000, 0, 0) == 0
+    assert lib.efcp_row_length(10 * B, 164, B) == 1640
+    assert lib.efcp_row_length(1000, 10, 4096) == 0                      # unsupported block size
+    assert lib.efcp_row_length(1000, B + 1, B) == 0                      # more than a block holds
+    ob = oracle_mod._load().eo_block_row_length
+    for d in (1, 3, B - 1, B, B + 1, 272_474, 110_000_000, 2 ** 31 - 1):
+        for kb in (1, 7, 164, 4099, B):
+            assert lib.efcp_row_length(d, kb, B) == ob(d, B, kb), (d, kb)
+    # a null context is refused by every new entry point too
+    assert lib.efcp_step_ex(None, None, 0, None, None, 0.0, 0.0, None) == binding.EFCP_EINVAL
+    assert lib.efcp_apply(None, None, None, None) == binding.EFCP_EINVAL
+    assert lib.efcp_state_bytes(None) == 0
