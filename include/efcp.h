@@ -208,8 +208,19 @@ int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes);
  * state is replaced. */
 int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes);
 
+/* Tuning knob, process-wide: the d-slice width of contexts created (and workspace sizes
+ * computed) afterwards.  0, the default: chosen from d so that the persistent SP / LCG
+ * workgroups all get the same number of slices.  Otherwise a multiple of 256 in
+ * [256, 16384] (EFCP_EINVAL if not); a width too small for the d of a later efcp_create
+ * makes that call fail with EFCP_EINVAL.  Ignored with Top-k in blocks, where the slice is
+ * the block.  The Top-k, the stored rows and e do not depend on the width;
+ * S, q, coef and with them F^-1 x do in the last bits (order of the fp64 sums).  A state exported under one width
+ * is refused by a context created under another. */
+int efcp_tune_slice_width(int32_t width);
+
 /* Geometry chosen at creation; any pointer may be NULL.
  *   slice      coordinates per d-slice staged in LDS by the SP and LCG kernels
+ *              (a multiple of 256, at most 16384)
  *   n_slices   ceil(d / slice)
  *   row_stride entries between consecutive rows of I and V (k rounded up) */
 int efcp_get_geometry(efcp_ctx *ctx, int32_t *slice, int32_t *n_slices, int64_t *row_stride);

@@ -22,7 +22,7 @@ EXPORTS = (
     "efcp_workspace_bytes", "efcp_workspace_bytes_fmt", "efcp_create", "efcp_create_fmt", "efcp_create_ex",
     "efcp_workspace_bytes_ex", "efcp_row_length", "efcp_create_ggt", "efcp_workspace_bytes_ggt", "efcp_step", "efcp_step_ex", "efcp_apply",
     "efcp_destroy", "efcp_get_row",
-    "efcp_get_error", "efcp_get_small", "efcp_get_geometry", "efcp_state_bytes",
+    "efcp_get_error", "efcp_get_small", "efcp_tune_slice_width", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
     "efcp_profile_read", "efcp_last_error",
 )
@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_get_error.argtypes = [vp, vp]
     lib.efcp_get_small.restype = ctypes.c_int
     lib.efcp_get_small.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.efcp_tune_slice_width.restype = ctypes.c_int
+    lib.efcp_tune_slice_width.argtypes = [i32]
     lib.efcp_get_geometry.restype = ctypes.c_int
     lib.efcp_get_geometry.argtypes = [vp, vp, vp, vp]
     lib.efcp_state_bytes.restype = ctypes.c_size_t
@@ -105,6 +107,14 @@ def efcp_workspace_bytes(d: int, m: int, k: int, values: int = VALUES_FP32, topk
                          ggt: bool = False) -> int:
     fn = load_library().efcp_workspace_bytes_ggt if ggt else load_library().efcp_workspace_bytes_ex
     return int(fn(d, m, k, values, topk_block))
+
+
+def tune_slice_width(width: int) -> None:
+    """efcp_tune_slice_width: d-slice width of contexts created afterwards
+    (0 = automatic; else a multiple of 256 in [256, 16384]).  Process-wide."""
+    rc = load_library().efcp_tune_slice_width(int(width))
+    if rc != 0:
+        raise EfcpError(rc, f"slice width {width} not a multiple of 256 in [256, 16384]")
 
 
 class Efcp:

@@ -5,6 +5,7 @@
 #include "../../include/efcp.h"
 #include "efcp_internal.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -19,13 +20,40 @@ constexpr int kProfEvents = EFCP_K_COUNT + 1;
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Largest power-of-two slice whose LDS working set fits the device.
 // Entries per row when every block of kCandBlock coordinates keeps kb and a ragged last block
 // keeps the same share rounded up.
 int64_t block_row_length(int64_t d, int64_t kb)
 {
     const int64_t full = d / kCandBlock, tail = d % kCandBlock;
     return full * kb + (tail ? (kb * tail + kCandBlock - 1) / kCandBlock : 0);
+}
+
+// Width of the d-slices that the SP and LCG workgroups stage in LDS, which are also the blocks of
+// the Top-k passes.  With Top-k in blocks it is the block.  Otherwise: the widest slice leaves
+// the persistent workgroups with unequal numbers of slices (684 slices of 16,384 over 256
+// workgroups: three rounds, the last one two thirds empty), which costs up to 1/rounds of the SP
+// and LCG passes.  Up to kBalanceRounds rounds the vector is therefore cut into a multiple of
+// kMaxWgs nearly equal slices: the fewest rounds that the LDS allows, every workgroup in every
+// round; short vectors get narrow slices for the same reason, all workgroups take part.  Longer
+// vectors keep the widest slice: the imbalance is small there, and the first Top-k pass pays a
+// fixed cost per block (measured at d = 110M: 5 % slower with 16,128-wide blocks than with 16,384).
+// No result depends on the width except the order of the fp64 sums of the SP pass.
+constexpr int kBalanceRounds = 4;
+std::atomic<int32_t> g_slice_width{0};             // efcp_tune_slice_width: 0 = automatic
+
+int32_t pick_slice_width(int64_t d, int32_t kb)
+{
+    if (kb) return kCandBlock;
+    const int32_t forced = g_slice_width.load();
+    if (forced) return forced;
+    const int64_t widest = (d + kCandBlock - 1) / kCandBlock;
+    const int64_t rounds = (widest + kMaxWgs - 1) / kMaxWgs;
+    if (rounds > kBalanceRounds) return kCandBlock;
+    int64_t w = (d + kMaxWgs * rounds - 1) / (kMaxWgs * rounds);
+    w = (w + 255) / 256 * 256;
+    if (w < kMinSlice) w = kMinSlice;
+    if (w > kCandBlock) w = kCandBlock;
+    return (int32_t)w;
 }
 
 // k_in: entries per row (topk_block == 0) or per block of kCandBlock coordinates.
@@ -58,18 +86,18 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
     g.ldm = (int32_t)align_up((size_t)m, 8);
     const size_t fixed_sp = 16 + 2 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double2) + 2 * 512 * sizeof(int32_t);
     const size_t fixed_lcg = 4 * kMaxM * sizeof(int32_t) + kMaxM * sizeof(double);
-    const int lg = 14;                             // 16384 coordinates: 128 KiB of the 160 KiB LDS
+    const int lg = 14;                             // kCandBlock coordinates: 128 KiB of the 160 KiB LDS
     if (((size_t)8 << lg) + fixed_sp > (size_t)lds || ((size_t)8 << lg) + fixed_lcg > (size_t)lds) {
         *why = "device LDS too small (needs the 160 KiB of gfx950)";
         return false;
     }
-    g.slice_log2 = lg;
-    g.slice = 1 << lg;
-    g.n_slices = (int32_t)((d + g.slice - 1) >> lg);
-    g.n_sel_blocks = (int32_t)((d + kCandBlock - 1) / kCandBlock);
+    g.slice = pick_slice_width(d, g.kb);
+    g.n_slices = (int32_t)((d + g.slice - 1) / g.slice);
     {
         const int32_t per = (g.n_slices + 7) / 8;
-        g.sp_grid = 8 * (per < 32 ? per : 32);
+        g.sp_grid = 8 * (per < kMaxWgs / 8 ? per : kMaxWgs / 8);
+        // the SP kernel keeps two numbers per slice of a workgroup in a fixed piece of LDS
+        if ((per + kMaxWgs / 8 - 1) / (kMaxWgs / 8) > 512) { *why = "slice width too small for this d"; return false; }
     }
     g.lds_sp = ((size_t)8 << lg) + fixed_sp;
     g.lds_lcg = ((size_t)8 << lg) + fixed_lcg;
@@ -99,8 +127,8 @@ Layout make_layout(const Geometry &g)
     l.ring = take((size_t)g.m * (size_t)g.row_bytes);
     l.partial = take((size_t)g.sp_grid * g.m * sizeof(double2));
     // candidate lists exist for the global Top-k only
-    l.cand_idx = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(int32_t));
-    l.cand_val = take(g.kb ? 0 : (size_t)g.n_sel_blocks * kCandBlock * sizeof(float));
+    l.cand_idx = take(g.kb ? 0 : (size_t)g.n_slices * g.slice * sizeof(int32_t));
+    l.cand_val = take(g.kb ? 0 : (size_t)g.n_slices * g.slice * sizeof(float));
     l.e = take((size_t)g.d * sizeof(float));
     l.offT = take((size_t)(g.n_slices + 1) * g.m * sizeof(int32_t));
     l.S = take((size_t)g.m * g.m * sizeof(double));
@@ -110,13 +138,13 @@ Layout make_layout(const Geometry &g)
     l.q = take((size_t)g.m * sizeof(double));
     l.coef = take((size_t)g.m * sizeof(double));
     l.rowmax = take((size_t)g.m * sizeof(uint32_t));
-    l.hist = take((size_t)(kBins1 + 2 * kHistPriv * kBins2) * sizeof(uint32_t));
+    l.hist = take((size_t)(kHist1Copies * kBins1 + 2 * kHistPriv * kBins2) * sizeof(uint32_t));
     l.sel = take(sizeof(SelState));
-    l.cnt_gt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
-    l.cnt_eq = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
-    l.sel_off = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
-    l.eq_before = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
-    l.cand_cnt = take((size_t)g.n_sel_blocks * sizeof(uint32_t));
+    l.cnt_gt = take((size_t)g.n_slices * sizeof(uint32_t));
+    l.cnt_eq = take((size_t)g.n_slices * sizeof(uint32_t));
+    l.sel_off = take((size_t)g.n_slices * sizeof(uint32_t));
+    l.eq_before = take((size_t)g.n_slices * sizeof(uint32_t));
+    l.cand_cnt = take((size_t)g.n_slices * sizeof(uint32_t));
     l.blk_max = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
     l.blk_tlo = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
     l.lam = take(g.ggt ? (size_t)g.m * sizeof(double) : 0);
@@ -289,7 +317,7 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     p.coef = reinterpret_cast<double *>(b + l.coef);
     p.rowmax = reinterpret_cast<uint32_t *>(b + l.rowmax);
     p.hist1 = reinterpret_cast<uint32_t *>(b + l.hist);
-    p.hist2 = p.hist1 + kBins1;
+    p.hist2 = p.hist1 + kHist1Copies * kBins1;
     p.hist3 = p.hist2 + kHistPriv * kBins2;
     p.sel = reinterpret_cast<SelState *>(b + l.sel);
     p.cnt_gt = reinterpret_cast<uint32_t *>(b + l.cnt_gt);
@@ -497,7 +525,7 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
         return (int32_t)v;
     };
     for (int32_t s = 0; s < g.n_slices; s++) {
-        const int32_t base = s << g.slice_log2;
+        const int32_t base = s * g.slice;
         for (int32_t p = offs[s]; p < offs[s + 1]; p++) idx_host[p] = base + stored_index(p);
     }
     for (int64_t p = 0; p < g.k; p++) {
@@ -673,7 +701,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     st.t_lo = h.t_lo;
     if (rc == hipSuccess) rc = hipMemcpy(p.sel, &st, sizeof st, hipMemcpyHostToDevice);
     if (rc == hipSuccess) rc = hipMemcpy(p.status, &h.status, 4, hipMemcpyHostToDevice);
-    if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, kBins1 * sizeof(uint32_t));
+    if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, (size_t)kHist1Copies * kBins1 * sizeof(uint32_t));
     // where each block starts counting is a hint only: start from "count everything"
     if (rc == hipSuccess && g.kb) rc = hipMemset(p.blk_tlo, 0, (size_t)g.n_slices * sizeof(uint32_t));
     // Sparse GGT: the decomposition that efcp_apply replays is rebuilt from the imported S
@@ -681,6 +709,13 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
     ctx->pending_slot = -1;                          // an exported e is final
+    return EFCP_OK;
+}
+
+extern "C" int efcp_tune_slice_width(int32_t width)
+{
+    if (width != 0 && (width < 256 || width > kCandBlock || width % 256 != 0)) return EFCP_EINVAL;
+    g_slice_width.store(width);
     return EFCP_OK;
 }
 

@@ -13,14 +13,16 @@
 //                                        row inside one slice is one contiguous piece of memory
 //   offT      int32  [n_slices+1][m]     offT[s][r] = first entry of row r whose
 //                                        index is >= s*slice (slice-major so one
-//                                        workgroup reads its m offsets contiguously)
+//                                        workgroup reads its m offsets contiguously).
+//                                        slice = Geometry::slice coordinates, a multiple of
+//                                        256 and at most 16,384, fixed when the context is made
 //   S         double [m][m]              Gram matrix by slot
 //   W         double [m rows][ldm]       inverse of the Cholesky factor of
 //                                        m*lambda*I + S (rows in age order), stored
 //                                        row-major by slot; zero above the diagonal
 //                                        in age order and for unfilled slots
-//   cand_*    [ceil(d/16384)][16384]      Top-k candidates of the current step, one
-//                                        segment per block of 16,384 coordinates
+//   cand_*    [n_slices][slice]          Top-k candidates of the current step, one
+//                                        segment per slice
 //                                        (global Top-k only; block-wise Top-k keeps
 //                                        two uint32 per block instead)
 //   partial   double2[sp_grid][m]        per-workgroup (q, Gram) partial sums
@@ -34,11 +36,14 @@
 namespace efcp {
 
 constexpr int kSelChunk = 4096;      // coordinates a 256-thread block streams at a time
-constexpr int kCandBlock = 16384;    // coordinates per candidate segment (== slice width)
+constexpr int kCandBlock = 16384;    // widest d-slice (its accumulators fill the LDS); block of the block-wise Top-k
+constexpr int kMinSlice = 1024;      // narrowest slice chosen automatically
+constexpr int kMaxWgs = 256;         // persistent SP / LCG workgroups at most: 32 on each of 8 XCDs
 constexpr int kSelThreads = 256;     // threads per select/compaction block
 constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
 constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
+constexpr int kHist1Copies = 4;      // copies of the first digit's histogram that the blocks add into
 constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
 constexpr int kHistPriv = 128;       // private histograms of the candidate passes
 constexpr int kGgtMaxM = 128;        // largest window of the Sparse GGT path (its matrix lives in LDS)
@@ -152,8 +157,7 @@ struct Geometry {
     int32_t ggt;             // 0: Sparse M-FAC coefficients; 1: Sparse GGT
     int32_t m, ldm;
     int32_t fmt;             // kFmtF32 / kFmtBf16
-    int32_t slice, slice_log2, n_slices;
-    int32_t n_sel_blocks;
+    int32_t slice, n_slices; // coordinates per d-slice (multiple of 256, <= kCandBlock), number of slices
     int32_t sp_grid;         // persistent SP workgroups: 8 * (workgroups per XCD)
     size_t lds_sp, lds_lcg;
 };
@@ -169,9 +173,9 @@ struct DevicePtrs {
     uint32_t *hist1, *hist2, *hist3;
     SelState *sel;
     uint32_t *cnt_gt, *cnt_eq, *sel_off, *eq_before;
-    int32_t *cand_idx;       // [n_sel_blocks][kCandBlock] candidate indices, ascending per segment
-    float *cand_val;         // [n_sel_blocks][kCandBlock] candidate values
-    uint32_t *cand_cnt;      // [n_sel_blocks] entries used per segment
+    int32_t *cand_idx;       // [n_slices][slice] candidate indices, ascending per segment
+    float *cand_val;         // [n_slices][slice] candidate values
+    uint32_t *cand_cnt;      // [n_slices] entries used per segment
     uint32_t *blk_max;       // [n_slices] largest key per block          (block-wise Top-k only)
     uint32_t *blk_tlo;       // [n_slices] where each block's first histogram starts counting
     double *lam;             // [m] eigenvalues of S                      (Sparse GGT only)

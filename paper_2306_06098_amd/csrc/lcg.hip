@@ -71,7 +71,7 @@ __device__ __forceinline__ void lcg_scatter(const typename Fmt<FMT>::iraw_t &iv,
 template <int FMT, bool XDENSE, bool UPDATE>
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
                                               int64_t d, int32_t m, int32_t n_filled, int64_t row_stride,
-                                              int32_t slice_log2, int32_t nsl, int32_t cpx,
+                                              int32_t slice, int32_t nsl, int32_t cpx,
                                               const uint8_t *__restrict__ ring,
                                               const int32_t *__restrict__ offT,
                                               const double *__restrict__ coef,
@@ -81,9 +81,10 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
 {
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
-    const int32_t slice = 1 << slice_log2;
-    unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem);   // [slice]
-    double *cf = reinterpret_cast<double *>(acc + slice);                     // [1024]
+    // `slice` coordinates (a multiple of 256, at most kCandBlock) are live; the LDS layout is that
+    // of the widest slice
+    unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem);   // [kCandBlock]
+    double *cf = reinterpret_cast<double *>(acc + kCandBlock);                // [1024]
     int32_t *offs = reinterpret_cast<int32_t *>(cf + kMaxM);                  // [2 buffers][2][1024]
     __shared__ double wsum[16];
 
@@ -92,13 +93,13 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
     const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
-    const int32_t mask = slice - 1;
+    const int32_t mask = kCandBlock - 1;
     if (sl.count == 0) return;                // uniform: this workgroup has no slice
     int32_t it = 0;
     int32_t s = sl.at(0);
     const int32_t trow = min(tid, m - 1);     // row whose offsets this thread fetches
 
-    for (int32_t i = tid; i < slice; i += 1024) acc[i] = 0ull;
+    for (int32_t i = tid; i < kCandBlock; i += 1024) acc[i] = 0ull;
     double cabs = 0.0;
     {
         offs[tid] = offT[(int64_t)s * m + trow];
@@ -165,12 +166,14 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     first(ba);
     load(ba);                                 // first batch of the first slice
     int buf = 0;
-    // One slice.  FULL: all 16384 coordinates exist, so x and out move as unconditional 16-byte
-    // accesses and the compiler can keep exact counts of the loads in flight.  The ragged last
-    // slice of the vector (at most one, and the last one of its workgroup) takes the guarded path.
+    // One slice.  FULL: all its coordinates exist, so x and out move as 16-byte accesses, the
+    // loads unconditional (past a narrow slice's end the last four coordinates are read again and
+    // the result is not stored), and the compiler can keep exact counts of the loads in flight.
+    // The ragged last slice of the vector (at most one, and the last one of its workgroup) takes
+    // the guarded path.
     auto do_slice = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const int64_t base64 = (int64_t)s << slice_log2;
+        const int64_t base64 = (int64_t)s * slice;
         const int32_t len = FULL ? slice : (int32_t)(d - base64);
         const int32_t snx = it + 1 < sl.count ? sl.at(it + 1) : s;     // this workgroup's next slice
         auto consume = [&](const LcgBatch<FMT> &b) {
@@ -187,7 +190,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         if (FULL && XDENSE) {
 #pragma unroll
             for (int u = 0; u < 4; u++)
-                xr[u] = load_stream_f4(x + base64 + tid * 4 + u * 4096);
+                xr[u] = load_stream_f4(x + base64 + min(tid * 4 + u * 4096, slice - 4));
         }
         const int32_t o0 = offT[(int64_t)snx * m + trow];
         const int32_t o1 = offT[(int64_t)(snx + 1) * m + trow];
@@ -215,7 +218,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         if (FULL && UPDATE) {
 #pragma unroll
             for (int u = 0; u < 4; u++)
-                th[u] = load_stream_f4(out + base64 + tid * 4 + u * 4096);
+                th[u] = load_stream_f4(out + base64 + min(tid * 4 + u * 4096, slice - 4));
         }
         __syncthreads();            // all rows of this slice are in the accumulators; offn visible
 
@@ -246,7 +249,8 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
                                      UPDATE ? th[u].w : 0.f};
 #pragma unroll
                 for (int q = 0; q < 4; q++) o[q] = result(xv[q], tv[q], acc[i + q]);
-                store_stream_f4(out + base64 + i, make_float4(o[0], o[1], o[2], o[3]));
+                if (i < slice)                // the same for all lanes of a wave
+                    store_stream_f4(out + base64 + i, make_float4(o[0], o[1], o[2], o[3]));
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         __syncthreads();            // accumulators are zero before the next slice scatters
     };
 
-    const int32_t n_full = (int32_t)(d >> slice_log2);            // slices with all coordinates
+    const int32_t n_full = (int32_t)(d / slice);                  // slices with all coordinates
     // the ragged slice, if this workgroup has it, is the last of its list
     const int32_t n_mine_full = sl.count - (sl.at(sl.count - 1) >= n_full ? 1 : 0);
     for (; it < n_mine_full; it++) {
@@ -293,7 +297,7 @@ void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float
                    double lambda, const LcgMode &md, hipStream_t stream)
 {
     hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
-                       g.d, g.m, n_filled, g.row_stride, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                       g.d, g.m, n_filled, g.row_stride, g.slice, g.n_slices, g.sp_grid / 8,
                        p.ring, p.offT,
                        p.coef, p.rowmax, p.status, 1.0 / lambda, md.x_row, md.decay, md.lr);
 }

@@ -29,8 +29,9 @@
 
 namespace efcp {
 
-// Streaming layout of a d-sized pass: a block owns kCandBlock = 16,384
-// consecutive coordinates, walked as 4 chunks of 4,096; inside a chunk wave w
+// Streaming layout of a d-sized pass: a block owns one d-slice (`blk`
+// consecutive coordinates, a multiple of 256 and at most 16,384), walked in
+// chunks of 4,096; inside a chunk wave w
 // owns 1,024 consecutive coordinates and lane l holds, for it = 0..3, the four
 // coordinates wave_first + it*256 + l*4 + (0..3), loaded as one 16-byte load.
 // All four loads of a lane are issued before any is used.
@@ -79,7 +80,8 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                                                          float *__restrict__ cand_val,
                                                          uint32_t *__restrict__ cand_cnt,
                                                          const uint8_t *__restrict__ pend_row,
-                                                         const int32_t *__restrict__ pend_off, int32_t m)
+                                                         const int32_t *__restrict__ pend_off, int32_t m,
+                                                         int32_t blk)
 {
     __shared__ uint32_t lh[REDO ? 1 : kBins1];
     __shared__ uint32_t s_cnt[2][4];
@@ -109,26 +111,35 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
         return 0.0f;
     };
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int64_t block_first = (int64_t)blockIdx.x * kCandBlock;
+    const int64_t block_first = (int64_t)blockIdx.x * blk;
+    const int64_t block_end = block_first + blk < d ? block_first + blk : d;
     int32_t *seg_idx = cand_idx + block_first;
     float *seg_val = cand_val + block_first;
     uint32_t used = 0;                                    // entries of the segment written so far
 
-    for (int cch = 0; cch < kCandBlock / kSelChunk; cch++) {
+    for (int cch = 0; cch * kSelChunk < blk; cch++) {
         const int64_t wave_first = block_first + cch * kSelChunk + w * 1024;
         const int64_t wave_base = wave_first + lane * 4;
-        const bool full = wave_first + 1024 <= d;        // scalar: whole wave inside the vector
+        // Lanes hold whole 16-byte pieces wherever the wave's part of the block ends on a multiple
+        // of 256 coordinates (always, except in the last block of a vector of ragged length):
+        // nit of the wave's four 256-coordinate pieces exist.
+        const int64_t rem = block_end - wave_first;        // scalar
         float a[4][4];
-        if (full) {
+        uint32_t inmask;                                   // bit it*4+c: the coordinate exists
+        auto vector_pieces = [&](const int nit) {
             float4 ev[4], gv[4];
 #pragma unroll
             for (int it = 0; it < 4; it++) {
-                ev[it] = load_stream_f4(e + wave_base + it * 256);
-                if (!REDO) gv[it] = load_stream_f4(g + wave_base + it * 256);
+                ev[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (it < nit) {
+                    ev[it] = load_stream_f4(e + wave_base + it * 256);
+                    if (!REDO) gv[it] = load_stream_f4(g + wave_base + it * 256);
+                }
             }
 #pragma unroll
             for (int it = 0; it < 4; it++) {
-                if (PEND) {
+                if (PEND && it < nit) {
                     // the four coordinates of this load share one word of the bitmap
                     const uint32_t q = (uint32_t)(cch * kSelChunk + w * 1024 + it * 256 + lane * 4);
                     const uint32_t bits4 = (pend[q >> 5] >> (q & 31u)) & 15u;
@@ -144,18 +155,28 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                     a[it][1] = ev[it].y + gv[it].y;
                     a[it][2] = ev[it].z + gv[it].z;
                     a[it][3] = ev[it].w + gv[it].w;
-                    store_stream_f4(e + wave_base + it * 256,
-                                    make_float4(a[it][0], a[it][1], a[it][2], a[it][3]));
+                    if (it < nit)
+                        store_stream_f4(e + wave_base + it * 256,
+                                        make_float4(a[it][0], a[it][1], a[it][2], a[it][3]));
                 }
             }
+        };
+        if (rem >= 1024) {
+            vector_pieces(4);
+            inmask = 0xffffu;
+        } else if (rem <= 0 || (rem & 255) == 0) {
+            const int nit = rem <= 0 ? 0 : (int)(rem >> 8);
+            vector_pieces(nit);
+            inmask = (1u << (4 * nit)) - 1u;
         } else {
+            inmask = 0;
 #pragma unroll
             for (int it = 0; it < 4; it++) {
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
                     const int64_t j = wave_base + it * 256 + c;
                     float t = 0.0f;
-                    if (j < d) {
+                    if (j < block_end) {
                         float ej = e[j];
                         if (PEND) {
                             const uint32_t q = (uint32_t)(j - block_first);
@@ -163,6 +184,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                         }
                         t = REDO ? ej : ej + g[j];
                         if (!REDO) e[j] = t;
+                        inmask |= 1u << (it * 4 + c);
                     }
                     a[it][c] = t;
                 }
@@ -174,8 +196,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
 #pragma unroll
             for (int c = 0; c < 4; c++) {
                 const uint32_t key = mag_key(a[it][c]);
-                const bool in = full || (wave_base + it * 256 + c < d);
-                if (in) {
+                if ((inmask >> (it * 4 + c)) & 1u) {
                     if (!REDO) atomicAdd(&lh[key >> 20], 1u);
                     if (key >= t_lo) flags |= 1u << (it * 4 + c);
                 }
@@ -197,16 +218,19 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
     if (threadIdx.x == 0) cand_cnt[blockIdx.x] = used;
     if (!REDO) {
         __syncthreads();
+        // Most keys fall into a few dozen bins, which every block adds to at about the same time:
+        // the adds to one address queue up, so the blocks are spread over kHist1Copies histograms.
+        uint32_t *mine = hist + (blockIdx.x % kHist1Copies) * kBins1;
         for (int i = threadIdx.x; i < kBins1; i += kSelThreads) {
             const uint32_t c = lh[i];
-            if (c) atomicAdd(&hist[i], c);
+            if (c) atomicAdd(&mine[i], c);
         }
     }
 }
 
 // ------------------------------------------------------------------
 // Histogram of the next 10-bit digit over the candidates whose higher key
-// bits equal the prefix found so far.  kHistGroups workgroups of 16 waves; a
+// bits equal the prefix found so far.  `groups` (at most kHistGroups) workgroups of 16 waves; a
 // wave takes one candidate segment at a time.  Every workgroup stores its own
 // 1024-bin histogram (no global atomics: device-scope atomics on a few hot
 // addresses from thousands of waves serialise); k_pick_digit adds them up.
@@ -216,7 +240,7 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ ca
                                                     const uint32_t *__restrict__ cand_cnt, int32_t nb,
                                                     const SelState *__restrict__ sel,
                                                     uint32_t *__restrict__ hist_priv, int shift_hi,
-                                                    int shift_lo)
+                                                    int shift_lo, int32_t blk, int32_t groups)
 {
     __shared__ uint32_t lh[kBins2];
     lh[threadIdx.x] = 0;
@@ -228,9 +252,9 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ ca
     int32_t b = blockIdx.x * 16 + w;
     uint32_t cnt = b < nb ? cand_cnt[b] : 0u;
     while (b < nb) {
-        const int32_t bn = b + kHistGroups * 16;
+        const int32_t bn = b + groups * 16;
         const uint32_t cnt_next = cand_cnt[min(bn, nb - 1)];
-        const float *seg = cand_val + (int64_t)b * kCandBlock;
+        const float *seg = cand_val + (int64_t)b * blk;
         for (uint32_t i0 = 0; i0 < cnt; i0 += 512) {
             float v[8];
 #pragma unroll
@@ -256,7 +280,8 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ ca
 template <int NB>
 __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist,
                                                      SelState *__restrict__ sel, int pass,
-                                                     uint32_t k, uint32_t *__restrict__ rowmax_slot)
+                                                     uint32_t k, uint32_t *__restrict__ rowmax_slot,
+                                                     int32_t groups)
 {
     __shared__ uint32_t tmp[33];
     __shared__ int top_bin;
@@ -268,20 +293,36 @@ __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist
     const uint32_t t_lo = sel->t_lo;
 
     // Walk the bins from the largest digit down: rb = NB-1-bin.
-    // pass 0: `hist` is one histogram filled by atomics (cleared here for the next step);
-    // passes 1, 2: `hist` holds kHistGroups private histograms to add up.
+    // pass 0: `hist` holds kHist1Copies histograms filled by atomics (cleared here for the next step);
+    // passes 1, 2: `hist` holds `groups` private histograms to add up.
     uint32_t c[PER];
     uint32_t local = 0;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int bin = NB - 1 - (threadIdx.x * PER + i);
         if (pass == 0) {
-            c[i] = hist[bin];
-            hist[bin] = 0;
+            uint32_t v[kHist1Copies];
+#pragma unroll
+            for (int u = 0; u < kHist1Copies; u++) v[u] = hist[u * NB + bin];
+            uint32_t t = 0;
+#pragma unroll
+            for (int u = 0; u < kHist1Copies; u++) {
+                t += v[u];
+                if (v[u]) hist[u * NB + bin] = 0;
+            }
+            c[i] = t;
             if (c[i]) atomicMax(&top_bin, bin);
         } else {
             uint32_t t = 0;
-            for (int g = 0; g < kHistGroups; g++) t += hist[(int64_t)g * NB + bin];
+            int g = 0;
+            for (; g + 8 <= groups; g += 8) {             // eight independent loads at a time
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) v[u] = hist[(int64_t)(g + u) * NB + bin];
+#pragma unroll
+                for (int u = 0; u < 8; u++) t += v[u];
+            }
+            for (; g < groups; g++) t += hist[(int64_t)g * NB + bin];
             c[i] = t;
         }
         local += c[i];
@@ -323,14 +364,14 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_count(const float *__restr
                                                             const uint32_t *__restrict__ cand_cnt,
                                                             int32_t nb, const SelState *__restrict__ sel,
                                                             uint32_t *__restrict__ cnt_gt,
-                                                            uint32_t *__restrict__ cnt_eq)
+                                                            uint32_t *__restrict__ cnt_eq, int32_t blk)
 {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int32_t b = blockIdx.x * 4 + w;
     if (b >= nb) return;
     const uint32_t tau = sel->tau;
     const uint32_t cnt = cand_cnt[b];
-    const float *seg = cand_val + (int64_t)b * kCandBlock;
+    const float *seg = cand_val + (int64_t)b * blk;
     uint32_t g = 0, q = 0;
     for (uint32_t i0 = 0; i0 < cnt; i0 += 512) {
         float v[8];
@@ -353,13 +394,12 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_count(const float *__restr
 // One workgroup: exclusive scans over the candidate segments.
 //   eq_before[b] = number of keys == tau in segments before b
 //   sel_off[b]   = number of selected entries in segments before b
-// and the slice offsets of the new row: offT[s][slot] = sel_off[first segment of slice s].
+// and the slice offsets of the new row: offT[s][slot] = sel_off[s] (a segment is a slice).
 __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict__ cnt_gt,
                                                       const uint32_t *__restrict__ cnt_eq,
                                                       uint32_t *__restrict__ sel_off,
                                                       uint32_t *__restrict__ eq_before,
                                                       SelState *__restrict__ sel, int32_t nb,
-                                                      int32_t blocks_per_slice, int32_t n_slices,
                                                       int32_t m, int32_t slot,
                                                       int32_t *__restrict__ offT, uint32_t k,
                                                       uint32_t *__restrict__ status)
@@ -395,8 +435,7 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
             if (b + i < nb) {
                 eq_before[b + i] = eb[i];
                 sel_off[b + i] = run2;
-                if ((b + i) % blocks_per_slice == 0)
-                    offT[(int64_t)((b + i) / blocks_per_slice) * m + slot] = (int32_t)run2;
+                offT[(int64_t)(b + i) * m + slot] = (int32_t)run2;
             }
             run2 += sc[i];
         }
@@ -404,7 +443,7 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
         carry_sel += total_sel;
     }
     if (threadIdx.x == 0) {
-        offT[(int64_t)n_slices * m + slot] = (int32_t)carry_sel;
+        offT[(int64_t)nb * m + slot] = (int32_t)carry_sel;
         sel->total = carry_sel;
         if (carry_sel != k) atomicOr(status, kStatusCount);
     }
@@ -423,16 +462,16 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
                                                               const SelState *__restrict__ sel,
                                                               const uint32_t *__restrict__ sel_off,
                                                               const uint32_t *__restrict__ eq_before,
-                                                              uint8_t *__restrict__ row)
+                                                              uint8_t *__restrict__ row, int32_t blk)
 {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int32_t b = blockIdx.x * 4 + w;
     if (b >= nb) return;
-    const int32_t seg_first = b * kCandBlock;
+    const int32_t seg_first = b * blk;
     const uint32_t tau = sel->tau, quota = sel->quota;
     const uint32_t cnt = cand_cnt[b];
-    const int32_t *sidx = cand_idx + (int64_t)b * kCandBlock;
-    const float *sval = cand_val + (int64_t)b * kCandBlock;
+    const int32_t *sidx = cand_idx + (int64_t)b * blk;
+    const float *sval = cand_val + (int64_t)b * blk;
     uint32_t eq_run = eq_before[b];
     uint32_t out_run = sel_off[b];
     for (uint32_t i0 = 0; i0 < cnt; i0 += 256) {
@@ -477,37 +516,39 @@ hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *g
     const uint8_t *pidx = pending_slot >= 0 ? p.ring + (int64_t)pending_slot * g.row_bytes : nullptr;
     const int32_t *poff = pending_slot >= 0 ? p.offT + pending_slot : nullptr;
     if (pending_slot < 0)
-        hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
-                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m);
+        hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_slices), dim3(kSelThreads), 0, stream, grad, p.e,
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
     else if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
-                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m);
+        hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_slices), dim3(kSelThreads), 0, stream, grad, p.e,
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
     else
-        hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_sel_blocks), dim3(kSelThreads), 0, stream, grad, p.e,
-                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m);
+        hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_slices), dim3(kSelThreads), 0, stream, grad, p.e,
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
     return hipGetLastError();
 }
 
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
-    const int32_t nb = g.n_sel_blocks;
+    const int32_t nb = g.n_slices;
+    // one wave per candidate segment until every private histogram is in use
+    const int32_t groups = (nb + 15) / 16 < kHistGroups ? (nb + 15) / 16 : kHistGroups;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
-                       (uint32_t)g.k, p.rowmax + slot);
+                       (uint32_t)g.k, p.rowmax + slot, groups);
     hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
                        p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint8_t *)nullptr,
-                       (const int32_t *)nullptr, g.m);
-    hipLaunchKernelGGL(k_cand_hist, dim3(kHistGroups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
-                       p.sel, p.hist2, 20, 10);
+                       (const int32_t *)nullptr, g.m, g.slice);
+    hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
+                       p.sel, p.hist2, 20, 10, g.slice, groups);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
-                       (uint32_t)g.k, p.rowmax + slot);
-    hipLaunchKernelGGL(k_cand_hist, dim3(kHistGroups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
-                       p.sel, p.hist3, 10, 0);
+                       (uint32_t)g.k, p.rowmax + slot, groups);
+    hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
+                       p.sel, p.hist3, 10, 0, g.slice, groups);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist3, p.sel, 2,
-                       (uint32_t)g.k, p.rowmax + slot);
+                       (uint32_t)g.k, p.rowmax + slot, groups);
     hipLaunchKernelGGL(k_cand_count, dim3((nb + 3) / 4), dim3(kSelThreads), 0, stream, p.cand_val,
-                       p.cand_cnt, nb, p.sel, p.cnt_gt, p.cnt_eq);
+                       p.cand_cnt, nb, p.sel, p.cnt_gt, p.cnt_eq, g.slice);
     hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, stream, p.cnt_gt, p.cnt_eq, p.sel_off,
-                       p.eq_before, p.sel, nb, g.slice / kCandBlock, g.n_slices, g.m, slot, p.offT,
+                       p.eq_before, p.sel, nb, g.m, slot, p.offT,
                        (uint32_t)g.k, p.status);
     return hipGetLastError();
 }
@@ -515,13 +556,13 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, h
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
 {
     if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
-                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.sel, p.sel_off,
-                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes);
+        hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
+                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
+                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice);
     else
-        hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_sel_blocks + 3) / 4), dim3(kSelThreads), 0,
-                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_sel_blocks, p.sel, p.sel_off,
-                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes);
+        hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
+                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
+                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice);
     return hipGetLastError();
 }
 

@@ -55,7 +55,7 @@ __device__ __forceinline__ void sp_accumulate(const typename Fmt<FMT>::iraw_t &i
     }
 }
 
-constexpr int kMaxSlicesPerWg = 512;     // ceil(2^31 / 16384 / 8 / 32)
+constexpr int kMaxSlicesPerWg = 512;     // ceil(2^31 / 16384 / 8 / 32); narrower slices: checked at creation
 
 // What the staged pair (x_j, c_new_j) holds:
 //   kXDense    x from memory, newest row scattered next to it      (step with x = gradient)
@@ -78,7 +78,7 @@ enum : int { kXDense = 0, kXNewest = 1, kXOnly = 2 };
 template <int FMT, int XM>
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              int32_t n_filled, int32_t slot, int64_t row_stride,
-                                             int64_t k, int32_t slice_log2, int32_t nsl, int32_t cpx,
+                                             int64_t k, int32_t slice, int32_t nsl, int32_t cpx,
                                              const uint8_t *__restrict__ ring,
                                              const int32_t *__restrict__ offT,
                                              double2 *__restrict__ partial)
@@ -87,9 +87,10 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     using val_t = typename Fmt<FMT>::val_t;
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
-    const int32_t slice = 1 << slice_log2;
-    float2 *xc = reinterpret_cast<float2 *>(smem);                 // [slice]: (x_j, c_new_j); [slice] = (0, 0)
-    double2 *racc = reinterpret_cast<double2 *>(xc + slice + 2);   // [1024] per-row sums
+    // `slice` coordinates (a multiple of 256, at most kCandBlock) are live; the LDS layout is that
+    // of the widest slice
+    float2 *xc = reinterpret_cast<float2 *>(smem);       // [kCandBlock]: (x_j, c_new_j); [kCandBlock] = (0, 0)
+    double2 *racc = reinterpret_cast<double2 *>(xc + kCandBlock + 2);   // [1024] per-row sums
     int32_t *off0 = reinterpret_cast<int32_t *>(racc + kMaxM);     // [1024]
     int32_t *off1 = off0 + kMaxM;                                  // [1024]
     int32_t *np0 = off1 + kMaxM;                                   // [kMaxSlicesPerWg] newest row's run
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
     const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
-    const int32_t mask = slice - 1;
+    const int32_t mask = kCandBlock - 1;
     const int32_t trow = min(tid, m - 1);
     constexpr int64_t kEntryBytes = Fmt<FMT>::kEntryBytes;
     uint8_t *nrow = const_cast<uint8_t *>(ring) + (int64_t)slot * row_stride * kEntryBytes;   // newest row (read only)
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int32_t klast = (int32_t)(k - 1);
 
     racc[tid] = make_double2(0.0, 0.0);
-    if (tid == 0) xc[slice] = make_float2(0.0f, 0.0f);             // what entries outside a run gather
+    if (tid == 0) xc[kCandBlock] = make_float2(0.0f, 0.0f);        // what entries outside a run gather
     if (sl.count == 0) {                      // uniform: no slice for this workgroup
         if (tid < m) partial[(int64_t)blockIdx.x * m + tid] = make_double2(0.0, 0.0);
         return;
@@ -132,13 +133,15 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 
     auto prefetch = [&](int32_t sp, int32_t ip, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const int64_t b64 = (int64_t)sp << slice_log2;
+        const int64_t b64 = (int64_t)sp * slice;
         if (XM == kXNewest) {
 #pragma unroll
             for (int u = 0; u < 4; u++) xr[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         } else if (FULL) {
+            // unconditional; past a narrow slice's end the last four coordinates are read again
+            // into LDS positions that no entry of the slice points at
 #pragma unroll
-            for (int u = 0; u < 4; u++) xr[u] = load_stream_f4(x + b64 + tid * 4 + u * 4096);
+            for (int u = 0; u < 4; u++) xr[u] = load_stream_f4(x + b64 + min(tid * 4 + u * 4096, slice - 4));
         } else {
             const int32_t len = (int32_t)(d - b64);
 #pragma unroll
@@ -159,7 +162,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         }
     };
 
-    const int32_t n_full = (int32_t)(d >> slice_log2);           // slices with all coordinates
+    const int32_t n_full = (int32_t)(d / slice);                 // slices with all coordinates
     __syncthreads();                          // np0/np1 visible, racc zeroed
     if (s < n_full) prefetch(s, 0, std::true_type{}); else prefetch(s, 0, std::false_type{});
 
@@ -297,7 +300,7 @@ void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, int32_
                   hipStream_t stream)
 {
     hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled,
-                       slot, g.row_stride, g.k, g.slice_log2, g.n_slices, g.sp_grid / 8,
+                       slot, g.row_stride, g.k, g.slice, g.n_slices, g.sp_grid / 8,
                        p.ring, p.offT, p.partial);
 }
 

@@ -4,6 +4,8 @@ import ctypes
 import os
 import re
 
+import pytest
+
 from paper_2306_06098_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -40,6 +42,21 @@ def test_null_context_is_rejected_without_a_gpu():
     assert lib.efcp_destroy(None) == binding.EFCP_OK
     assert lib.efcp_step(None, None, None, None) == binding.EFCP_EINVAL
     assert lib.efcp_last_error(None) == b"null context"
+
+
+def test_slice_width_knob_validates_without_a_gpu():
+    """efcp_tune_slice_width is host state only: 0 or a multiple of 256 in [256, 16384]."""
+    from paper_2306_06098_amd import binding
+    lib = binding.load_library()
+    try:
+        for ok in (0, 256, 1024, 14_592, 16_384):
+            assert lib.efcp_tune_slice_width(ok) == 0
+        for bad in (-256, 1, 128, 255, 1000, 16_640, 32_768):
+            assert lib.efcp_tune_slice_width(bad) != 0
+        with pytest.raises(binding.EfcpError):
+            binding.tune_slice_width(100)
+    finally:
+        assert lib.efcp_tune_slice_width(0) == 0
 
 
 def test_row_length_arithmetic_matches_the_oracle(oracle_mod):

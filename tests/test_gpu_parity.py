@@ -87,6 +87,50 @@ def test_shapes_and_edges(env, d, m, k, lam, T, bf16):
     print((d, m, k, bf16), w)
 
 
+@pytest.mark.parametrize("width", [256, 1024, 4352, 12_544, 16_384])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_slice_widths(env, width, bf16):
+    """The d-slice width is a tuning knob (efcp_tune_slice_width): slices of 256 up to 16,384
+    coordinates, widths that end in the middle of a wave's part of a block and in the middle of a
+    4,096-coordinate chunk, d not a multiple of any of them; every variant of the step."""
+    torch, oracle_mod, binding = env
+    d, m, k, lam, T = 150_011, 6, 1_500, 1e-3, 14
+    rng = np.random.default_rng(width)
+    scale = np.exp(rng.standard_normal(d)).astype(np.float32)
+
+    def grads():
+        z = np.zeros(d, np.float32)
+        for _ in range(T):
+            z = (0.7 * z + rng.standard_normal(d)).astype(np.float32)
+            yield scale * z
+    binding.tune_slice_width(width)
+    try:
+        g = binding.Efcp(d, m, k, lam)
+        geo = g.geometry()
+        g.destroy()
+        assert geo["slice"] == width and geo["n_slices"] == -(-d // width)
+        w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16, apply_every=5)
+        w2 = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16, compressed=True,
+                        update=(0.05, 0.01))
+    finally:
+        binding.tune_slice_width(0)
+    print(width, bf16, w, w2)
+
+
+def test_slice_width_is_chosen_from_d(env):
+    """Automatic width: short vectors are cut into (up to) 256 slices of at least 1,024
+    coordinates, vectors of a few rounds into a multiple of 256 equal slices, Top-k in blocks
+    keeps the block."""
+    torch, oracle_mod, binding = env
+    for d, kw, want in [(5_000, {}, 1024), (272_474, {}, 1280), (11_200_000, {}, 14_592),
+                        (4_194_304, {}, 16_384), (4_194_305, {}, 8_448),
+                        (272_474, dict(topk_block=binding.TOPK_BLOCK), 16_384)]:
+        g = binding.Efcp(d, 2, 3, 1e-3, **kw)
+        geo = g.geometry()
+        g.destroy()
+        assert geo["slice"] == want and geo["n_slices"] == -(-d // want), (d, geo)
+
+
 def test_random_shapes_sweep(env):
     """Thirty seeded random (d, m, k, lambda) with d from a handful of elements to
     several slices plus a ragged tail, k from 1 to d, windows that fill and evict;
