@@ -13,8 +13,8 @@
  *   e    = a - c                            +0 where selected, a_j elsewhere
  *   slot (t-1) mod m of the window <- c     (index, fp32 value) pairs, indices
  *                                           ascending, oldest row replaced.  In memory an
- *                                           index is its 16-bit position inside the
- *                                           16384-coordinate slice it falls in (the slice
+ *                                           index is its 16-bit position inside the d-slice
+ *                                           (at most 16384 coordinates) it falls in (the slice
  *                                           follows from a per-row offset table): lossless,
  *                                           6 bytes per entry instead of 8; efcp_get_row
  *                                           returns plain int32 indices

@@ -9,13 +9,13 @@
 // Only the first pass touches the whole vector.  While it forms a = e + g and
 // the histogram of the first digit, it also copies every element whose key is
 // at least t_lo -- a bin edge two bins below the previous step's threshold --
-// to a candidate list, in index order, one segment per block of 16,384
-// coordinates.  All later passes (two digit histograms, per-block counts and
+// to a candidate list, in index order, one segment per block (a d-slice, at
+// most 16,384 coordinates).  All later passes (two digit histograms, per-block counts and
 // the ordered compaction into the ring) read the candidates only: a few
 // percent of d.  e = a - c is not finished by this step: clearing k scattered
 // entries costs a partial HBM write each, so the buffer keeps a, and the NEXT
 // step's first pass, which rewrites e anyway, drops the entries of the row
-// inserted last (a bitmap in LDS per block of 16,384 coordinates).  Host code
+// inserted last (a bitmap in LDS, one bit per coordinate of the block).  Host code
 // that reads e in between applies the same rule.  The first-digit histogram
 // is exact, so it tells whether the threshold bin lies at or above t_lo; if it
 // does not (the threshold dropped by more than two bins in one step), one
