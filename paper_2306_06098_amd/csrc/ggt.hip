@@ -27,8 +27,11 @@ __device__ __forceinline__ void rr_pair(int32_t N, int32_t r, int32_t j, int32_t
         a = N - 1;
         b = r;
     } else {
-        a = (r + j) % (N - 1);
-        b = (r - j + (N - 1)) % (N - 1);
+        // r < N-1 and j < N/2: one conditional step replaces the division of a modulo
+        a = r + j;
+        if (a >= N - 1) a -= N - 1;
+        b = r - j;
+        if (b < 0) b += N - 1;
     }
     p = a < b ? a : b;
     q = a < b ? b : a;
@@ -48,9 +51,7 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t 
     extern __shared__ __align__(16) unsigned char smem[];
     double *A = reinterpret_cast<double *>(smem);                          // [kGgtMaxM][kGgtLd]
     double2 *cs = reinterpret_cast<double2 *>(A + kGgtMaxM * kGgtLd);      // [64]
-    int32_t *pp = reinterpret_cast<int32_t *>(cs + 64);                    // [64]
-    int32_t *qq = pp + 64;                                                 // [64]
-    int32_t *n_rot = qq + 64;                                              // [1]
+    int32_t *n_rot = reinterpret_cast<int32_t *>(cs + 64);                 // [1] rotations of this sweep
 
     const int tid = threadIdx.x;
     if (update) {
@@ -71,6 +72,30 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t 
     if (tid == 0) *n_rot = 0;
     __syncthreads();
 
+    // The 2x2 blocks a thread updates are the same pairs of pairs (k1 <= k2) in every stage; found
+    // once, which keeps integer divisions out of the stages.  Only the blocks on and above the
+    // diagonal of the pair grid are computed: A stays symmetric, the block (k2, k1) is the
+    // transpose of (k1, k2) and is written along with it.  What limits a stage is LDS traffic,
+    // and this way a pair of blocks costs 4 reads and 8 writes instead of 8 and 8, with one
+    // fetch of the two rotations instead of two.
+    constexpr int kPairsMax = kGgtMaxM / 2;
+    constexpr int kBlocksPerThread = (kPairsMax * (kPairsMax + 1) / 2 + 1023) / 1024;
+    int32_t bk1[kBlocksPerThread], bk2[kBlocksPerThread];
+#pragma unroll
+    for (int i = 0; i < kBlocksPerThread; i++) {
+        int32_t rem = tid + i * 1024, k1 = 0;
+        bk1[i] = -1;
+        bk2[i] = 0;
+        if (rem < half * (half + 1) / 2) {
+            while (rem >= half - k1) {        // row k1 of the triangle holds half - k1 blocks
+                rem -= half - k1;
+                k1++;
+            }
+            bk1[i] = k1;
+            bk2[i] = k1 + rem;
+        }
+    }
+
     int32_t stage_out = 0;
     for (int32_t sweep = 0; sweep < max_sweeps; sweep++) {
         for (int32_t r = 0; r < N - 1; r++) {
@@ -82,26 +107,43 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t 
                     if (q < n) {
                         const double apq = A[p * kGgtLd + q];
                         const double app = A[p * kGgtLd + p], aqq = A[q * kGgtLd + q];
-                        if (apq != 0.0 && fabs(apq) > 0x1p-54 * sqrt(fabs(app) * fabs(aqq))) {
-                            const double tau = (aqq - app) / (2.0 * apq);
-                            const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
-                            c = 1.0 / sqrt(1.0 + t * t);
-                            s = t * c;
-                            atomicAdd(n_rot, 1);
+                        // Scaled by a power of two so that the largest of the two diagonal entries is in
+                        // [1, 2): squares below neither overflow nor lose a pair that matters.
+                        const double dmax = fmax(fabs(app), fabs(aqq));
+                        if (apq != 0.0 && dmax > 0.0 && dmax < 1.0e300) {
+                            const int ex = ilogb(dmax);
+                            const double as = ldexp(apq, -ex), ps = ldexp(app, -ex), qs = ldexp(aqq, -ex);
+                            // at rest when |apq| <= 2^-54 sqrt(|app aqq|), compared in squares
+                            if (as * as > 0x1p-108 * fabs(ps * qs)) {
+                                // t = tan of the rotation angle, the smaller root of t^2 + 2 tau t - 1 = 0,
+                                // tau = (aqq - app) / (2 apq): t = sign(tau) / (|tau| + sqrt(1 + tau^2))
+                                //     = apq sign(h) / (|h| + sqrt(h^2 + apq^2)),  h = (aqq - app) / 2
+                                // (one square root and one division; h = 0 gives t = +-1)
+                                const double h = 0.5 * (qs - ps);
+                                const double hy = sqrt(h * h + as * as);
+                                const double t = (h >= 0.0 ? as : -as) / (fabs(h) + hy);
+                                c = rsqrt(1.0 + t * t);
+                                s = t * c;
+                                atomicAdd(n_rot, 1);
+                            }
                         }
                     }
                 }
-                pp[tid] = p;
-                qq[tid] = q;
                 cs[tid] = make_double2(c, s);
                 rot[(int64_t)stage_out * 64 + tid] = make_double2(c, s);
             }
             __syncthreads();
-            // A <- J^T A J, one 2x2 block per (row pair, column pair); all blocks are disjoint
-            for (int32_t b = tid; b < half * half; b += 1024) {
-                const int32_t k1 = b / half, k2 = b - k1 * half;
-                const int32_t p1 = pp[k1], q1 = qq[k1], p2 = pp[k2], q2 = qq[k2];
+            // A <- J^T A J, one 2x2 block per (row pair, column pair) and its mirror image; all
+            // blocks are disjoint.  The pairs are recomputed rather than fetched from LDS.
+#pragma unroll
+            for (int i = 0; i < kBlocksPerThread; i++) {
+                const int32_t k1 = bk1[i], k2 = bk2[i];
+                if (k1 < 0) continue;
+                int32_t p1, q1, p2, q2;
+                rr_pair(N, r, k1, p1, q1);
+                rr_pair(N, r, k2, p2, q2);
                 const double2 r1 = cs[k1], r2 = cs[k2];
+                if (r1.y == 0.0 && r2.y == 0.0) continue;   // both pairs at rest (late sweeps): block unchanged
                 const double b00 = A[p1 * kGgtLd + p2], b01 = A[p1 * kGgtLd + q2];
                 const double b10 = A[q1 * kGgtLd + p2], b11 = A[q1 * kGgtLd + q2];
                 const double t00 = r2.x * b00 - r2.y * b01, t01 = r2.y * b00 + r2.x * b01;
@@ -113,6 +155,12 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t 
                 A[p1 * kGgtLd + q2] = n01;
                 A[q1 * kGgtLd + p2] = n10;
                 A[q1 * kGgtLd + q2] = n11;
+                if (k1 != k2) {
+                    A[p2 * kGgtLd + p1] = n00;
+                    A[q2 * kGgtLd + p1] = n01;
+                    A[p2 * kGgtLd + q1] = n10;
+                    A[q2 * kGgtLd + q1] = n11;
+                }
             }
             __syncthreads();
             stage_out++;
@@ -178,25 +226,27 @@ __global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, int32_t n, double ep
     }
     __syncthreads();
     // backwards: stage st used r = st mod (N-1)
+    int32_t rb = stages > 0 ? (stages - 1) % (N - 1) : 0;
     nxt = stages > 0 ? rot[(int64_t)(stages - 1) * 64 + lane] : make_double2(1.0, 0.0);
     for (int32_t st = stages - 1; st >= 0; st--) {
         const double2 cur = nxt;
         if (st > 0) nxt = rot[(int64_t)(st - 1) * 64 + lane];
         if (lane < half && cur.y != 0.0) {
             int32_t p, q;
-            rr_pair(N, st % (N - 1), lane, p, q);
+            rr_pair(N, rb, lane, p, q);
             const double zp = y[p], zq = y[q];
             y[p] = cur.x * zp + cur.y * zq;
             y[q] = -cur.y * zp + cur.x * zq;
         }
         __syncthreads();
+        rb = rb == 0 ? N - 2 : rb - 1;
     }
     for (int32_t i = lane; i < m; i += 64) coef_out[i] = i < n ? y[i] : 0.0;
 }
 
 size_t ggt_eig_lds_bytes()
 {
-    return (size_t)kGgtMaxM * kGgtLd * sizeof(double) + 64 * sizeof(double2) + 2 * 64 * sizeof(int32_t) + 16;
+    return (size_t)kGgtMaxM * kGgtLd * sizeof(double) + 64 * sizeof(double2) + 16;
 }
 
 hipError_t configure_ggt()
