@@ -348,6 +348,15 @@ def test_export_import_resumes_bit_identically(env):
             b.import_state(blob[: blob.size // 2])
         for ctx in (a, b, c):
             ctx.destroy()
+    # a context cut into slices of another width refuses the blob as well
+    binding.tune_slice_width(2048)
+    try:
+        c = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16)
+        with pytest.raises(binding.EfcpError):
+            c.import_state(blob)
+        c.destroy()
+    finally:
+        binding.tune_slice_width(0)
 
 
 def test_argument_checks(env):
