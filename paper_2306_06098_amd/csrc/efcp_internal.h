@@ -35,11 +35,10 @@
 
 namespace efcp {
 
-constexpr int kSelChunk = 4096;      // coordinates a 256-thread block streams at a time
 constexpr int kCandBlock = 16384;    // widest d-slice (its accumulators fill the LDS); block of the block-wise Top-k
 constexpr int kMinSlice = 1024;      // narrowest slice chosen automatically
 constexpr int kMaxWgs = 256;         // persistent SP / LCG workgroups at most: 32 on each of 8 XCDs
-constexpr int kSelThreads = 256;     // threads per select/compaction block
+constexpr int kSelThreads = 256;     // threads per candidate count / compaction block (a wave per segment)
 constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
 constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20

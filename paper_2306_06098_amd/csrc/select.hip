@@ -31,7 +31,8 @@ namespace efcp {
 
 // Streaming layout of a d-sized pass: a block owns one d-slice (`blk`
 // consecutive coordinates, a multiple of 256 and at most 16,384), walked in
-// chunks of 4,096; inside a chunk wave w
+// chunks of 8,192 by 512 threads (measured against 256 and 1024 threads per
+// block: 0.252 / 0.250 / 0.291 ms at d = 110M); inside a chunk wave w
 // owns 1,024 consecutive coordinates and lane l holds, for it = 0..3, the four
 // coordinates wave_first + it*256 + l*4 + (0..3), loaded as one 16-byte load.
 // All four loads of a lane are issued before any is used.
@@ -71,8 +72,12 @@ __device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t
 // PEND (first pass only): `e` still holds the previous step's accumulator; the entries of the
 // row inserted then (pend_row, the run of this block given by two entries of its offset column)
 // count as +0, or as the rounding remainder a - bf16(a) when the window keeps bfloat16 values.
+constexpr int kEfThreads = 512;                  // threads of a first-pass block
+constexpr int kEfWaves = kEfThreads / 64;
+constexpr int kEfChunk = kEfWaves * 1024;        // coordinates the block streams at a time
+
 template <bool REDO, int PEND>
-__global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict__ g,
+__global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict__ g,
                                                          float *__restrict__ e, int64_t d,
                                                          uint32_t *__restrict__ hist,
                                                          const SelState *__restrict__ sel,
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
                                                          int32_t blk)
 {
     __shared__ uint32_t lh[REDO ? 1 : kBins1];
-    __shared__ uint32_t s_cnt[2][4];
+    __shared__ uint32_t s_cnt[2][kEfWaves];
     __shared__ uint32_t pend[PEND ? kCandBlock / 32 : 1];       // one bit per coordinate of the block
     uint32_t t_lo;
     if (REDO) {
@@ -92,12 +97,12 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
         t_lo = sel->prefix << 20;
     } else {
         t_lo = sel->t_lo;
-        for (int i = threadIdx.x; i < kBins1; i += kSelThreads) lh[i] = 0;
+        for (int i = threadIdx.x; i < kBins1; i += kEfThreads) lh[i] = 0;
         if (PEND) {
-            for (int i = threadIdx.x; i < kCandBlock / 32; i += kSelThreads) pend[i] = 0;
+            for (int i = threadIdx.x; i < kCandBlock / 32; i += kEfThreads) pend[i] = 0;
             __syncthreads();
             const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
-            for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kSelThreads) {
+            for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kEfThreads) {
                 constexpr int PF = PEND == 2 ? kFmtBf16 : kFmtF32;
                 const uint32_t pos = *entry_idx_ptr<PF>(const_cast<uint8_t *>(pend_row), (uint32_t)p);
                 atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
@@ -117,8 +122,8 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
     float *seg_val = cand_val + block_first;
     uint32_t used = 0;                                    // entries of the segment written so far
 
-    for (int cch = 0; cch * kSelChunk < blk; cch++) {
-        const int64_t wave_first = block_first + cch * kSelChunk + w * 1024;
+    for (int cch = 0; cch * kEfChunk < blk; cch++) {
+        const int64_t wave_first = block_first + cch * kEfChunk + w * 1024;
         const int64_t wave_base = wave_first + lane * 4;
         // Lanes hold whole 16-byte pieces wherever the wave's part of the block ends on a multiple
         // of 256 coordinates (always, except in the last block of a vector of ragged length):
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
             for (int it = 0; it < 4; it++) {
                 if (PEND && it < nit) {
                     // the four coordinates of this load share one word of the bitmap
-                    const uint32_t q = (uint32_t)(cch * kSelChunk + w * 1024 + it * 256 + lane * 4);
+                    const uint32_t q = (uint32_t)(cch * kEfChunk + w * 1024 + it * 256 + lane * 4);
                     const uint32_t bits4 = (pend[q >> 5] >> (q & 31u)) & 15u;
                     if (bits4 & 1u) ev[it].x = settled(ev[it].x);
                     if (bits4 & 2u) ev[it].y = settled(ev[it].y);
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
         __syncthreads();
         uint32_t base = used, total = 0;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
+        for (int i = 0; i < kEfWaves; i++) {
             const uint32_t c = s_cnt[cch & 1][i];
             if (i < w) base += c;
             total += c;
@@ -221,7 +226,7 @@ __global__ __launch_bounds__(kSelThreads) void k_ef_hist(const float *__restrict
         // Most keys fall into a few dozen bins, which every block adds to at about the same time:
         // the adds to one address queue up, so the blocks are spread over kHist1Copies histograms.
         uint32_t *mine = hist + (blockIdx.x % kHist1Copies) * kBins1;
-        for (int i = threadIdx.x; i < kBins1; i += kSelThreads) {
+        for (int i = threadIdx.x; i < kBins1; i += kEfThreads) {
             const uint32_t c = lh[i];
             if (c) atomicAdd(&mine[i], c);
         }
@@ -516,13 +521,13 @@ hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *g
     const uint8_t *pidx = pending_slot >= 0 ? p.ring + (int64_t)pending_slot * g.row_bytes : nullptr;
     const int32_t *poff = pending_slot >= 0 ? p.offT + pending_slot : nullptr;
     if (pending_slot < 0)
-        hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_slices), dim3(kSelThreads), 0, stream, grad, p.e,
+        hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
                            g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
     else if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_slices), dim3(kSelThreads), 0, stream, grad, p.e,
+        hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
                            g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
     else
-        hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_slices), dim3(kSelThreads), 0, stream, grad, p.e,
+        hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
                            g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
     return hipGetLastError();
 }
@@ -534,7 +539,7 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, h
     const int32_t groups = (nb + 15) / 16 < kHistGroups ? (nb + 15) / 16 : kHistGroups;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
                        (uint32_t)g.k, p.rowmax + slot, groups);
-    hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kSelThreads), 0, stream, (const float *)nullptr,
+    hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kEfThreads), 0, stream, (const float *)nullptr,
                        p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint8_t *)nullptr,
                        (const int32_t *)nullptr, g.m, g.slice);
     hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
