@@ -26,8 +26,9 @@
  *          (unfilled slots are zero rows, the divisor stays m).
  *
  * All pointers named "device" are HIP device pointers on the device that was
- * current when efcp_create ran; pointers named "host" are ordinary host
- * memory.  Every function returns EFCP_OK (0) or a negative efcp_status; no
+ * current when efcp_create ran, and that device has to be current in every
+ * later call on the context (EFCP_EINVAL otherwise; efcp_destroy switches to it
+ * by itself and back); pointers named "host" are ordinary host memory.  Every function returns EFCP_OK (0) or a negative efcp_status; no
  * function throws, aborts or prints.  A context may be used by one host
  * thread at a time.
  */

@@ -196,6 +196,16 @@ static int fail(efcp_ctx *ctx, int code, const char *msg)
     return code;
 }
 
+// Every call on a context needs the device it was created on to be current: its memory, side
+// stream and events live there.
+static int wrong_device(efcp_ctx *ctx)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(ctx, EFCP_EHIP, "no current HIP device");
+    if (dev != ctx->device) return fail(ctx, EFCP_EINVAL, "the device of efcp_create is not current");
+    return EFCP_OK;
+}
+
 static size_t workspace_bytes(int64_t d, int32_t m, int64_t k, int32_t value_format, int32_t topk_block,
                               int32_t ggt)
 {
@@ -377,6 +387,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
                             double lr, double weight_decay, void *stream_v)
 {
     if (!ctx) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     if (!grad) return fail(ctx, EFCP_EINVAL, "grad is NULL");
     if (x_source != EFCP_X_GRAD && x_source != EFCP_X_COMPRESSED)
         return fail(ctx, EFCP_EINVAL, "unknown x_source");
@@ -451,6 +462,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
 extern "C" int efcp_apply(efcp_ctx *ctx, const float *x, float *outp, void *stream_v)
 {
     if (!ctx) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     if (!x || !outp) return fail(ctx, EFCP_EINVAL, "x or out is NULL");
     if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(outp) & 15))
         return fail(ctx, EFCP_EINVAL, "x/out not 16-byte aligned");
@@ -482,12 +494,17 @@ extern "C" int efcp_destroy(efcp_ctx *ctx)
 {
     if (!ctx) return EFCP_OK;
     int rcode = EFCP_OK;
+    // the context's device is made current for the clean-up and the caller's restored afterwards
+    int cur = ctx->device;
+    (void)hipGetDevice(&cur);
+    if (cur != ctx->device && hipSetDevice(ctx->device) != hipSuccess) rcode = EFCP_EHIP;
     if (hipDeviceSynchronize() != hipSuccess) rcode = EFCP_EHIP;
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
     (void)hipStreamDestroy(ctx->side);
     if (ctx->own_ws && hipFree(ctx->ws) != hipSuccess) rcode = EFCP_EHIP;
+    if (cur != ctx->device) (void)hipSetDevice(cur);
     delete ctx;
     return rcode;
 }
@@ -502,6 +519,7 @@ static int sync_last(efcp_ctx *ctx)
 extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, float *val_host)
 {
     if (!ctx || !idx_host || !val_host) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     const Geometry &g = ctx->g;
     const int64_t filled = ctx->t < g.m ? ctx->t : g.m;
     if (slot < 0 || slot >= filled) return fail(ctx, EFCP_EINVAL, "slot not filled");
@@ -560,6 +578,7 @@ static int settle_error(efcp_ctx *ctx, float *e_host)
 extern "C" int efcp_get_error(efcp_ctx *ctx, float *e_host)
 {
     if (!ctx || !e_host) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     if (int rc = sync_last(ctx)) return rc;
     if (hipMemcpy(e_host, ctx->p.e, (size_t)ctx->g.d * 4, hipMemcpyDeviceToHost) != hipSuccess)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
@@ -570,6 +589,7 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
                               uint32_t *tau, int64_t *step)
 {
     if (!ctx) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     if (int rc = sync_last(ctx)) return rc;
     const Geometry &g = ctx->g;
     hipError_t rc = hipSuccess;
@@ -621,6 +641,7 @@ extern "C" size_t efcp_state_bytes(efcp_ctx *ctx) { return ctx ? state_bytes(ctx
 extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
 {
     if (!ctx || !host_buf) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     if (bytes < state_bytes(ctx)) return fail(ctx, EFCP_ENOMEM, "state buffer too small");
     if (reinterpret_cast<uintptr_t>(host_buf) & 7) return fail(ctx, EFCP_EINVAL, "state buffer not 8-byte aligned");
     if (int rc = sync_last(ctx)) return rc;
@@ -666,6 +687,7 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
 extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes)
 {
     if (!ctx || !host_buf) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
     if (bytes < sizeof(StateHeader)) return fail(ctx, EFCP_EINVAL, "state buffer truncated");
     StateHeader h;
     std::memcpy(&h, host_buf, sizeof h);
