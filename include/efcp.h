@@ -117,7 +117,9 @@ size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_f
                                 int32_t topk_block);
 
 /* One step (see the top of this file).
- *   grad    device, d floats, 16-byte aligned, read only
+ *   grad    device, d floats, 16-byte aligned, read only.  Meant to be finite.  Infinities
+ *           and NaN are not rejected: Top-k orders them by their bits (above every finite
+ *           value), e = a - c turns them into NaN, and S, q, coef and out are then NaN too
  *   out     device, d floats, 16-byte aligned, receives F^-1 grad; must not
  *           overlap grad.  NULL: the state (e, window, S, the coefficient
  *           factor, q, coef) is updated exactly as usual but F^-1 grad is not

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
                 *entry_idx_ptr<FMT>(row, pos) = (uint16_t)i;       // position inside the slice
                 if constexpr (FMT == kFmtF32) {
                     *entry_val_ptr<FMT>(row, pos) = av;
-                    rest = 0.0f;
+                    rest = av - av;                              // a - c: +0 for every finite a
                 } else {
                     const uint32_t hb = bf16_bits(av);
                     *entry_val_ptr<FMT>(row, pos) = (uint16_t)hb;

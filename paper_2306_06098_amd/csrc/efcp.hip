@@ -570,7 +570,7 @@ static int settle_error(efcp_ctx *ctx, float *e_host)
     if (int rc = efcp_get_row(ctx, ctx->pending_slot, idx.data(), val.data())) return rc;
     for (int64_t p = 0; p < g.k; p++) {
         float &ej = e_host[idx[(size_t)p]];
-        ej = g.fmt == kFmtBf16 ? ej - val[(size_t)p] : 0.0f;     // val is bf16(a) there, ej is a
+        ej = ej - val[(size_t)p];                 // ej is a, val the stored a or bf16(a): +0 or the remainder
     }
     return EFCP_OK;
 }

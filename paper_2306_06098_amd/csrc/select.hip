@@ -111,9 +111,10 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
         __syncthreads();
     }
     // value of e at a coordinate whose pending bit is set
+    // a - c as written (Algorithm 1, line 7): +0 for every finite a, NaN for an infinite one
     auto settled = [](float a) {
         if (PEND == 2) return a - __uint_as_float(bf16_bits(a) << 16);
-        return 0.0f;
+        return a - a;
     };
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t block_first = (int64_t)blockIdx.x * blk;

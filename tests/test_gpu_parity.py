@@ -156,6 +156,47 @@ def test_random_shapes_sweep(env):
         print(case, (d, m, k, lam, T, quant), w["out"])
 
 
+@pytest.mark.parametrize("topk_block", [0, 16_384])
+def test_non_finite_gradient_entries_are_ordered_by_their_bits(env, topk_block):
+    """Infinities and NaN are not rejected: their magnitude keys (0x7f800000, 0x7fc00000) sort
+    above every finite value, so they are selected like any other large entry, e = a - c makes
+    them NaN, and later steps select those again.  Indices must agree exactly; values and e
+    bit for bit except that any NaN matches any NaN (the two machines sign the NaN of inf - inf
+    differently).  The preconditioned output is meaningless from then on and is not looked at."""
+    torch, oracle_mod, binding = env
+    d, m, lam = 50_003, 4, 1e-3
+    k = 40 if topk_block else 500
+    rng = np.random.default_rng(77)
+    o = oracle_mod.Oracle(d, m, k, lam, block=topk_block)
+    ctx = binding.Efcp(d, m, k, lam, topk_block=topk_block)
+    g_d = torch.empty(d, dtype=torch.float32, device="cuda:0")
+    out_d = torch.empty_like(g_d)
+
+    def same(a, b):
+        a, b = np.asarray(a, np.float32), np.asarray(b, np.float32)
+        return bool(np.all((bits(a) == bits(b)) | (np.isnan(a) & np.isnan(b))))
+    try:
+        for t in range(6):
+            g = rng.standard_normal(d).astype(np.float32)
+            if t == 2:
+                g[100], g[20_000], g[33_333] = np.inf, -np.inf, np.float32(np.nan)
+            o.step(g)
+            g_d.copy_(torch.from_numpy(g))
+            ctx.step(g_d, out_d)
+            torch.cuda.synchronize()
+            slot = t % m
+            idx, val = ctx.get_row(slot)
+            oi, ov = o.row(slot)
+            assert np.array_equal(idx, oi), f"step {t + 1}: indices differ"
+            assert same(val, ov), f"step {t + 1}: values differ"
+            assert same(ctx.get_error(), o.error), f"step {t + 1}: error feedback differs"
+            if t >= 2:
+                assert np.isin([100, 20_000, 33_333], idx).all()
+    finally:
+        ctx.destroy()
+        o.close()
+
+
 def test_forced_ties_integer_gradients(env):
     """Small-integer gradients: the threshold magnitude is shared by many
     coordinates on every step, so the lowest-index tie rule decides."""
