@@ -31,14 +31,14 @@ int64_t block_row_length(int64_t d, int64_t kb)
 // Width of the d-slices that the SP and LCG workgroups stage in LDS, which are also the blocks of
 // the Top-k passes.  With Top-k in blocks it is the block.  Otherwise: the widest slice leaves
 // the persistent workgroups with unequal numbers of slices (684 slices of 16,384 over 256
-// workgroups: three rounds, the last one two thirds empty), which costs up to 1/rounds of the SP
-// and LCG passes.  Up to kBalanceRounds rounds the vector is therefore cut into a multiple of
+// workgroups: three rounds, the last one two thirds empty; 1,288 slices: six rounds, the last one
+// with 8 slices), which costs up to 1/rounds of the SP and LCG passes.  When the rounds would hold
+// at least 4 % more slices than there are, the vector is therefore cut into a multiple of
 // kMaxWgs nearly equal slices: the fewest rounds that the LDS allows, every workgroup in every
-// round; short vectors get narrow slices for the same reason, all workgroups take part.  Longer
-// vectors keep the widest slice: the imbalance is small there, and the first Top-k pass pays a
-// fixed cost per block (measured at d = 110M: 5 % slower with 16,128-wide blocks than with 16,384).
+// round; short vectors get narrow slices by the same rule, all workgroups take part.  Below 4 %
+// the widest slice stays: the first Top-k pass pays a fixed cost per block (measured at
+// d = 110M, 2.9 %: SP 1.5 % faster, that pass 5 % slower with 16,128-wide blocks, no net gain).
 // No result depends on the width except the order of the fp64 sums of the SP pass.
-constexpr int kBalanceRounds = 4;
 std::atomic<int32_t> g_slice_width{0};             // efcp_tune_slice_width: 0 = automatic
 
 int32_t pick_slice_width(int64_t d, int32_t kb)
@@ -48,7 +48,7 @@ int32_t pick_slice_width(int64_t d, int32_t kb)
     if (forced) return forced;
     const int64_t widest = (d + kCandBlock - 1) / kCandBlock;
     const int64_t rounds = (widest + kMaxWgs - 1) / kMaxWgs;
-    if (rounds > kBalanceRounds) return kCandBlock;
+    if ((rounds * kMaxWgs - widest) * 25 < widest) return kCandBlock;
     int64_t w = (d + kMaxWgs * rounds - 1) / (kMaxWgs * rounds);
     w = (w + 255) / 256 * 256;
     if (w < kMinSlice) w = kMinSlice;

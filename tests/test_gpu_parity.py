@@ -119,11 +119,13 @@ def test_slice_widths(env, width, bf16):
 
 def test_slice_width_is_chosen_from_d(env):
     """Automatic width: short vectors are cut into (up to) 256 slices of at least 1,024
-    coordinates, vectors of a few rounds into a multiple of 256 equal slices, Top-k in blocks
-    keeps the block."""
+    coordinates; longer ones into a multiple of 256 equal slices when rounds of 256 widest
+    slices would be at least 4 % empty, else into widest slices; Top-k in blocks keeps the
+    block."""
     torch, oracle_mod, binding = env
     for d, kw, want in [(5_000, {}, 1024), (272_474, {}, 1280), (11_200_000, {}, 14_592),
                         (4_194_304, {}, 16_384), (4_194_305, {}, 8_448),
+                        (21_100_000, {}, 13_824), (110_000_000, {}, 16_384),
                         (272_474, dict(topk_block=binding.TOPK_BLOCK), 16_384)]:
         g = binding.Efcp(d, 2, 3, 1e-3, **kw)
         geo = g.geometry()
