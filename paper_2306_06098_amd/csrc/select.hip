@@ -400,7 +400,9 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_count(const float *__restr
 // One workgroup: exclusive scans over the candidate segments.
 //   eq_before[b] = number of keys == tau in segments before b
 //   sel_off[b]   = number of selected entries in segments before b
-// and the slice offsets of the new row: offT[s][slot] = sel_off[s] (a segment is a slice).
+// and the end of the new row's offset column, offT[n_slices][slot] = k; the other entries of
+// the column (offT[s][slot] = sel_off[s]: a segment is a slice) are strided single stores, which
+// the compaction kernel spreads over its waves.
 __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict__ cnt_gt,
                                                       const uint32_t *__restrict__ cnt_eq,
                                                       uint32_t *__restrict__ sel_off,
@@ -440,8 +442,7 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
         for (int i = 0; i < 4; i++) {
             if (b + i < nb) {
                 eq_before[b + i] = eb[i];
-                sel_off[b + i] = run2;
-                offT[(int64_t)(b + i) * m + slot] = (int32_t)run2;
+                sel_off[b + i] = run2;           // k_cand_compact copies it into the offset table
             }
             run2 += sc[i];
         }
@@ -468,7 +469,9 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
                                                               const SelState *__restrict__ sel,
                                                               const uint32_t *__restrict__ sel_off,
                                                               const uint32_t *__restrict__ eq_before,
-                                                              uint8_t *__restrict__ row, int32_t blk)
+                                                              uint8_t *__restrict__ row, int32_t blk,
+                                                              int32_t *__restrict__ offT, int32_t m,
+                                                              int32_t slot)
 {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int32_t b = blockIdx.x * 4 + w;
@@ -480,6 +483,7 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
     const float *sval = cand_val + (int64_t)b * blk;
     uint32_t eq_run = eq_before[b];
     uint32_t out_run = sel_off[b];
+    if (lane == 0) offT[(int64_t)b * m + slot] = (int32_t)out_run;     // where this slice's run starts
     for (uint32_t i0 = 0; i0 < cnt; i0 += 256) {
         float vv[4];
         int32_t jj[4];
@@ -564,11 +568,11 @@ hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, 
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
-                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice);
+                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice, p.offT, g.m, slot);
     else
         hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
-                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice);
+                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice, p.offT, g.m, slot);
     return hipGetLastError();
 }
 
