@@ -138,7 +138,7 @@ Layout make_layout(const Geometry &g)
     l.q = take((size_t)g.m * sizeof(double));
     l.coef = take((size_t)g.m * sizeof(double));
     l.rowmax = take((size_t)g.m * sizeof(uint32_t));
-    l.hist = take((size_t)(kHist1Copies * kBins1 + 2 * kHistPriv * kBins2) * sizeof(uint32_t));
+    l.hist = take((size_t)kHist1Copies * (kBins1 + 2 * kBins2) * sizeof(uint32_t));
     l.sel = take(sizeof(SelState));
     l.cnt_gt = take((size_t)g.n_slices * sizeof(uint32_t));
     l.cnt_eq = take((size_t)g.n_slices * sizeof(uint32_t));
@@ -328,7 +328,7 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     p.rowmax = reinterpret_cast<uint32_t *>(b + l.rowmax);
     p.hist1 = reinterpret_cast<uint32_t *>(b + l.hist);
     p.hist2 = p.hist1 + kHist1Copies * kBins1;
-    p.hist3 = p.hist2 + kHistPriv * kBins2;
+    p.hist3 = p.hist2 + kHist1Copies * kBins2;
     p.sel = reinterpret_cast<SelState *>(b + l.sel);
     p.cnt_gt = reinterpret_cast<uint32_t *>(b + l.cnt_gt);
     p.cnt_eq = reinterpret_cast<uint32_t *>(b + l.cnt_eq);
@@ -723,7 +723,7 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     st.t_lo = h.t_lo;
     if (rc == hipSuccess) rc = hipMemcpy(p.sel, &st, sizeof st, hipMemcpyHostToDevice);
     if (rc == hipSuccess) rc = hipMemcpy(p.status, &h.status, 4, hipMemcpyHostToDevice);
-    if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, (size_t)kHist1Copies * kBins1 * sizeof(uint32_t));
+    if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, (size_t)kHist1Copies * (kBins1 + 2 * kBins2) * sizeof(uint32_t));
     // where each block starts counting is a hint only: start from "count everything"
     if (rc == hipSuccess && g.kb) rc = hipMemset(p.blk_tlo, 0, (size_t)g.n_slices * sizeof(uint32_t));
     // Sparse GGT: the decomposition that efcp_apply replays is rebuilt from the imported S

@@ -42,9 +42,9 @@ constexpr int kSelThreads = 256;     // threads per candidate count / compaction
 constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
 constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
-constexpr int kHist1Copies = 4;      // copies of the first digit's histogram that the blocks add into
+constexpr int kHist1Copies = 4;      // copies of a digit's histogram that the blocks add into
 constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
-constexpr int kHistPriv = 128;       // private histograms of the candidate passes
+constexpr int kHistGroups = 1024;    // workgroups of a candidate histogram pass at most
 constexpr int kGgtMaxM = 128;        // largest window of the Sparse GGT path (its matrix lives in LDS)
 constexpr int kGgtMaxSweeps = 30;    // Jacobi sweeps at most (a sweep without rotations ends earlier)
 

@@ -237,10 +237,10 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
 // ------------------------------------------------------------------
 // Histogram of the next 10-bit digit over the candidates whose higher key
 // bits equal the prefix found so far.  `groups` (at most kHistGroups) workgroups of 16 waves; a
-// wave takes one candidate segment at a time.  Every workgroup stores its own
-// 1024-bin histogram (no global atomics: device-scope atomics on a few hot
-// addresses from thousands of waves serialise); k_pick_digit adds them up.
-constexpr int kHistGroups = kHistPriv;
+// wave takes one candidate segment at a time.  Every workgroup counts in its own
+// 1024-bin histogram in LDS (device-scope atomics on a few hot addresses from
+// thousands of waves serialise) and adds it once, at the end, into one of
+// kHist1Copies histograms in memory; k_pick_digit adds those up and clears them.
 
 __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ cand_val,
                                                     const uint32_t *__restrict__ cand_cnt, int32_t nb,
@@ -276,7 +276,8 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ ca
         cnt = cnt_next;
     }
     __syncthreads();
-    hist_priv[(int64_t)blockIdx.x * kBins2 + threadIdx.x] = lh[threadIdx.x];
+    const uint32_t c = lh[threadIdx.x];
+    if (c) atomicAdd(&hist_priv[(blockIdx.x % kHist1Copies) * kBins2 + threadIdx.x], c);
 }
 
 // ------------------------------------------------------------------
@@ -286,8 +287,7 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ ca
 template <int NB>
 __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist,
                                                      SelState *__restrict__ sel, int pass,
-                                                     uint32_t k, uint32_t *__restrict__ rowmax_slot,
-                                                     int32_t groups)
+                                                     uint32_t k, uint32_t *__restrict__ rowmax_slot)
 {
     __shared__ uint32_t tmp[33];
     __shared__ int top_bin;
@@ -298,39 +298,24 @@ __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist
     const uint32_t prefix = (pass == 0) ? 0u : sel->prefix;
     const uint32_t t_lo = sel->t_lo;
 
-    // Walk the bins from the largest digit down: rb = NB-1-bin.
-    // pass 0: `hist` holds kHist1Copies histograms filled by atomics (cleared here for the next step);
-    // passes 1, 2: `hist` holds `groups` private histograms to add up.
+    // Walk the bins from the largest digit down: rb = NB-1-bin.  `hist` holds kHist1Copies
+    // histograms filled by atomics; they are added up here and cleared for the next step.
     uint32_t c[PER];
     uint32_t local = 0;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int bin = NB - 1 - (threadIdx.x * PER + i);
-        if (pass == 0) {
-            uint32_t v[kHist1Copies];
+        uint32_t v[kHist1Copies];
 #pragma unroll
-            for (int u = 0; u < kHist1Copies; u++) v[u] = hist[u * NB + bin];
-            uint32_t t = 0;
+        for (int u = 0; u < kHist1Copies; u++) v[u] = hist[u * NB + bin];
+        uint32_t t = 0;
 #pragma unroll
-            for (int u = 0; u < kHist1Copies; u++) {
-                t += v[u];
-                if (v[u]) hist[u * NB + bin] = 0;
-            }
-            c[i] = t;
-            if (c[i]) atomicMax(&top_bin, bin);
-        } else {
-            uint32_t t = 0;
-            int g = 0;
-            for (; g + 8 <= groups; g += 8) {             // eight independent loads at a time
-                uint32_t v[8];
-#pragma unroll
-                for (int u = 0; u < 8; u++) v[u] = hist[(int64_t)(g + u) * NB + bin];
-#pragma unroll
-                for (int u = 0; u < 8; u++) t += v[u];
-            }
-            for (; g < groups; g++) t += hist[(int64_t)g * NB + bin];
-            c[i] = t;
+        for (int u = 0; u < kHist1Copies; u++) {
+            t += v[u];
+            if (v[u]) hist[u * NB + bin] = 0;
         }
+        c[i] = t;
+        if (pass == 0 && t) atomicMax(&top_bin, bin);
         local += c[i];
     }
     uint32_t total;
@@ -543,18 +528,18 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, h
     // one wave per candidate segment until every private histogram is in use
     const int32_t groups = (nb + 15) / 16 < kHistGroups ? (nb + 15) / 16 : kHistGroups;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
-                       (uint32_t)g.k, p.rowmax + slot, groups);
+                       (uint32_t)g.k, p.rowmax + slot);
     hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kEfThreads), 0, stream, (const float *)nullptr,
                        p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint8_t *)nullptr,
                        (const int32_t *)nullptr, g.m, g.slice);
     hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
                        p.sel, p.hist2, 20, 10, g.slice, groups);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
-                       (uint32_t)g.k, p.rowmax + slot, groups);
+                       (uint32_t)g.k, p.rowmax + slot);
     hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
                        p.sel, p.hist3, 10, 0, g.slice, groups);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist3, p.sel, 2,
-                       (uint32_t)g.k, p.rowmax + slot, groups);
+                       (uint32_t)g.k, p.rowmax + slot);
     hipLaunchKernelGGL(k_cand_count, dim3((nb + 3) / 4), dim3(kSelThreads), 0, stream, p.cand_val,
                        p.cand_cnt, nb, p.sel, p.cnt_gt, p.cnt_eq, g.slice);
     hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, stream, p.cnt_gt, p.cnt_eq, p.sel_off,
