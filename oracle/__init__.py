@@ -59,6 +59,8 @@ def _load():
     lib.eo_destroy.argtypes = [vp]
     lib.eo_step.restype = ctypes.c_int
     lib.eo_step.argtypes = [vp, vp, vp, vp]
+    lib.eo_step_no_output.restype = ctypes.c_int
+    lib.eo_step_no_output.argtypes = [vp, vp]
     lib.eo_step_compressed.restype = ctypes.c_int
     lib.eo_step_compressed.argtypes = [vp, vp, vp]
     lib.eo_apply.restype = ctypes.c_int
@@ -195,6 +197,13 @@ class Oracle:
         if self._lib.eo_step(self._st, _ptr(g), xp, _ptr(y)) != 0:
             raise MemoryError("eo_step")
         return y
+
+    def step_no_output(self, g: np.ndarray) -> None:
+        """Error feedback, Top-k and the window update of one step; F^-1 x is not formed."""
+        g = np.ascontiguousarray(g, dtype=np.float32)
+        assert g.size == self.d
+        if self._lib.eo_step_no_output(self._st, _ptr(g)) != 0:
+            raise MemoryError("eo_step_no_output")
 
     def step_compressed(self, g: np.ndarray) -> np.ndarray:
         """One step that preconditions the compressed accumulator c_t itself."""

@@ -454,6 +454,11 @@ static int compress_and_insert(eo_state *st, const float *g)
     return rc;
 }
 
+int eo_step_no_output(eo_state *st, const float *g)
+{
+    return compress_and_insert(st, g);
+}
+
 int eo_step(eo_state *st, const float *g, const float *x, double *y)
 {
     if (compress_and_insert(st, g) != 0) return -1;

@@ -79,6 +79,12 @@ void eo_destroy(eo_state *st);
  * allocation failure. */
 int eo_step(eo_state *st, const float *g, const float *x, double *y);
 
+/* Lines 5-7 of Algorithm 1 and the window update of line 8 only (a = e + g, c = TopK(a),
+ * e = a - c, c into the ring, its row and column of S): exactly what eo_step does before it
+ * preconditions, so the state afterwards is the state eo_step leaves, bit for bit; q and coef
+ * keep their previous contents.  For filling a window without paying for F^-1 x. */
+int eo_step_no_output(eo_state *st, const float *g);
+
 /* Algorithm 1 line 8 as printed: the vector preconditioned is the compressed
  * accumulator itself, u = A(c_t), i.e. x = c_t scattered to dense.  Otherwise
  * identical to eo_step. */

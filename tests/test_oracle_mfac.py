@@ -258,3 +258,32 @@ def test_ill_conditioned_window_still_matches_woodbury(oracle_mod):
     C = _dense_rows(o)[order]
     y_ref = g.astype(np.float64) / lam - ref @ C
     assert _rel(y, y_ref) < 1e-7
+
+
+@pytest.mark.parametrize("bf16,block", [(False, 0), (True, 0), (False, 64)])
+def test_step_without_output_leaves_the_state_of_a_full_step(oracle_mod, bf16, block):
+    """eo_step_no_output is Algorithm 1 lines 5-7 plus the window update of line 8 and nothing
+    else: after any mix of it with full steps, e, every stored row and S are bit for bit those of
+    a run made of full steps only, and the next full step returns the same y.  y itself is pinned
+    by dense inversion (which knows nothing of how the window was filled)."""
+    d, m, k, lam = 400, 6, (5 if block else 23), 1e-2
+    a = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=block)
+    b = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=block)
+    rng = np.random.default_rng(17)
+    for t in range(1, 16):
+        g = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+        ya = a.step(g)
+        if t % 4 == 0 or t == 15:
+            yb = b.step(g)
+            assert np.array_equal(ya, yb)
+            assert np.array_equal(a.q, b.q) and np.array_equal(a.coef, b.coef)
+        else:
+            b.step_no_output(g)
+        assert a.t == b.t == t and a.filled == b.filled
+        assert np.array_equal(a.error.view(np.uint32), b.error.view(np.uint32))
+        assert np.array_equal(a.gram, b.gram)
+        for r in range(a.filled):
+            (ia, va), (ib, vb) = a.row(r), b.row(r)
+            assert np.array_equal(ia, ib) and np.array_equal(va.view(np.uint32), vb.view(np.uint32))
+    C = _dense_rows(b)
+    assert _rel(yb, _dense_solve(C, m, lam, g)) < 1e-9
