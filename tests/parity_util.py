@@ -27,7 +27,8 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
                check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False,
-               compressed=False, update=None, apply_every=0, topk_block=0, ggt=False):
+               compressed=False, update=None, apply_every=0, topk_block=0, ggt=False, fill=0,
+               fill_check_every=128, say=None):
     """grads: iterable of float32 numpy arrays.  bf16: the bfloat16 window
     format on both sides.  compressed: the step preconditions c_t instead of
     the gradient.  update=(lr, weight_decay): the step updates a parameter
@@ -37,7 +38,11 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
     step a seeded random x is applied to the window as it stands on both
     sides (no insertion).  topk_block=B: Top-k applied in blocks of B
     coordinates on both sides, k entries per block.  ggt: Sparse GGT on both
-    sides, lam is its epsilon.  Returns dict of worst errors."""
+    sides, lam is its epsilon.  fill=n: the first n steps only insert on both
+    sides (the oracle's step without output, out = NULL on the GPU): the new row
+    is still compared bit for bit on every one of them, e and all of S on every
+    fill_check_every-th and on the last; from step n+1 on every step is a full one.  say: callable for
+    progress lines.  Returns dict of worst errors."""
     dev = torch.device("cuda:0")
     o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=topk_block, ggt=ggt)
     g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
@@ -56,10 +61,16 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
             t += 1
             g = np.ascontiguousarray(g, dtype=np.float32)
             a = e_prev + g                      # the accumulator, one fp32 rounding per element
-            y = o.step_compressed(g) if compressed else o.step(g)
+            filling = t <= fill
+            if filling:
+                o.step_no_output(g)
+            else:
+                y = o.step_compressed(g) if compressed else o.step(g)
             e_prev = o.error.copy()
             grad_d.copy_(torch.from_numpy(g))
-            if update:
+            if filling:
+                g_gpu.step(grad_d, None)
+            elif update:
                 out_d.copy_(torch.from_numpy(theta))
                 g_gpu.step_ex(grad_d, x_source, param=out_d, lr=update[0], weight_decay=update[1])
             elif compressed:
@@ -72,9 +83,22 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
             oi, ov = o.row(slot)
             assert np.array_equal(idx, oi), f"step {t}: Top-k indices differ"
             assert np.array_equal(bits(val), bits(ov)), f"step {t}: stored values differ"
-            if check_error_every and (t % check_error_every == 0 or t == 1):
+            if filling:
+                check_e = t == fill or t % fill_check_every == 0
+            else:
+                check_e = check_error_every and (t % check_error_every == 0 or t == 1)
+            if check_e:
                 assert np.array_equal(bits(g_gpu.get_error()), bits(o.error)), \
                     f"step {t}: error feedback differs"
+            if filling:
+                if check_e:
+                    S_gpu, S_ref = g_gpu.get_small()["S"], o.gram
+                    sS = np.abs(S_gpu - S_ref).max() / max(np.abs(S_ref).max(), 1e-300)
+                    worst["S"] = max(worst["S"], sS)
+                    assert sS <= 1e-10, f"step {t} (fill): Gram matrix off by {sS:.3e}"
+                    if say:
+                        say(f"fill step {t}/{fill}: rows, e bit-exact so far; S within {sS:.1e}")
+                continue
             out = out_d.cpu().numpy()
             assert np.isfinite(out).all(), f"step {t}: non-finite output"
             if update:
@@ -115,6 +139,8 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
                 assert g_gpu.get_small()["step"] == t
             if verbose:
                 print(f"  step {t}: out {err:.2e}", flush=True)
+            if say:
+                say(f"step {t}: rows, e bit-exact; out {err:.2e}")
     finally:
         g_gpu.destroy()
         o.close()
