@@ -166,6 +166,25 @@ int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, float *out,
  * another stream).  Must not run concurrently with a step of the same context. */
 int efcp_apply(efcp_ctx *ctx, const float *x, float *out, void *stream);
 
+/* efcp_apply for callers that cannot allocate and want the context left exactly as it is: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit for bit the same `out` as efcp_apply, but every scratch buffer
+ * of the call (the per-workgroup partial sums of the SP pass, their reduction, the products
+ * with the inverse factor, q and the coefficients) lives in a fixed array inside the library's
+ * code object (4 MiB + 64 KiB on every device that loads the library, held until the process
+ * ends) instead of the context's workspace.  So q and coef that efcp_get_small reports stay
+ * those of the last step, and neither this call nor anything it calls allocates or frees
+ * memory (no hipMalloc, no hipFree, no host allocation).  The array's address on the
+ * context's device is resolved once, in efcp_create.
+ *   EFCP_EINVAL  as efcp_apply, and if the context needs more scratch than the array holds
+ *                (more than 256 SP workgroups x 1024 window rows: no context that efcp_create*
+ *                accepts today does).
+ * All calls on one device share the one array: two efcp_apply_noalloc calls (of the same or of
+ * different contexts) that may overlap in time on a device race with each other; put them on
+ * one stream or order them.  Nothing in the array needs to be cleared between calls: every
+ * entry a call reads was written by that call. */
+int efcp_apply_noalloc(efcp_ctx *ctx, const float *x, float *out, void *stream);
+
 /* Frees the context (and its workspace if the library allocated it) after
  * synchronising the device.  efcp_destroy(NULL) is EFCP_OK. */
 int efcp_destroy(efcp_ctx *ctx);

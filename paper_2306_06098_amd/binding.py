@@ -21,6 +21,7 @@ VALUES_FP32, VALUES_BF16 = 0, 1
 EXPORTS = (
     "efcp_workspace_bytes", "efcp_workspace_bytes_fmt", "efcp_create", "efcp_create_fmt", "efcp_create_ex",
     "efcp_workspace_bytes_ex", "efcp_row_length", "efcp_create_ggt", "efcp_workspace_bytes_ggt", "efcp_step", "efcp_step_ex", "efcp_apply",
+    "efcp_apply_noalloc",
     "efcp_destroy", "efcp_get_row",
     "efcp_get_error", "efcp_get_small", "efcp_tune_slice_width", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
@@ -72,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_step_ex.argtypes = [vp, vp, i32, vp, vp, dbl, dbl, vp]
     lib.efcp_apply.restype = ctypes.c_int
     lib.efcp_apply.argtypes = [vp, vp, vp, vp]
+    lib.efcp_apply_noalloc.restype = ctypes.c_int
+    lib.efcp_apply_noalloc.argtypes = [vp, vp, vp, vp]
     lib.efcp_destroy.restype = ctypes.c_int
     lib.efcp_destroy.argtypes = [vp]
     lib.efcp_get_row.restype = ctypes.c_int
@@ -181,6 +184,14 @@ class Efcp:
         assert ok(x) and ok(out)
         s = stream if stream is not None else torch.cuda.current_stream(x.device)
         self._check(self._lib.efcp_apply(self._ctx, x.data_ptr(), out.data_ptr(), s.cuda_stream))
+
+    def apply_noalloc(self, x, out, stream=None) -> None:
+        """efcp_apply_noalloc: as apply(), scratch in the library's static device array."""
+        import torch
+        ok = lambda t: t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == self.d
+        assert ok(x) and ok(out)
+        s = stream if stream is not None else torch.cuda.current_stream(x.device)
+        self._check(self._lib.efcp_apply_noalloc(self._ctx, x.data_ptr(), out.data_ptr(), s.cuda_stream))
 
     def destroy(self) -> None:
         if getattr(self, "_ctx", None) and self._ctx.value:

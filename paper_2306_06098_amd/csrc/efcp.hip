@@ -8,6 +8,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -166,9 +167,48 @@ __global__ void k_offset_column(const int32_t *__restrict__ offT, int32_t m, int
     if (s < n) out[s] = offT[(int64_t)s * m + slot];
 }
 
+// ---- scratch memory of efcp_apply_noalloc ----
+// The buffers that efcp_apply takes from the context's workspace and only uses as scratch (the
+// per-workgroup partial sums of the SP pass, their reduction sq, the product zw with the inverse
+// factor, q and the coefficients) exist once more here, in the code object itself, for callers
+// that want the context's own copies left alone.  Sized for the largest context the library
+// creates: kMaxWgs workgroups x kMaxM rows of double2, and four m-sized arrays.  Every device
+// that loads the library holds its own copy at its own address; host code must never use the
+// name `scratch` as an address, only what hipGetSymbolAddress returned with that device current.
+constexpr size_t kStaticPartialBytes = (size_t)kMaxWgs * kMaxM * sizeof(double2);
+constexpr size_t kStaticSmallBytes = (size_t)kMaxM * sizeof(double2);
+constexpr size_t kStaticScratchBytes = kStaticPartialBytes + 4 * kStaticSmallBytes;     // 4 MiB + 64 KiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];            // device address of `scratch` on each device, once resolved
+
+// Address of `scratch` on `device`, which must be current.
+hipError_t static_scratch_address(int device, void **ptr)
+{
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (device >= 0 && device < kMaxDevices && g_scratch_ptr[device]) {
+        *ptr = g_scratch_ptr[device];
+        return hipSuccess;
+    }
+    void *at = nullptr;
+    const hipError_t rc = hipGetSymbolAddress(&at, HIP_SYMBOL(scratch));
+    if (rc != hipSuccess) return rc;
+    if (!at) return hipErrorInvalidSymbol;
+    if (device >= 0 && device < kMaxDevices) g_scratch_ptr[device] = at;
+    *ptr = at;
+    return hipSuccess;
+}
+
+}  // namespace
+
 struct efcp_ctx {
     Geometry g;
     DevicePtrs p;
+    void *static_scratch;            // this device's copy of `scratch` (resolved in efcp_create)
     double lambda;
     int device;
     void *ws;
@@ -355,6 +395,8 @@ static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double l
     if (rc == hipSuccess) rc = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
     if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
+    ctx->static_scratch = nullptr;
+    if (rc == hipSuccess) rc = static_scratch_address(ctx->device, &ctx->static_scratch);
     if (rc == hipSuccess) rc = configure_sp(g);
     if (rc == hipSuccess) rc = configure_lcg(g);
     if (rc == hipSuccess && g.ggt) rc = configure_ggt();
@@ -459,17 +501,14 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     return EFCP_OK;
 }
 
-extern "C" int efcp_apply(efcp_ctx *ctx, const float *x, float *outp, void *stream_v)
+// p: the context's pointers, or a copy of them whose scratch members point somewhere else.
+static int apply_impl(efcp_ctx *ctx, const DevicePtrs &p, const float *x, float *outp, void *stream_v)
 {
-    if (!ctx) return EFCP_EINVAL;
-    if (int rc = wrong_device(ctx)) return rc;
-    if (!x || !outp) return fail(ctx, EFCP_EINVAL, "x or out is NULL");
     if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(outp) & 15))
         return fail(ctx, EFCP_EINVAL, "x/out not 16-byte aligned");
     if (overlap(x, outp, (size_t)ctx->g.d * sizeof(float))) return fail(ctx, EFCP_EINVAL, "x and out overlap");
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const Geometry &g = ctx->g;
-    const DevicePtrs &p = ctx->p;
     const int32_t n_filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
     hipError_t rc = hipSuccess;
     if (ctx->last_stream != stream && ctx->t > 0) {
@@ -488,6 +527,35 @@ extern "C" int efcp_apply(efcp_ctx *ctx, const float *x, float *outp, void *stre
     ctx->last_stream = stream;
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
     return EFCP_OK;
+}
+
+extern "C" int efcp_apply(efcp_ctx *ctx, const float *x, float *outp, void *stream_v)
+{
+    if (!ctx) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
+    if (!x || !outp) return fail(ctx, EFCP_EINVAL, "x or out is NULL");
+    return apply_impl(ctx, ctx->p, x, outp, stream_v);
+}
+
+extern "C" int efcp_apply_noalloc(efcp_ctx *ctx, const float *x, float *outp, void *stream_v)
+{
+    if (!ctx) return EFCP_EINVAL;
+    if (int rc = wrong_device(ctx)) return rc;
+    if (!x || !outp) return fail(ctx, EFCP_EINVAL, "x or out is NULL");
+    const Geometry &g = ctx->g;
+    const size_t partial_bytes = (size_t)g.sp_grid * g.m * sizeof(double2);
+    const size_t small_bytes = (size_t)g.m * sizeof(double2);
+    if (partial_bytes > kStaticPartialBytes || small_bytes > kStaticSmallBytes)
+        return fail(ctx, EFCP_EINVAL, "window too large for the static scratch (256 workgroups x 1024 rows)");
+    if (!ctx->static_scratch) return fail(ctx, EFCP_EHIP, "static scratch address was not resolved");
+    unsigned char *b = static_cast<unsigned char *>(ctx->static_scratch);
+    DevicePtrs p = ctx->p;
+    p.partial = reinterpret_cast<double2 *>(b);
+    p.sq = reinterpret_cast<double2 *>(b + kStaticPartialBytes);
+    p.zw = reinterpret_cast<double2 *>(b + kStaticPartialBytes + kStaticSmallBytes);
+    p.q = reinterpret_cast<double *>(b + kStaticPartialBytes + 2 * kStaticSmallBytes);
+    p.coef = reinterpret_cast<double *>(b + kStaticPartialBytes + 3 * kStaticSmallBytes);
+    return apply_impl(ctx, p, x, outp, stream_v);
 }
 
 extern "C" int efcp_destroy(efcp_ctx *ctx)
