@@ -28,9 +28,9 @@
  * All pointers named "device" are HIP device pointers on the device that was
  * current when efcp_create ran, and that device has to be current in every
  * later call on the context (EFCP_EINVAL otherwise; efcp_destroy switches to it
- * by itself and back); pointers named "host" are ordinary host memory.  Every function returns EFCP_OK (0) or a negative efcp_status; no
- * function throws, aborts or prints.  A context may be used by one host
- * thread at a time.
+ * by itself and back); pointers named "host" are ordinary host memory.  Every
+ * function returns EFCP_OK (0) or a negative efcp_status; no function throws,
+ * aborts or prints.  A context may be used by one host thread at a time.
  */
 #ifndef EFCP_H
 #define EFCP_H
@@ -115,6 +115,28 @@ int efcp_create_ggt(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double epsi
                     int32_t value_format, int32_t topk_block, void *workspace, size_t workspace_bytes);
 size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_format,
                                 int32_t topk_block);
+
+/* The general constructor: everything the calls above choose, as one structure, plus the
+ * d-slice width.  opts == NULL means all zeros (fp32 values, global Top-k, Sparse M-FAC,
+ * automatic width); the calls above are this one with slice_width = 0. */
+typedef enum { EFCP_SPARSE_MFAC = 0, EFCP_SPARSE_GGT = 1 } efcp_preconditioner;
+typedef struct efcp_options {
+    int32_t value_format;    /* efcp_value_format */
+    int32_t topk_block;      /* 0 or EFCP_TOPK_BLOCK, as in efcp_create_ex */
+    int32_t preconditioner;  /* efcp_preconditioner; with EFCP_SPARSE_GGT `damping` is epsilon, m <= 128 */
+    int32_t slice_width;     /* Coordinates per d-slice (the LDS tile of the SP and LCG kernels and the
+                                block of the Top-k passes).  0: chosen from d so that the persistent
+                                SP / LCG workgroups all get the same number of slices.  Otherwise a
+                                multiple of 256 in [256, 16384]; a width too small for d (more than 512
+                                slices per workgroup) is EFCP_EINVAL.  Ignored with Top-k in blocks,
+                                where the slice is the block.  The Top-k, the stored rows and e do not
+                                depend on the width; S, q, coef and with them F^-1 x do in the last bits
+                                (order of the fp64 sums).  A state exported under one width is refused by
+                                a context created under another. */
+} efcp_options;
+int efcp_create_opts(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double damping,
+                     const efcp_options *opts, void *workspace, size_t workspace_bytes);
+size_t efcp_workspace_bytes_opts(int64_t d, int32_t m, int64_t k, const efcp_options *opts);
 
 /* One step (see the top of this file).
  *   grad    device, d floats, 16-byte aligned, read only.  Meant to be finite.  Infinities
@@ -229,16 +251,6 @@ int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes);
  * (EFCP_EINVAL otherwise, and on a damaged or truncated buffer); its previous
  * state is replaced. */
 int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes);
-
-/* Tuning knob, process-wide: the d-slice width of contexts created (and workspace sizes
- * computed) afterwards.  0, the default: chosen from d so that the persistent SP / LCG
- * workgroups all get the same number of slices.  Otherwise a multiple of 256 in
- * [256, 16384] (EFCP_EINVAL if not); a width too small for the d of a later efcp_create
- * makes that call fail with EFCP_EINVAL.  Ignored with Top-k in blocks, where the slice is
- * the block.  The Top-k, the stored rows and e do not depend on the width;
- * S, q, coef and with them F^-1 x do in the last bits (order of the fp64 sums).  A state exported under one width
- * is refused by a context created under another. */
-int efcp_tune_slice_width(int32_t width);
 
 /* Geometry chosen at creation; any pointer may be NULL.
  *   slice      coordinates per d-slice staged in LDS by the SP and LCG kernels

@@ -23,7 +23,7 @@ EXPORTS = (
     "efcp_workspace_bytes_ex", "efcp_row_length", "efcp_create_ggt", "efcp_workspace_bytes_ggt", "efcp_step", "efcp_step_ex", "efcp_apply",
     "efcp_apply_noalloc",
     "efcp_destroy", "efcp_get_row",
-    "efcp_get_error", "efcp_get_small", "efcp_tune_slice_width", "efcp_get_geometry", "efcp_state_bytes",
+    "efcp_get_error", "efcp_get_small", "efcp_create_opts", "efcp_workspace_bytes_opts", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
     "efcp_profile_read", "efcp_last_error",
 )
@@ -31,6 +31,12 @@ EXPORTS = (
 X_GRAD, X_COMPRESSED = 0, 1
 
 _lib = None
+
+
+class Options(ctypes.Structure):
+    """struct efcp_options."""
+    _fields_ = [("value_format", ctypes.c_int32), ("topk_block", ctypes.c_int32),
+                ("preconditioner", ctypes.c_int32), ("slice_width", ctypes.c_int32)]
 
 
 class EfcpError(RuntimeError):
@@ -83,8 +89,11 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_get_error.argtypes = [vp, vp]
     lib.efcp_get_small.restype = ctypes.c_int
     lib.efcp_get_small.argtypes = [vp, vp, vp, vp, vp, vp]
-    lib.efcp_tune_slice_width.restype = ctypes.c_int
-    lib.efcp_tune_slice_width.argtypes = [i32]
+    lib.efcp_create_opts.restype = ctypes.c_int
+    lib.efcp_create_opts.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, ctypes.POINTER(Options), vp,
+                                     ctypes.c_size_t]
+    lib.efcp_workspace_bytes_opts.restype = ctypes.c_size_t
+    lib.efcp_workspace_bytes_opts.argtypes = [i64, i32, i64, ctypes.POINTER(Options)]
     lib.efcp_get_geometry.restype = ctypes.c_int
     lib.efcp_get_geometry.argtypes = [vp, vp, vp, vp]
     lib.efcp_state_bytes.restype = ctypes.c_size_t
@@ -107,28 +116,21 @@ TOPK_BLOCK = 16384      # EFCP_TOPK_BLOCK
 
 
 def efcp_workspace_bytes(d: int, m: int, k: int, values: int = VALUES_FP32, topk_block: int = 0,
-                         ggt: bool = False) -> int:
-    fn = load_library().efcp_workspace_bytes_ggt if ggt else load_library().efcp_workspace_bytes_ex
-    return int(fn(d, m, k, values, topk_block))
-
-
-def tune_slice_width(width: int) -> None:
-    """efcp_tune_slice_width: d-slice width of contexts created afterwards
-    (0 = automatic; else a multiple of 256 in [256, 16384]).  Process-wide."""
-    rc = load_library().efcp_tune_slice_width(int(width))
-    if rc != 0:
-        raise EfcpError(rc, f"slice width {width} not a multiple of 256 in [256, 16384]")
+                         ggt: bool = False, slice_width: int = 0) -> int:
+    o = Options(values, topk_block, 1 if ggt else 0, slice_width)
+    return int(load_library().efcp_workspace_bytes_opts(d, m, k, ctypes.byref(o)))
 
 
 class Efcp:
     """One libefcp context: efcp_create / efcp_step / efcp_destroy."""
 
     def __init__(self, d: int, m: int, k: int, lam: float, workspace=None, values: int = VALUES_FP32,
-                 topk_block: int = 0, ggt: bool = False):
+                 topk_block: int = 0, ggt: bool = False, slice_width: int = 0):
         """topk_block = 0: global Top-k of k entries; TOPK_BLOCK: Top-k applied in
         blocks of that many coordinates, k entries per block (self.k is then the
         resulting row length, self.k_arg what was passed).  ggt: Sparse GGT
-        (efcp_create_ggt), `lam` is then its epsilon and m <= 128."""
+        (EFCP_SPARSE_GGT), `lam` is then its epsilon and m <= 128.  slice_width: coordinates
+        per d-slice, 0 = chosen by the library (efcp_options)."""
         self._lib = load_library()
         self.d, self.m, self.lam = int(d), int(m), float(lam)
         self.k_arg, self.topk_block = int(k), int(topk_block)
@@ -139,9 +141,9 @@ class Efcp:
         ws_ptr, ws_bytes = None, 0
         if workspace is not None:
             ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-        create = self._lib.efcp_create_ggt if ggt else self._lib.efcp_create_ex
-        rc = create(ctypes.byref(self._ctx), self.d, self.m, self.k_arg, self.lam,
-                    self.values, self.topk_block, ws_ptr, ws_bytes)
+        opts = Options(self.values, self.topk_block, 1 if ggt else 0, int(slice_width))
+        rc = self._lib.efcp_create_opts(ctypes.byref(self._ctx), self.d, self.m, self.k_arg, self.lam,
+                                        ctypes.byref(opts), ws_ptr, ws_bytes)
         if rc != EFCP_OK:
             self._ctx = ctypes.c_void_p()
             raise EfcpError(rc, "efcp_create failed")

@@ -5,7 +5,6 @@
 #include "../../include/efcp.h"
 #include "efcp_internal.h"
 
-#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -40,12 +39,10 @@ int64_t block_row_length(int64_t d, int64_t kb)
 // the widest slice stays: the first Top-k pass pays a fixed cost per block (measured at
 // d = 110M, 2.9 %: SP 1.5 % faster, that pass 5 % slower with 16,128-wide blocks, no net gain).
 // No result depends on the width except the order of the fp64 sums of the SP pass.
-std::atomic<int32_t> g_slice_width{0};             // efcp_tune_slice_width: 0 = automatic
-
-int32_t pick_slice_width(int64_t d, int32_t kb)
+// forced: the width asked for in efcp_options (0 = choose as described).
+int32_t pick_slice_width(int64_t d, int32_t kb, int32_t forced)
 {
     if (kb) return kCandBlock;
-    const int32_t forced = g_slice_width.load();
     if (forced) return forced;
     const int64_t widest = (d + kCandBlock - 1) / kCandBlock;
     const int64_t rounds = (widest + kMaxWgs - 1) / kMaxWgs;
@@ -59,9 +56,14 @@ int32_t pick_slice_width(int64_t d, int32_t kb)
 
 // k_in: entries per row (topk_block == 0) or per block of kCandBlock coordinates.
 bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk_block, int32_t ggt,
-                   Geometry &g, const char **why)
+                   int32_t slice_width, Geometry &g, const char **why)
 {
     g.ggt = ggt ? 1 : 0;
+    if (ggt != 0 && ggt != 1) { *why = "unknown preconditioner"; return false; }
+    if (slice_width != 0 && (slice_width < 256 || slice_width > kCandBlock || slice_width % 256 != 0)) {
+        *why = "slice_width must be 0 or a multiple of 256 in [256, 16384]";
+        return false;
+    }
     if (ggt && m > kGgtMaxM) { *why = "Sparse GGT: m out of range [1, 128]"; return false; }
     if (fmt != kFmtF32 && fmt != kFmtBf16) { *why = "unknown value format"; return false; }
     if (d < 1 || d >= ((int64_t)1 << 31)) { *why = "d out of range [1, 2^31)"; return false; }
@@ -92,7 +94,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
         *why = "device LDS too small (needs the 160 KiB of gfx950)";
         return false;
     }
-    g.slice = pick_slice_width(d, g.kb);
+    g.slice = pick_slice_width(d, g.kb, slice_width);
     g.n_slices = (int32_t)((d + g.slice - 1) / g.slice);
     {
         const int32_t per = (g.n_slices + 7) / 8;
@@ -246,25 +248,37 @@ static int wrong_device(efcp_ctx *ctx)
     return EFCP_OK;
 }
 
-static size_t workspace_bytes(int64_t d, int32_t m, int64_t k, int32_t value_format, int32_t topk_block,
-                              int32_t ggt)
+static efcp_options options_of(int32_t value_format, int32_t topk_block, int32_t preconditioner)
 {
+    efcp_options o;
+    o.value_format = value_format;
+    o.topk_block = topk_block;
+    o.preconditioner = preconditioner;
+    o.slice_width = 0;
+    return o;
+}
+
+extern "C" size_t efcp_workspace_bytes_opts(int64_t d, int32_t m, int64_t k, const efcp_options *opts)
+{
+    const efcp_options o = opts ? *opts : options_of(EFCP_VALUES_FP32, 0, EFCP_SPARSE_MFAC);
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, value_format, topk_block, ggt, g, &why)) return 0;
+    if (!make_geometry(d, m, k, o.value_format, o.topk_block, o.preconditioner, o.slice_width, g, &why)) return 0;
     return make_layout(g).total;
 }
 
 extern "C" size_t efcp_workspace_bytes_ex(int64_t d, int32_t m, int64_t k, int32_t value_format,
                                           int32_t topk_block)
 {
-    return workspace_bytes(d, m, k, value_format, topk_block, 0);
+    const efcp_options o = options_of(value_format, topk_block, EFCP_SPARSE_MFAC);
+    return efcp_workspace_bytes_opts(d, m, k, &o);
 }
 
 extern "C" size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_format,
                                            int32_t topk_block)
 {
-    return workspace_bytes(d, m, k, value_format, topk_block, 1);
+    const efcp_options o = options_of(value_format, topk_block, EFCP_SPARSE_GGT);
+    return efcp_workspace_bytes_opts(d, m, k, &o);
 }
 
 extern "C" size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int32_t value_format)
@@ -296,32 +310,34 @@ extern "C" int efcp_create_fmt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, 
     return efcp_create_ex(out, d, m, k, lambda, value_format, 0, workspace, workspace_bytes);
 }
 
-static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda, int32_t value_format,
-                       int32_t topk_block, int32_t ggt, void *workspace, size_t workspace_bytes);
-
 extern "C" int efcp_create_ex(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
                               int32_t value_format, int32_t topk_block, void *workspace,
                               size_t workspace_bytes)
 {
-    return create_impl(out, d, m, k, lambda, value_format, topk_block, 0, workspace, workspace_bytes);
+    const efcp_options o = options_of(value_format, topk_block, EFCP_SPARSE_MFAC);
+    return efcp_create_opts(out, d, m, k, lambda, &o, workspace, workspace_bytes);
 }
 
 extern "C" int efcp_create_ggt(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double epsilon,
                                int32_t value_format, int32_t topk_block, void *workspace,
                                size_t workspace_bytes)
 {
-    return create_impl(out, d, m, k, epsilon, value_format, topk_block, 1, workspace, workspace_bytes);
+    const efcp_options o = options_of(value_format, topk_block, EFCP_SPARSE_GGT);
+    return efcp_create_opts(out, d, m, k, epsilon, &o, workspace, workspace_bytes);
 }
 
-static int create_impl(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda, int32_t value_format,
-                       int32_t topk_block, int32_t ggt, void *workspace, size_t workspace_bytes)
+extern "C" int efcp_create_opts(efcp_ctx **out, int64_t d, int32_t m, int64_t k, double lambda,
+                                const efcp_options *opts, void *workspace, size_t workspace_bytes)
 {
+    const efcp_options o = opts ? *opts : options_of(EFCP_VALUES_FP32, 0, EFCP_SPARSE_MFAC);
+    const int32_t value_format = o.value_format, topk_block = o.topk_block, ggt = o.preconditioner;
+
     if (!out) return EFCP_EINVAL;
     *out = nullptr;
     if (!(lambda > 0.0) || !std::isfinite(lambda)) return EFCP_EINVAL;
     Geometry g;
     const char *why = "";
-    if (!make_geometry(d, m, k, value_format, topk_block, ggt, g, &why)) return EFCP_EINVAL;
+    if (!make_geometry(d, m, k, value_format, topk_block, ggt, o.slice_width, g, &why)) return EFCP_EINVAL;
     const Layout l = make_layout(g);
 
     efcp_ctx *ctx = new (std::nothrow) efcp_ctx();
@@ -799,13 +815,6 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
     ctx->pending_slot = -1;                          // an exported e is final
-    return EFCP_OK;
-}
-
-extern "C" int efcp_tune_slice_width(int32_t width)
-{
-    if (width != 0 && (width < 256 || width > kCandBlock || width % 256 != 0)) return EFCP_EINVAL;
-    g_slice_width.store(width);
     return EFCP_OK;
 }
 

@@ -28,7 +28,7 @@ def rel_l2(a: np.ndarray, ref: np.ndarray) -> float:
 def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_every=1,
                check_small=True, verbose=False, out_tol=OUT_TOL, bf16=False,
                compressed=False, update=None, apply_every=0, topk_block=0, ggt=False, fill=0,
-               fill_check_every=128, say=None):
+               fill_check_every=128, say=None, slice_width=0):
     """grads: iterable of float32 numpy arrays.  bf16: the bfloat16 window
     format on both sides.  compressed: the step preconditions c_t instead of
     the gradient.  update=(lr, weight_decay): the step updates a parameter
@@ -42,11 +42,12 @@ def run_parity(torch, oracle_mod, binding, d, m, k, lam, grads, check_error_ever
     sides (the oracle's step without output, out = NULL on the GPU): the new row
     is still compared bit for bit on every one of them, e and all of S on every
     fill_check_every-th and on the last; from step n+1 on every step is a full one.  say: callable for
-    progress lines.  Returns dict of worst errors."""
+    progress lines.  slice_width: d-slice width of the GPU context (0 = automatic).
+    Returns dict of worst errors."""
     dev = torch.device("cuda:0")
     o = oracle_mod.Oracle(d, m, k, lam, values_bf16=bf16, block=topk_block, ggt=ggt)
     g_gpu = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
-                         topk_block=topk_block, ggt=ggt)
+                         topk_block=topk_block, ggt=ggt, slice_width=slice_width)
     assert g_gpu.k == o.k, "row length differs"
     e_prev = np.zeros(d, np.float32)
     grad_d = torch.empty(d, dtype=torch.float32, device=dev)

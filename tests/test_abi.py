@@ -44,19 +44,16 @@ def test_null_context_is_rejected_without_a_gpu():
     assert lib.efcp_last_error(None) == b"null context"
 
 
-def test_slice_width_knob_validates_without_a_gpu():
-    """efcp_tune_slice_width is host state only: 0 or a multiple of 256 in [256, 16384]."""
-    from paper_2306_06098_amd import binding
+def test_options_structure_matches_the_header():
+    """struct efcp_options: four int32 in the order the header declares them."""
+    text = open(os.path.join(ROOT, "include", "efcp.h")).read()
+    body = re.search(r"typedef struct efcp_options \{(.*?)\} efcp_options;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"int32_t\s+(\w+)\s*;", body)
+    assert fields == [f[0] for f in binding.Options._fields_]
+    assert ctypes.sizeof(binding.Options) == 16
     lib = binding.load_library()
-    try:
-        for ok in (0, 256, 1024, 14_592, 16_384):
-            assert lib.efcp_tune_slice_width(ok) == 0
-        for bad in (-256, 1, 128, 255, 1000, 16_640, 32_768):
-            assert lib.efcp_tune_slice_width(bad) != 0
-        with pytest.raises(binding.EfcpError):
-            binding.tune_slice_width(100)
-    finally:
-        assert lib.efcp_tune_slice_width(0) == 0
+    assert lib.efcp_create_opts(None, 10, 1, 1, 1.0, None, None, 0) == binding.EFCP_EINVAL
 
 
 def test_row_length_arithmetic_matches_the_oracle(oracle_mod):

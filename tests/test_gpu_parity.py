@@ -90,7 +90,7 @@ def test_shapes_and_edges(env, d, m, k, lam, T, bf16):
 @pytest.mark.parametrize("width", [256, 1024, 4352, 12_544, 16_384])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_slice_widths(env, width, bf16):
-    """The d-slice width is a tuning knob (efcp_tune_slice_width): slices of 256 up to 16,384
+    """The d-slice width is an option of the context (efcp_options.slice_width): slices of 256 up to 16,384
     coordinates, widths that end in the middle of a wave's part of a block and in the middle of a
     4,096-coordinate chunk, d not a multiple of any of them; every variant of the step."""
     torch, oracle_mod, binding = env
@@ -103,17 +103,14 @@ def test_slice_widths(env, width, bf16):
         for _ in range(T):
             z = (0.7 * z + rng.standard_normal(d)).astype(np.float32)
             yield scale * z
-    binding.tune_slice_width(width)
-    try:
-        g = binding.Efcp(d, m, k, lam)
-        geo = g.geometry()
-        g.destroy()
-        assert geo["slice"] == width and geo["n_slices"] == -(-d // width)
-        w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16, apply_every=5)
-        w2 = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16, compressed=True,
-                        update=(0.05, 0.01))
-    finally:
-        binding.tune_slice_width(0)
+    g = binding.Efcp(d, m, k, lam, slice_width=width)
+    geo = g.geometry()
+    g.destroy()
+    assert geo["slice"] == width and geo["n_slices"] == -(-d // width)
+    w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16, apply_every=5,
+                   slice_width=width)
+    w2 = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), bf16=bf16, compressed=True,
+                    update=(0.05, 0.01), slice_width=width)
     print(width, bf16, w, w2)
 
 
@@ -392,14 +389,10 @@ def test_export_import_resumes_bit_identically(env):
         for ctx in (a, b, c):
             ctx.destroy()
     # a context cut into slices of another width refuses the blob as well
-    binding.tune_slice_width(2048)
-    try:
-        c = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16)
-        with pytest.raises(binding.EfcpError):
-            c.import_state(blob)
-        c.destroy()
-    finally:
-        binding.tune_slice_width(0)
+    c = binding.Efcp(d, m, k, lam, values=binding.VALUES_BF16, slice_width=2048)
+    with pytest.raises(binding.EfcpError):
+        c.import_state(blob)
+    c.destroy()
 
 
 def test_argument_checks(env):
@@ -409,6 +402,14 @@ def test_argument_checks(env):
         with pytest.raises(binding.EfcpError) as ei:
             binding.Efcp(*bad)
         assert ei.value.code == binding.EFCP_EINVAL
+    for width in (-256, 1, 128, 255, 1000, 16_640, 32_768):         # not a multiple of 256 in [256, 16384]
+        with pytest.raises(binding.EfcpError) as ei:
+            binding.Efcp(100_000, 4, 10, 1e-3, slice_width=width)
+        assert ei.value.code == binding.EFCP_EINVAL
+        assert binding.efcp_workspace_bytes(100_000, 4, 10, slice_width=width) == 0
+    with pytest.raises(binding.EfcpError):                          # 2^30 / 256 slices: too many per workgroup
+        binding.Efcp(2 ** 30, 1, 10, 1e-3, slice_width=256)
+    assert binding.efcp_workspace_bytes(100_000, 4, 10, slice_width=512) > 0
     ctx = binding.Efcp(1000, 4, 10, 1e-3)
     g = torch.zeros(1004, dtype=torch.float32, device="cuda:0")
     with pytest.raises(binding.EfcpError):
