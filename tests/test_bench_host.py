@@ -31,3 +31,40 @@ def test_more_than_one_gpu_is_refused_before_anything_runs():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_traffic_is_read_from_the_committed_counter_summary(tmp_path):
+    """roofline.traffic comes from the profile summary's machine-readable lines, not from a
+    constant in bench.py; a missing file or kernel gives None."""
+    f = tmp_path / "c.txt"
+    f.write_text("prose\ntraffic_bytes_per_launch k_sp 7.5e9\ntraffic_bytes_per_launch k_lcg 7.9e9\n"
+                 "traffic_bytes_per_launch broken\n")
+    assert bench.measured_traffic("k_lcg", str(f)) == 7.9e9
+    assert bench.measured_traffic("k_sp", str(f)) == 7.5e9
+    assert bench.measured_traffic("k_ef_hist", str(f)) is None
+    assert bench.measured_traffic("k_lcg", str(tmp_path / "absent.txt")) is None
+    # the committed summary carries a figure for both window passes, of the right magnitude:
+    # between the stored bytes (6 per entry) and the algorithmic bytes (8 per entry) of a launch
+    d, k, n = 110_000_000, 1_100_000, 1024
+    for kern, part in (("k_sp", "sp"), ("k_lcg", "lcg")):
+        t = bench.measured_traffic(kern)
+        assert t is not None
+        assert bench.step_bytes(d, k, n, entry=6)[part] * 0.98 <= t <= bench.step_bytes(d, k, n)[part]
+
+
+def test_step_time_statistics():
+    st = bench.step_time_stats([3.0, 1.0, 2.0, 10.0])
+    assert st == {"median": 2.5, "min": 1.0, "max": 10.0, "mean": 4.0, "n": 4}
+    assert bench.step_time_stats([5.0, 1.0, 3.0])["median"] == 3.0
+
+
+def test_cpu_baseline_reports_host_cores_and_both_legs():
+    """On a tiny stand-in workload: the fields the benchmark line must carry."""
+    from paper_2306_06098_amd import synth
+    wl = synth.Workload("mini", 40_000, 16, 400, 1e-4, 3, 0.9, 5)
+    cb = bench.cpu_baseline(wl)
+    assert cb["kind"] == "oracle" and cb["unit"] == "steps/s" and cb["cores"] == 1
+    assert cb["host_cores"] == os.cpu_count()
+    assert cb["value"] > 0 and abs(cb["value"] * cb["seconds_per_step_full_window_scaled"] - 1) < 1e-9
+    assert cb["seconds_per_step_first_step_measured"] > 0
+    assert "measured" in cb["sample"] and "scaled" in cb["sample"]
