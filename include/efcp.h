@@ -151,8 +151,17 @@ size_t efcp_workspace_bytes_opts(int64_t d, int32_t m, int64_t k, const efcp_opt
  * synchronisation and no allocation.  Steps of one context must be issued in
  * order on one stream, or on streams ordered by the caller, with the device of
  * efcp_create current.  EFCP_EINVAL leaves the context untouched; after
- * EFCP_EHIP (a launch failed part-way) its state is undefined and it can only
- * be destroyed or overwritten by efcp_import_state. */
+ * EFCP_EHIP (a launch failed part-way) its state is undefined: every later
+ * efcp_step* / efcp_apply* returns EFCP_EHIP until efcp_import_state has
+ * replaced the state, or the context is destroyed.
+ *
+ * HIP graphs: the step number, the slot written, the number of filled rows and whether a row is
+ * evicted are kept in device memory and advanced by the step's own kernels; no kernel argument
+ * depends on them.  A call captured into a HIP graph (stream capture; the call then only records)
+ * is therefore not one particular step but "the next step": the graph can be replayed as every
+ * later step of the context, from the empty window on, with new contents in the captured grad
+ * buffer.  The inspection calls below synchronise the stream of the last efcp_* call only; after
+ * graph replays on another stream, synchronise that stream before calling them. */
 int efcp_step(efcp_ctx *ctx, const float *grad, float *out, void *stream);
 
 /* Which vector the step preconditions (Algorithm 1, line 8). */

@@ -51,10 +51,11 @@ __device__ __forceinline__ void pick_bin(const uint32_t *hist, uint32_t kr, uint
 
 template <int FMT>
 __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
-    const float *__restrict__ g, float *__restrict__ e, int64_t d, int32_t m, int32_t slot,
-    int64_t row_stride, int64_t k, int32_t kb, int32_t nsl,
+    const float *__restrict__ g, float *__restrict__ e, int64_t d, int32_t m,
+    const StepState *__restrict__ step, int64_t row_stride, int64_t k, int32_t kb, int32_t nsl,
     uint8_t *__restrict__ ring, int32_t *__restrict__ offT, uint32_t *__restrict__ blk_max, uint32_t *__restrict__ blk_tlo)
 {
+    const int32_t slot = step_view(step, m, kBefore).slot;           // the slot this step writes
     __shared__ uint32_t hist[kBins1];
     __shared__ uint32_t tmp[40];
     __shared__ uint32_t res[4];
@@ -226,7 +227,8 @@ __global__ __launch_bounds__(kBlkThreads, 8) void k_block_topk(
 // rowmax[slot] = upper edge of the 2^20-key bin that holds the largest |a_j| of the step: an upper
 // bound of every stored magnitude of the new row, bfloat16 rounding included.
 __global__ __launch_bounds__(1024) void k_block_finish(const uint32_t *__restrict__ blk_max, int32_t nsl,
-                                                       uint32_t *__restrict__ rowmax_slot,
+                                                       uint32_t *__restrict__ rowmax, int32_t m,
+                                                       const StepState *__restrict__ step,
                                                        SelState *__restrict__ sel)
 {
     __shared__ uint32_t wmax[16];
@@ -241,27 +243,26 @@ __global__ __launch_bounds__(1024) void k_block_finish(const uint32_t *__restric
 #pragma unroll
         for (int i = 0; i < 16; i++) bm = max(bm, wmax[i]);
         const uint32_t edge = ((bm >> 20) + 1u) << 20;
-        *rowmax_slot = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
+        rowmax[step_view(step, m, kBefore).slot] = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
         sel->tau = 0u;                          // no single threshold exists in this mode
         sel->quota = 0u;
     }
 }
 
-hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t slot,
-                             hipStream_t stream)
+hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream)
 {
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_block_topk<kFmtBf16>, dim3(g.n_slices), dim3(kBlkThreads), 0, stream, grad, p.e,
-                           g.d, g.m, slot, g.row_stride, g.k, g.kb, g.n_slices,
+                           g.d, g.m, p.step, g.row_stride, g.k, g.kb, g.n_slices,
                            p.ring, p.offT,
                            p.blk_max, p.blk_tlo);
     else
         hipLaunchKernelGGL(k_block_topk<kFmtF32>, dim3(g.n_slices), dim3(kBlkThreads), 0, stream, grad, p.e,
-                           g.d, g.m, slot, g.row_stride, g.k, g.kb, g.n_slices,
+                           g.d, g.m, p.step, g.row_stride, g.k, g.kb, g.n_slices,
                            p.ring, p.offT,
                            p.blk_max, p.blk_tlo);
     hipLaunchKernelGGL(k_block_finish, dim3(1), dim3(1024), 0, stream, p.blk_max, g.n_slices,
-                       p.rowmax + slot, p.sel);
+                       p.rowmax, g.m, p.step, p.sel);
     return hipGetLastError();
 }
 

@@ -65,9 +65,13 @@ __device__ __forceinline__ double block_sum_f64_1024(double v, double *buf)
 // factor sigma_start/sigma_end, and a second sweep recomputes the chunk from
 // the right starting value and stores it.  Block b owns columns [64b, 64b+64);
 // column `old` is left alone (k_bwd clears it).
-__global__ __launch_bounds__(1024) void k_evict(int32_t m, int32_t ldm, int32_t old,
+// The kernel is part of every step; it returns at once while the window is not yet full.
+__global__ __launch_bounds__(1024) void k_evict(int32_t m, int32_t ldm, const StepState *__restrict__ step,
                                                 double *__restrict__ W)
 {
+    const StepView sv = step_view(step, m, kBefore);
+    if (!sv.evict) return;                    // uniform: nothing is replaced by this step
+    const int32_t old = sv.slot;
     __shared__ double s_p[kMaxM], s_ik[kMaxM], s_g[kMaxM], s_sig[kMaxM + 1];
     __shared__ double s_wave[16];
     __shared__ double s_B[16][64];
@@ -150,11 +154,13 @@ __global__ __launch_bounds__(1024) void k_evict(int32_t m, int32_t ldm, int32_t 
 // ------------------------------------------------------------------
 // z = W s, w = W q.  One wave per row; sq[j] = (q_j, s_j).  The entry of the
 // slot being (re)written is excluded on both sides.
-__global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, int32_t slot,
-                                             const double *__restrict__ W,
+// whole != 0 (efcp_apply): no slot is being rewritten, the product runs over the whole factor.
+__global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, const StepState *__restrict__ step,
+                                             int32_t whole, const double *__restrict__ W,
                                              const double2 *__restrict__ sq,
                                              double2 *__restrict__ zw)
 {
+    const int32_t slot = whole ? -1 : step_view(step, m, kAfter).slot;
     __shared__ double2 s_sq[kMaxM];
     for (int j = threadIdx.x; j < kMaxM; j += 256)
         s_sq[j] = (j < m && j != slot) ? sq[j] : make_double2(0.0, 0.0);
@@ -182,8 +188,8 @@ __global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, int32_t slo
 // column cl, so 64 blocks share the one pass over W and a thread waits for 16 loads, not 64.
 constexpr int kBwdCols = 16;
 
-__global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t slot, double lambda,
-                                              double *__restrict__ W,
+__global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const StepState *__restrict__ step,
+                                              double lambda, double *__restrict__ W,
                                               const double2 *__restrict__ sq,
                                               const double2 *__restrict__ zw,
                                               double *__restrict__ S, double *__restrict__ q_out,
@@ -194,6 +200,7 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, int32_t sl
     __shared__ double buf[16];
     __shared__ double2 red[64][kBwdCols];
 
+    const int32_t slot = step_view(step, m, kAfter).slot;         // the slot written by this step
     const int tid = threadIdx.x;
     double z = 0.0, w = 0.0;
     if (tid < m && tid != slot) {
@@ -288,26 +295,25 @@ __global__ __launch_bounds__(1024) void k_apply_bwd(int32_t m, int32_t ldm, doub
     }
 }
 
-hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
+hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, slot, p.W);
+    hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, p.step, p.W);
     return hipGetLastError();
 }
 
-hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
-                       int32_t evict, double lambda, hipStream_t stream)
+hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, slot, p.W, p.sq,
+    hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, p.step, 0, p.W, p.sq,
                        p.zw);
-    hipLaunchKernelGGL(k_bwd, dim3((g.m + kBwdCols - 1) / kBwdCols), dim3(1024), 0, stream, g.m, g.ldm, slot, lambda,
-                       p.W, p.sq, p.zw, p.S, p.q, p.coef, p.status);
+    hipLaunchKernelGGL(k_bwd, dim3((g.m + kBwdCols - 1) / kBwdCols), dim3(1024), 0, stream, g.m, g.ldm, p.step,
+                       lambda, p.W, p.sq, p.zw, p.S, p.q, p.coef, p.status);
     return hipGetLastError();
 }
 
 hipError_t launch_coef_apply(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream)
 {
-    // slot = -1: no row is left out; unfilled rows and columns of W are exact zeros
-    hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, -1, p.W, p.sq, p.zw);
+    // no row is left out; unfilled rows and columns of W are exact zeros
+    hipLaunchKernelGGL(k_fwd, dim3((g.m + 3) / 4), dim3(256), 0, stream, g.m, g.ldm, p.step, 1, p.W, p.sq, p.zw);
     hipLaunchKernelGGL(k_apply_bwd, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, lambda, p.W,
                        p.sq, p.zw, p.q, p.coef);
     return hipGetLastError();

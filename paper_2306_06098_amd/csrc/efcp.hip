@@ -119,7 +119,7 @@ size_t row_payload_bytes(const Geometry &g)
 struct Layout {
     size_t e, ring, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
         cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
-        n_stages, col, total;
+        n_stages, col, step, total;
 };
 
 Layout make_layout(const Geometry &g)
@@ -155,6 +155,7 @@ Layout make_layout(const Geometry &g)
     l.n_stages = take(g.ggt ? 256 : 0);
     l.col = take(((size_t)g.n_slices + 1) * sizeof(int32_t));
     l.status = take(256);
+    l.step = take(sizeof(StepState));
     l.total = o;
     return l;
 }
@@ -216,10 +217,10 @@ struct efcp_ctx {
     void *ws;
     size_t ws_bytes;
     bool own_ws;
-    int64_t t;
-    // Global Top-k: the slot whose row still has to be taken out of e (the next step's first
-    // pass does it; read-outs do it on the host); -1: e is final.
-    int32_t pending_slot;
+    // The step count and the slot whose row is still to be taken out of e live in device memory
+    // (p.step) and are advanced by the step's kernels; host code reads them only in the
+    // inspection calls, after synchronising.
+    bool broken;                     // a launch failed part-way: the state is undefined
     hipStream_t last_stream;
     // The eviction update of the inverse factor depends on the previous step only; it runs on
     // this stream next to the d-sized passes of the step and is joined before k_fwd.
@@ -344,8 +345,7 @@ extern "C" int efcp_create_opts(efcp_ctx **out, int64_t d, int32_t m, int64_t k,
     if (!ctx) return EFCP_ENOMEM;
     ctx->g = g;
     ctx->lambda = lambda;
-    ctx->t = 0;
-    ctx->pending_slot = -1;
+    ctx->broken = false;
     ctx->last_stream = nullptr;
     ctx->err = "no error";
     ctx->prof_on = false;
@@ -400,12 +400,15 @@ extern "C" int efcp_create_opts(efcp_ctx **out, int64_t d, int32_t m, int64_t k,
     p.n_stages = reinterpret_cast<int32_t *>(b + l.n_stages);
     p.col = reinterpret_cast<int32_t *>(b + l.col);
     p.status = reinterpret_cast<uint32_t *>(b + l.status);
+    p.step = reinterpret_cast<StepState *>(b + l.step);
 
     // Everything starts as zero bytes: e = 0, offsets, Gram matrix, factor, histograms, counters,
     // and the ring too: the SP pass multiplies entries that lie outside a run (other slices' entries,
     // or the unused tail of a row's last group) by zero, so they must be finite numbers, never
     // whatever the memory held before.
     hipError_t rc = hipMemset(b, 0, l.total);
+    const StepState first_state = {0, -1, 0};              // no step done, e is final
+    if (rc == hipSuccess) rc = hipMemcpy(p.step, &first_state, sizeof first_state, hipMemcpyHostToDevice);
     ctx->side = nullptr;
     ctx->ev_fork = ctx->ev_join = nullptr;
     if (rc == hipSuccess) rc = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
@@ -458,62 +461,66 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     const size_t bytes = (size_t)ctx->g.d * sizeof(float);
     if (overlap(grad, dst, bytes)) return fail(ctx, EFCP_EINVAL, "grad and out/param overlap");
 
+    if (ctx->broken) return fail(ctx, EFCP_EHIP, "an earlier launch failed: the context can only be destroyed or re-imported");
+
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const Geometry &g = ctx->g;
     const DevicePtrs &p = ctx->p;
-    const int64_t t = ctx->t + 1;
-    const int32_t slot = (int32_t)((t - 1) % g.m);
-    const int32_t n_filled = (int32_t)(t < g.m ? t : g.m);
-    const int32_t evict = (t > g.m && !g.ggt) ? 1 : 0;      // Sparse GGT keeps no factor to update
     const bool x_is_row = x_source == EFCP_X_COMPRESSED;
+    // Nothing below depends on the step number: slot, rows filled and "does this step evict" are
+    // read by the kernels from p.step, which the reduction after the SP pass advances.  The same
+    // sequence of launches is therefore every step of the context (and a HIP graph captured
+    // from it can be replayed as the following steps).
+    const bool factor = !g.ggt;                          // Sparse GGT keeps no factor to update
 
     hipEvent_t *ev = nullptr;
     if (ctx->prof_on) ev = &ctx->ev[(size_t)(ctx->prof_count % kProfSteps) * kProfEvents];
     hipError_t rc = hipSuccess;
     auto mark = [&](int i) { if (ev && rc == hipSuccess) rc = hipEventRecord(ev[i], stream); };
 
-    if (evict) {        // fork: delete the oldest row from the inverse factor while the d-sized passes run
+    if (factor) {       // fork: delete the oldest row from the inverse factor while the d-sized passes run
         if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_fork, stream);
         if (rc == hipSuccess) rc = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
-        if (rc == hipSuccess) rc = launch_evict(g, p, slot, ctx->side);
+        if (rc == hipSuccess) rc = launch_evict(g, p, ctx->side);      // returns at once until the window is full
         if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_join, ctx->side);
     }
     mark(0);
     if (g.kb) {         // Top-k in blocks: error feedback, selection and compaction in one kernel
-        if (rc == hipSuccess) rc = launch_block_topk(g, p, grad, slot, stream);
+        if (rc == hipSuccess) rc = launch_block_topk(g, p, grad, stream);
         mark(1);
         mark(2);
     } else {
-        if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, ctx->pending_slot, stream);
+        if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
         mark(1);
-        if (rc == hipSuccess) rc = launch_select(g, p, slot, stream);
+        if (rc == hipSuccess) rc = launch_select(g, p, stream);
         mark(2);
-        if (rc == hipSuccess) rc = launch_compact(g, p, slot, stream);
+        if (rc == hipSuccess) rc = launch_compact(g, p, stream);
     }
     mark(3);
-    if (rc == hipSuccess) rc = launch_sp(g, p, grad, n_filled, slot, x_is_row ? 1 : 0, stream);
+    if (rc == hipSuccess) rc = launch_sp(g, p, grad, x_is_row ? 1 : 0, stream);
     mark(4);
-    if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
-    if (evict && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);      // join
+    // join before the reduction: it counts the step, and the eviction kernel reads the old count
+    if (factor && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);
+    if (rc == hipSuccess) rc = launch_sp_reduce(g, p, true, stream);
     if (rc == hipSuccess)
-        rc = g.ggt ? launch_ggt_step(g, p, n_filled, slot, ctx->lambda, stream)
-                   : launch_coef(g, p, n_filled, slot, evict, ctx->lambda, stream);
+        rc = g.ggt ? launch_ggt_step(g, p, ctx->lambda, stream) : launch_coef(g, p, ctx->lambda, stream);
     mark(5);
     if (rc == hipSuccess && dst) {
         LcgMode md;
-        md.x_row = x_is_row ? slot : -1;
+        md.x_is_newest_row = x_is_row;
         md.update = param != nullptr;
         md.lr = lr;
         md.decay = 1.0 - lr * weight_decay;
-        rc = launch_lcg(g, p, grad, dst, n_filled, ctx->lambda, md, stream);
+        rc = launch_lcg(g, p, grad, dst, ctx->lambda, md, stream);
     }
     mark(6);
 
-    ctx->t = t;
-    ctx->pending_slot = g.kb ? -1 : slot;
     ctx->last_stream = stream;
+    if (rc != hipSuccess) {
+        ctx->broken = true;
+        return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
+    }
     if (ctx->prof_on) ctx->prof_count++;
-    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
     return EFCP_OK;
 }
 
@@ -523,23 +530,22 @@ static int apply_impl(efcp_ctx *ctx, const DevicePtrs &p, const float *x, float 
     if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(outp) & 15))
         return fail(ctx, EFCP_EINVAL, "x/out not 16-byte aligned");
     if (overlap(x, outp, (size_t)ctx->g.d * sizeof(float))) return fail(ctx, EFCP_EINVAL, "x and out overlap");
+    if (ctx->broken) return fail(ctx, EFCP_EHIP, "an earlier launch failed: the context can only be destroyed or re-imported");
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const Geometry &g = ctx->g;
-    const int32_t n_filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
     hipError_t rc = hipSuccess;
-    if (ctx->last_stream != stream && ctx->t > 0) {
+    if (ctx->last_stream != stream && ctx->last_stream != nullptr) {
         // the window was written on another stream: order this call after it
         rc = hipEventRecord(ctx->ev_fork, ctx->last_stream);
         if (rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_fork, 0);
     }
-    if (n_filled > 0) {
-        if (rc == hipSuccess) rc = launch_sp(g, p, x, n_filled, 0, 2, stream);
-        if (rc == hipSuccess) rc = launch_sp_reduce(g, p, n_filled, stream);
-        if (rc == hipSuccess)
-            rc = g.ggt ? launch_ggt_apply(g, p, n_filled, ctx->lambda, stream)
-                       : launch_coef_apply(g, p, ctx->lambda, stream);
-    }
-    if (rc == hipSuccess) rc = launch_lcg(g, p, x, outp, n_filled, ctx->lambda, LcgMode{}, stream);
+    // the kernels take the number of filled rows from p.step; with an empty window they move no
+    // row and the result is x/lambda
+    if (rc == hipSuccess) rc = launch_sp(g, p, x, 2, stream);
+    if (rc == hipSuccess) rc = launch_sp_reduce(g, p, false, stream);
+    if (rc == hipSuccess)
+        rc = g.ggt ? launch_ggt_apply(g, p, ctx->lambda, stream) : launch_coef_apply(g, p, ctx->lambda, stream);
+    if (rc == hipSuccess) rc = launch_lcg(g, p, x, outp, ctx->lambda, LcgMode{}, stream);
     ctx->last_stream = stream;
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, hipGetErrorString(rc));
     return EFCP_OK;
@@ -600,14 +606,28 @@ static int sync_last(efcp_ctx *ctx)
     return EFCP_OK;
 }
 
+// The step state as the device holds it, after the stream of the last call has drained.
+static int read_step_state(efcp_ctx *ctx, StepState &st)
+{
+    if (int rc = sync_last(ctx)) return rc;
+    if (hipMemcpy(&st, ctx->p.step, sizeof st, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(ctx, EFCP_EHIP, "copy to host failed");
+    return EFCP_OK;
+}
+
+static int64_t rows_filled(const efcp_ctx *ctx, const StepState &st)
+{
+    return st.t_done < ctx->g.m ? st.t_done : ctx->g.m;
+}
+
 extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, float *val_host)
 {
     if (!ctx || !idx_host || !val_host) return EFCP_EINVAL;
     if (int rc = wrong_device(ctx)) return rc;
     const Geometry &g = ctx->g;
-    const int64_t filled = ctx->t < g.m ? ctx->t : g.m;
-    if (slot < 0 || slot >= filled) return fail(ctx, EFCP_EINVAL, "slot not filled");
-    if (int rc = sync_last(ctx)) return rc;
+    StepState now;
+    if (int rc = read_step_state(ctx, now)) return rc;
+    if (slot < 0 || slot >= rows_filled(ctx, now)) return fail(ctx, EFCP_EINVAL, "slot not filled");
     // the row's groups ([indices][values]) and its slice offsets; 16-bit in-slice indices become
     // absolute with the offsets
     const size_t ge = (size_t)group_entries(g), vb = value_bytes(g), gb = ge * (2 + vb);
@@ -647,11 +667,13 @@ extern "C" int efcp_get_row(efcp_ctx *ctx, int32_t slot, int32_t *idx_host, floa
 // e = a - c for a copy of the device buffer that still holds a at the entries of the newest row.
 static int settle_error(efcp_ctx *ctx, float *e_host)
 {
-    if (ctx->pending_slot < 0) return EFCP_OK;
+    StepState now;
+    if (int rc = read_step_state(ctx, now)) return rc;
+    if (now.pend_slot < 0) return EFCP_OK;
     const Geometry &g = ctx->g;
     std::vector<int32_t> idx((size_t)g.k);
     std::vector<float> val((size_t)g.k);
-    if (int rc = efcp_get_row(ctx, ctx->pending_slot, idx.data(), val.data())) return rc;
+    if (int rc = efcp_get_row(ctx, now.pend_slot, idx.data(), val.data())) return rc;
     for (int64_t p = 0; p < g.k; p++) {
         float &ej = e_host[idx[(size_t)p]];
         ej = ej - val[(size_t)p];                 // ej is a, val the stored a or bf16(a): +0 or the remainder
@@ -674,7 +696,8 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
 {
     if (!ctx) return EFCP_EINVAL;
     if (int rc = wrong_device(ctx)) return rc;
-    if (int rc = sync_last(ctx)) return rc;
+    StepState now;
+    if (int rc = read_step_state(ctx, now)) return rc;
     const Geometry &g = ctx->g;
     hipError_t rc = hipSuccess;
     if (S_host) rc = hipMemcpy(S_host, ctx->p.S, (size_t)g.m * g.m * 8, hipMemcpyDeviceToHost);
@@ -687,7 +710,7 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
     if (rc == hipSuccess) rc = hipMemcpy(&status, ctx->p.status, 4, hipMemcpyDeviceToHost);
     if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to host failed");
     if (tau) *tau = st.tau;
-    if (step) *step = ctx->t;
+    if (step) *step = now.t_done;
     if (status & kStatusCount) return fail(ctx, EFCP_EHIP, "selection wrote a row whose length is not k");
     if (status & kStatusRange) return fail(ctx, EFCP_ENUMERIC, "coefficients are not finite");
     if (status & kStatusPivot) return fail(ctx, EFCP_ENUMERIC, "non-positive pivot in the factor update");
@@ -709,10 +732,10 @@ struct StateHeader {
 };
 constexpr uint64_t kStateMagic = 0x3430545350434645ull;
 
-size_t state_bytes(const efcp_ctx *ctx)
+size_t state_bytes(const efcp_ctx *ctx, int64_t t_done)
 {
     const Geometry &g = ctx->g;
-    const size_t filled = (size_t)(ctx->t < g.m ? ctx->t : g.m);
+    const size_t filled = (size_t)(t_done < g.m ? t_done : g.m);
     return sizeof(StateHeader) + (size_t)g.d * 4 + filled * row_payload_bytes(g) +
            (size_t)(g.n_slices + 1) * g.m * 4 + (size_t)g.m * g.m * 8 +
            (g.ggt ? 0 : (size_t)g.m * g.ldm * 8) + (size_t)g.m * 4;
@@ -720,15 +743,22 @@ size_t state_bytes(const efcp_ctx *ctx)
 
 }  // namespace
 
-extern "C" size_t efcp_state_bytes(efcp_ctx *ctx) { return ctx ? state_bytes(ctx) : 0; }
+extern "C" size_t efcp_state_bytes(efcp_ctx *ctx)
+{
+    if (!ctx || wrong_device(ctx) != EFCP_OK) return 0;
+    StepState now;
+    if (read_step_state(ctx, now) != EFCP_OK) return 0;
+    return state_bytes(ctx, now.t_done);
+}
 
 extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
 {
     if (!ctx || !host_buf) return EFCP_EINVAL;
     if (int rc = wrong_device(ctx)) return rc;
-    if (bytes < state_bytes(ctx)) return fail(ctx, EFCP_ENOMEM, "state buffer too small");
+    StepState now;
+    if (int rc = read_step_state(ctx, now)) return rc;
+    if (bytes < state_bytes(ctx, now.t_done)) return fail(ctx, EFCP_ENOMEM, "state buffer too small");
     if (reinterpret_cast<uintptr_t>(host_buf) & 7) return fail(ctx, EFCP_EINVAL, "state buffer not 8-byte aligned");
-    if (int rc = sync_last(ctx)) return rc;
     const Geometry &g = ctx->g;
     const DevicePtrs &p = ctx->p;
     SelState st;
@@ -738,11 +768,11 @@ extern "C" int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes)
         return fail(ctx, EFCP_EHIP, "copy to host failed");
     StateHeader h{};
     h.magic = kStateMagic;
-    h.d = g.d; h.k = g.k; h.row_stride = g.row_stride; h.t = ctx->t;
+    h.d = g.d; h.k = g.k; h.row_stride = g.row_stride; h.t = now.t_done;
     h.m = g.m; h.ldm = g.ldm; h.slice = g.slice; h.n_slices = g.n_slices;
     h.lambda = ctx->lambda;
     h.t_lo = st.t_lo; h.status = status;
-    h.filled = (int32_t)(ctx->t < g.m ? ctx->t : g.m);
+    h.filled = (int32_t)rows_filled(ctx, now);
     h.fmt = g.fmt;
     h.kb = g.kb;
     h.ggt = g.ggt;
@@ -781,13 +811,8 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
         h.fmt != g.fmt || h.kb != g.kb || h.ggt != g.ggt ||
         h.t < 0 || h.filled != (int32_t)(h.t < g.m ? h.t : g.m))
         return fail(ctx, EFCP_EINVAL, "state does not belong to a context of this shape");
-    const int64_t t_keep = ctx->t;
-    ctx->t = h.t;                                    // state_bytes() depends on the step count
-    if (bytes < state_bytes(ctx)) {
-        ctx->t = t_keep;
-        return fail(ctx, EFCP_EINVAL, "state buffer truncated");
-    }
-    if (hipDeviceSynchronize() != hipSuccess) { ctx->t = t_keep; return fail(ctx, EFCP_EHIP, "sync failed"); }
+    if (bytes < state_bytes(ctx, h.t)) return fail(ctx, EFCP_EINVAL, "state buffer truncated");
+    if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, EFCP_EHIP, "sync failed");
     const DevicePtrs &p = ctx->p;
     const unsigned char *o = static_cast<const unsigned char *>(host_buf) + sizeof h;
     hipError_t rc = hipSuccess;
@@ -807,14 +832,19 @@ extern "C" int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t byt
     st.t_lo = h.t_lo;
     if (rc == hipSuccess) rc = hipMemcpy(p.sel, &st, sizeof st, hipMemcpyHostToDevice);
     if (rc == hipSuccess) rc = hipMemcpy(p.status, &h.status, 4, hipMemcpyHostToDevice);
+    const StepState imported = {h.t, -1, 0};         // an exported e is final: nothing is pending
+    if (rc == hipSuccess) rc = hipMemcpy(p.step, &imported, sizeof imported, hipMemcpyHostToDevice);
     if (rc == hipSuccess) rc = hipMemset(p.hist1, 0, (size_t)kHist1Copies * (kBins1 + 2 * kBins2) * sizeof(uint32_t));
     // where each block starts counting is a hint only: start from "count everything"
     if (rc == hipSuccess && g.kb) rc = hipMemset(p.blk_tlo, 0, (size_t)g.n_slices * sizeof(uint32_t));
     // Sparse GGT: the decomposition that efcp_apply replays is rebuilt from the imported S
-    if (rc == hipSuccess && g.ggt && h.filled > 0) rc = launch_ggt_refresh(g, p, h.filled, nullptr);
+    if (rc == hipSuccess && g.ggt && h.filled > 0) rc = launch_ggt_refresh(g, p, nullptr);
     if (rc == hipSuccess) rc = hipDeviceSynchronize();
-    if (rc != hipSuccess) return fail(ctx, EFCP_EHIP, "copy to device failed");
-    ctx->pending_slot = -1;                          // an exported e is final
+    if (rc != hipSuccess) {
+        ctx->broken = true;
+        return fail(ctx, EFCP_EHIP, "copy to device failed");
+    }
+    ctx->broken = false;                             // a complete state replaces whatever was there
     return EFCP_OK;
 }
 

@@ -149,6 +149,46 @@ struct SelState {
 
 enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
 
+// Where the context is in its sequence of steps.  It lives in device memory and is advanced by
+// the step's own kernels, so that no kernel argument depends on the step number: a step captured
+// in a HIP graph can be replayed as every later step.
+//   t_done      steps completed.  A step's kernels up to and including the SP pass run with
+//               t_done = t - 1 ("before": the slot written is t_done mod m, t_done + 1 rows are
+//               filled afterwards at most m, the oldest row is evicted iff t_done >= m); the
+//               reduction of the SP partial sums then adds one, and everything after it (the
+//               coefficient kernels, the LCG pass, efcp_apply) sees t_done = t ("after").
+//   pend_slot   global Top-k: the slot whose row still has to be taken out of e (the next step's
+//               first pass does it; read-outs do it on the host); -1: e is final.
+struct StepState {
+    long long t_done;
+    int32_t pend_slot;
+    int32_t reserved;
+};
+
+struct StepView {
+    int32_t slot;        // before: the slot this step writes; after: the slot written last
+    int32_t n_filled;    // rows of the window that hold a vector (including this step's)
+    int32_t evict;       // before: this step replaces a row (the window was full)
+};
+
+enum : int { kBefore = 0, kAfter = 1 };
+
+__device__ __forceinline__ StepView step_view(const StepState *__restrict__ st, int32_t m, int phase)
+{
+    const long long td = st->t_done;
+    StepView v;
+    if (phase == kBefore) {
+        v.slot = (int32_t)(td % m);
+        v.n_filled = (int32_t)(td + 1 < (long long)m ? td + 1 : (long long)m);
+        v.evict = td >= (long long)m ? 1 : 0;
+    } else {
+        v.slot = td > 0 ? (int32_t)((td - 1) % m) : 0;
+        v.n_filled = (int32_t)(td < (long long)m ? td : (long long)m);
+        v.evict = 0;
+    }
+    return v;
+}
+
 struct Geometry {
     int64_t d, k, row_stride;    // row_stride: entries per row of the ring (k rounded up to 64)
     int64_t row_bytes;           // row_stride * bytes per entry
@@ -182,37 +222,37 @@ struct DevicePtrs {
     int32_t *n_stages;       // stages logged by the last decomposition
     int32_t *col;            // [n_slices+1] one column of offT, gathered for read-outs
     uint32_t *status;
+    StepState *step;
 };
 
 // Launchers (each enqueues on `stream` and returns hipGetLastError()).
-hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t pending_slot,
-                          hipStream_t stream);
-hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
-hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
-// x_source: 0 = dense x next to the newest row, 1 = the newest row is x, 2 = dense x only
-hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t slot,
-                             hipStream_t stream);
-hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
-                     int32_t slot, int32_t x_source, hipStream_t stream);
-hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
-hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream);
-hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot,
-                       int32_t evict, double lambda, hipStream_t stream);
+// No launcher takes the step number, the slot or the number of filled rows: the kernels read them
+// from p.step.
+hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
+hipError_t launch_select(const Geometry &g, const DevicePtrs &p, hipStream_t stream);
+hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, hipStream_t stream);
+hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
+// x_source: 0 = dense x next to the newest row (a step), 1 = the newest row is x (a step),
+// 2 = dense x only, on the window as it stands (efcp_apply)
+hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t x_source,
+                     hipStream_t stream);
+// commit: this reduction ends the "before" part of a step: it advances p.step
+hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, bool commit, hipStream_t stream);
+hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, hipStream_t stream);
+hipError_t launch_coef(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream);
 // Coefficients for an arbitrary x on the window as it stands (nothing is inserted).
 hipError_t launch_coef_apply(const Geometry &g, const DevicePtrs &p, double lambda, hipStream_t stream);
-hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot, double eps,
-                           hipStream_t stream);
-hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, int32_t n_filled, double eps,
-                            hipStream_t stream);
-hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream);
+hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, double eps, hipStream_t stream);
+hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, double eps, hipStream_t stream);
+hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, hipStream_t stream);
 hipError_t configure_ggt();
 struct LcgMode {
-    int32_t x_row = -1;      // >= 0: x is this window row (the dense pointer is not read)
-    bool update = false;     // out holds parameters: theta <- decay*theta - lr*(F^-1 x)
+    bool x_is_newest_row = false;    // x is the row written last (the dense pointer is not read)
+    bool update = false;             // out holds parameters: theta <- decay*theta - lr*(F^-1 x)
     double decay = 1.0, lr = 0.0;
 };
-hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
-                      int32_t n_filled, double lambda, const LcgMode &md, hipStream_t stream);
+hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out, double lambda,
+                      const LcgMode &md, hipStream_t stream);
 hipError_t configure_sp(const Geometry &g);
 hipError_t configure_lcg(const Geometry &g);
 

@@ -42,7 +42,8 @@ __device__ __forceinline__ void rr_pair(int32_t N, int32_t r, int32_t j, int32_t
 // One workgroup of 1024 threads.  update != 0: first write the new Gram row and column (sq[].y)
 // into S and q (sq[].x) into q_out.  Then diagonalise S[0..n)[0..n).  Outputs: lam[m]
 // (eigenvalues, 0 beyond n), the rotation log rot[stage][64] = (c, s) and *n_stages.
-__global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t slot, int32_t update,
+// The slot written last and the number of filled rows n come from the step state ("after").
+__global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__restrict__ step, int32_t update,
                                                   double *__restrict__ S, const double2 *__restrict__ sq,
                                                   double *__restrict__ q_out, double *__restrict__ lam,
                                                   double2 *__restrict__ rot, int32_t *__restrict__ n_stages,
@@ -53,6 +54,8 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t 
     double2 *cs = reinterpret_cast<double2 *>(A + kGgtMaxM * kGgtLd);      // [64]
     int32_t *n_rot = reinterpret_cast<int32_t *>(cs + 64);                 // [1] rotations of this sweep
 
+    const StepView sv = step_view(step, m, kAfter);
+    const int32_t n = sv.n_filled, slot = sv.slot;
     const int tid = threadIdx.x;
     if (update) {
         if (tid < m) {
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, int32_t n, int32_t 
 
 // One wave.  y = V^T q by the logged rotations in order, z_i = y_i / (eps sigma_i (sigma_i + eps)),
 // coef = V z by the log backwards.  q is sq[].x; coef of slots >= n is 0.
-__global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, int32_t n, double eps,
+__global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, const StepState *__restrict__ step, double eps,
                                                  const double2 *__restrict__ sq,
                                                  const double *__restrict__ lam,
                                                  const double2 *__restrict__ rot,
@@ -186,6 +189,7 @@ __global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, int32_t n, double ep
 {
     __shared__ double y[kGgtMaxM + 2];
     const int lane = threadIdx.x;
+    const int32_t n = step_view(step, m, kAfter).n_filled;
     const int32_t N = (n + 1) & ~1, half = N >> 1;
     const int32_t stages = *n_stages;
     double lmax = 0.0;
@@ -256,29 +260,27 @@ hipError_t configure_ggt()
 }
 
 // Coefficients of the step: new Gram row/column, eigendecomposition, coefficients for q.
-hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, int32_t n_filled, int32_t slot, double eps,
-                           hipStream_t stream)
+hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, double eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, n_filled, slot, 1, p.S,
+    hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, p.step, 1, p.S,
                        p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps);
-    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, n_filled, eps, p.sq, p.lam, p.rot,
+    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, p.step, eps, p.sq, p.lam, p.rot,
                        p.n_stages, p.q, p.coef);
     return hipGetLastError();
 }
 
 // Decomposition of S as it stands (after a state import), without touching S or q.
-hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream)
+hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, n_filled, 0, 0, p.S,
+    hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, p.step, 0, p.S,
                        p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps);
     return hipGetLastError();
 }
 
 // Coefficients for another x on the window as it stands: the decomposition of the last step is reused.
-hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, int32_t n_filled, double eps,
-                            hipStream_t stream)
+hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, double eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, n_filled, eps, p.sq, p.lam, p.rot,
+    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, p.step, eps, p.sq, p.lam, p.rot,
                        p.n_stages, p.q, p.coef);
     return hipGetLastError();
 }

@@ -62,23 +62,30 @@ __device__ __forceinline__ void lcg_scatter(const typename Fmt<FMT>::iraw_t &iv,
 // moment (same mapping as the SP pass).  While a slice's rows stream, the x values of its epilogue and
 // the row offsets of the workgroup's next slice are already on their way in registers.
 //
-// XDENSE = false: x is window row `x_row` itself (x = c_t, Algorithm 1 line 8 as printed).  Then
-// x/lambda is one more multiple of a stored row, out = -sum_r (coef_r - [r = x_row]/lambda) c_r,
+// XDENSE = false: x is the window row written last (x = c_t, Algorithm 1 line 8 as printed).  Then
+// x/lambda is one more multiple of a stored row, out = -sum_r (coef_r - [r = that row]/lambda) c_r,
 // and no dense x is read at all.
+// The number of filled rows and the row written last come from the step state ("after": the
+// step has been counted by the time this kernel runs).  With an empty window (efcp_apply before
+// the first step) no row streams and the epilogue writes x/lambda.
 // UPDATE = true: `out` holds the parameters and receives the optimizer step with decoupled
 // weight decay, theta <- decay*theta - lr*(x/lambda - sum) (Algorithm 1 line 9), instead of
 // the preconditioned vector.
 template <int FMT, bool XDENSE, bool UPDATE>
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
-                                              int64_t d, int32_t m, int32_t n_filled, int64_t row_stride,
+                                              int64_t d, int32_t m, const StepState *__restrict__ step,
+                                              int64_t row_stride,
                                               int32_t slice, int32_t nsl, int32_t cpx,
                                               const uint8_t *__restrict__ ring,
                                               const int32_t *__restrict__ offT,
                                               const double *__restrict__ coef,
                                               const uint32_t *__restrict__ rowmax,
                                               uint32_t *__restrict__ status, double inv_lambda,
-                                              int32_t x_row, double decay, double lr)
+                                              double decay, double lr)
 {
+    const StepView sv = step_view(step, m, kAfter);
+    const int32_t n_filled = sv.n_filled, x_row = sv.slot;
+    const int32_t r_last = max(n_filled, 1) - 1;      // rows past the end repeat this one
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
     // `slice` coordinates (a multiple of 256, at most kCandBlock) are live; the LDS layout is that
@@ -134,7 +141,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const int32_t *off0 = offs, *off1 = offs + kMaxM;             // offsets of the current slice
     auto first = [&](LcgBatch<FMT> &b) {
         b.r = grp;
-        const int32_t rc = min(b.r, n_filled - 1);
+        const int32_t rc = min(b.r, r_last);
         b.p0 = off0[rc]; b.p1 = off1[rc]; b.c = cf[rc];
         b.pcs = b.p0 & ~(EPL - 1);
     };
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         const int32_t cont = a.pcs + kBatch * kChunk;
         const bool same = cont < a.p1;
         b.r = same ? a.r : a.r + kRowGroups;
-        const int32_t rc = min(b.r, n_filled - 1);                // past the end: repeat of the last row
+        const int32_t rc = min(b.r, r_last);                      // past the end: repeat of the last row
         const int32_t q0 = off0[rc], q1 = off1[rc];
         b.p0 = same ? a.p0 : q0;
         b.p1 = same ? a.p1 : q1;
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         b.pcs = same ? cont : (q0 & ~(EPL - 1));
     };
     auto load = [&](LcgBatch<FMT> &b) {
-        const int32_t rc = min(b.r, n_filled - 1);
+        const int32_t rc = min(b.r, r_last);
         const uint8_t *row =
             ring + (uint64_t)(uint32_t)rc * (uint32_t)row_stride * (uint64_t)Fmt<FMT>::kEntryBytes;
 #pragma unroll
@@ -280,37 +287,27 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     }
 }
 
-// out = x/lambda (empty window: F = lambda*I), or the parameter update with that vector.
-__global__ __launch_bounds__(256) void k_scale(const float *__restrict__ x, float *__restrict__ out, int64_t d,
-                                               double inv_lambda, int32_t update, double decay, double lr)
-{
-    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (j >= d) return;
-    const double y = (double)x[j] * inv_lambda;
-    out[j] = update ? (float)((double)out[j] * decay - lr * y) : (float)y;
-}
-
 namespace {
 
 template <int FMT, bool XDENSE, bool UPDATE>
-void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float *out, int32_t n_filled,
-                   double lambda, const LcgMode &md, hipStream_t stream)
+void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float *out, double lambda,
+                   const LcgMode &md, hipStream_t stream)
 {
     hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
-                       g.d, g.m, n_filled, g.row_stride, g.slice, g.n_slices, g.sp_grid / 8,
+                       g.d, g.m, p.step, g.row_stride, g.slice, g.n_slices, g.sp_grid / 8,
                        p.ring, p.offT,
-                       p.coef, p.rowmax, p.status, 1.0 / lambda, md.x_row, md.decay, md.lr);
+                       p.coef, p.rowmax, p.status, 1.0 / lambda, md.decay, md.lr);
 }
 
 template <int FMT>
-void launch_lcg_fmt(const Geometry &g, const DevicePtrs &p, const float *x, float *out, int32_t n_filled,
-                    double lambda, const LcgMode &md, hipStream_t stream)
+void launch_lcg_fmt(const Geometry &g, const DevicePtrs &p, const float *x, float *out, double lambda,
+                    const LcgMode &md, hipStream_t stream)
 {
-    const bool dense = md.x_row < 0;
-    if (dense && !md.update) launch_lcg_as<FMT, true, false>(g, p, x, out, n_filled, lambda, md, stream);
-    else if (dense) launch_lcg_as<FMT, true, true>(g, p, x, out, n_filled, lambda, md, stream);
-    else if (!md.update) launch_lcg_as<FMT, false, false>(g, p, x, out, n_filled, lambda, md, stream);
-    else launch_lcg_as<FMT, false, true>(g, p, x, out, n_filled, lambda, md, stream);
+    const bool dense = !md.x_is_newest_row;
+    if (dense && !md.update) launch_lcg_as<FMT, true, false>(g, p, x, out, lambda, md, stream);
+    else if (dense) launch_lcg_as<FMT, true, true>(g, p, x, out, lambda, md, stream);
+    else if (!md.update) launch_lcg_as<FMT, false, false>(g, p, x, out, lambda, md, stream);
+    else launch_lcg_as<FMT, false, true>(g, p, x, out, lambda, md, stream);
 }
 
 template <int FMT, bool XDENSE, bool UPDATE>
@@ -333,17 +330,12 @@ hipError_t set_lds_lcg_fmt(const Geometry &g)
 }  // namespace
 
 // `out` receives x/lambda - sum_r coef_r c_r, or (md.update) is the parameter vector updated in
-// place.  md.x_row >= 0: x is that window row and the pointer x is not read.
-hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out,
-                      int32_t n_filled, double lambda, const LcgMode &md, hipStream_t stream)
+// place.  md.x_is_newest_row: x is the window row written last and the pointer x is not read.
+hipError_t launch_lcg(const Geometry &g, const DevicePtrs &p, const float *x, float *out, double lambda,
+                      const LcgMode &md, hipStream_t stream)
 {
-    if (n_filled == 0) {                      // only reachable with a dense x
-        hipLaunchKernelGGL(k_scale, dim3((unsigned)((g.d + 255) / 256)), dim3(256), 0, stream, x, out, g.d,
-                           1.0 / lambda, md.update ? 1 : 0, md.decay, md.lr);
-        return hipGetLastError();
-    }
-    if (g.fmt == kFmtBf16) launch_lcg_fmt<kFmtBf16>(g, p, x, out, n_filled, lambda, md, stream);
-    else launch_lcg_fmt<kFmtF32>(g, p, x, out, n_filled, lambda, md, stream);
+    if (g.fmt == kFmtBf16) launch_lcg_fmt<kFmtBf16>(g, p, x, out, lambda, md, stream);
+    else launch_lcg_fmt<kFmtF32>(g, p, x, out, lambda, md, stream);
     return hipGetLastError();
 }
 

@@ -69,9 +69,10 @@ __device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t
 // REDO = true: the pass that rebuilds the candidates from a (already in e)
 // with the threshold bin found by the first digit; it exits at once unless
 // the select state asks for it.
-// PEND (first pass only): `e` still holds the previous step's accumulator; the entries of the
-// row inserted then (pend_row, the run of this block given by two entries of its offset column)
-// count as +0, or as the rounding remainder a - bf16(a) when the window keeps bfloat16 values.
+// PEND (first pass only; 1: fp32 window, 2: bfloat16 window): if the step state names a pending
+// slot, `e` still holds the previous step's accumulator; the entries of the row inserted then (the
+// run of this block given by two entries of its offset column) count as +0, or as the rounding
+// remainder a - bf16(a) when the window keeps bfloat16 values.
 constexpr int kEfThreads = 512;                  // threads of a first-pass block
 constexpr int kEfWaves = kEfThreads / 64;
 constexpr int kEfChunk = kEfWaves * 1024;        // coordinates the block streams at a time
@@ -84,9 +85,10 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
                                                          int32_t *__restrict__ cand_idx,
                                                          float *__restrict__ cand_val,
                                                          uint32_t *__restrict__ cand_cnt,
-                                                         const uint8_t *__restrict__ pend_row,
-                                                         const int32_t *__restrict__ pend_off, int32_t m,
-                                                         int32_t blk)
+                                                         const uint8_t *__restrict__ ring,
+                                                         int64_t row_bytes,
+                                                         const int32_t *__restrict__ offT, int32_t m,
+                                                         int32_t blk, const StepState *__restrict__ step)
 {
     __shared__ uint32_t lh[REDO ? 1 : kBins1];
     __shared__ uint32_t s_cnt[2][kEfWaves];
@@ -101,11 +103,16 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
         if (PEND) {
             for (int i = threadIdx.x; i < kCandBlock / 32; i += kEfThreads) pend[i] = 0;
             __syncthreads();
-            const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
-            for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kEfThreads) {
-                constexpr int PF = PEND == 2 ? kFmtBf16 : kFmtF32;
-                const uint32_t pos = *entry_idx_ptr<PF>(const_cast<uint8_t *>(pend_row), (uint32_t)p);
-                atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
+            const int32_t ps = step->pend_slot;               // uniform
+            if (ps >= 0) {
+                const uint8_t *pend_row = ring + (int64_t)ps * row_bytes;
+                const int32_t *pend_off = offT + ps;
+                const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
+                for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kEfThreads) {
+                    constexpr int PF = PEND == 2 ? kFmtBf16 : kFmtF32;
+                    const uint32_t pos = *entry_idx_ptr<PF>(const_cast<uint8_t *>(pend_row), (uint32_t)p);
+                    atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
+                }
             }
         }
         __syncthreads();
@@ -287,7 +294,8 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ ca
 template <int NB>
 __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist,
                                                      SelState *__restrict__ sel, int pass,
-                                                     uint32_t k, uint32_t *__restrict__ rowmax_slot)
+                                                     uint32_t k, uint32_t *__restrict__ rowmax, int32_t m,
+                                                     const StepState *__restrict__ step)
 {
     __shared__ uint32_t tmp[33];
     __shared__ int top_bin;
@@ -345,7 +353,7 @@ __global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist
         // every |a_j| of this step is below the upper edge of the highest occupied bin:
         // an upper bound on the largest stored magnitude, enough to scale the LCG sum
         const uint32_t edge = ((uint32_t)top_bin + 1u) << 20;
-        *rowmax_slot = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
+        rowmax[step_view(step, m, kBefore).slot] = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
     }
 }
 
@@ -393,7 +401,7 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
                                                       uint32_t *__restrict__ sel_off,
                                                       uint32_t *__restrict__ eq_before,
                                                       SelState *__restrict__ sel, int32_t nb,
-                                                      int32_t m, int32_t slot,
+                                                      int32_t m, const StepState *__restrict__ step,
                                                       int32_t *__restrict__ offT, uint32_t k,
                                                       uint32_t *__restrict__ status)
 {
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict
         carry_sel += total_sel;
     }
     if (threadIdx.x == 0) {
-        offT[(int64_t)nb * m + slot] = (int32_t)carry_sel;
+        offT[(int64_t)nb * m + step_view(step, m, kBefore).slot] = (int32_t)carry_sel;
         sel->total = carry_sel;
         if (carry_sel != k) atomicOr(status, kStatusCount);
     }
@@ -454,13 +462,16 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
                                                               const SelState *__restrict__ sel,
                                                               const uint32_t *__restrict__ sel_off,
                                                               const uint32_t *__restrict__ eq_before,
-                                                              uint8_t *__restrict__ row, int32_t blk,
+                                                              uint8_t *__restrict__ ring,
+                                                              int64_t row_bytes, int32_t blk,
                                                               int32_t *__restrict__ offT, int32_t m,
-                                                              int32_t slot)
+                                                              const StepState *__restrict__ step)
 {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int32_t b = blockIdx.x * 4 + w;
     if (b >= nb) return;
+    const int32_t slot = step_view(step, m, kBefore).slot;
+    uint8_t *row = ring + (int64_t)slot * row_bytes;
     const int32_t seg_first = b * blk;
     const uint32_t tau = sel->tau, quota = sel->quota;
     const uint32_t cnt = cand_cnt[b];
@@ -503,61 +514,55 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
 
 // ------------------------------------------------------------------
 
-// pending_slot >= 0: the row in that slot was inserted by the previous step and its entries are
-// still to be taken out of e.
-hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, int32_t pending_slot,
-                          hipStream_t stream)
+hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream)
 {
-    const uint8_t *pidx = pending_slot >= 0 ? p.ring + (int64_t)pending_slot * g.row_bytes : nullptr;
-    const int32_t *poff = pending_slot >= 0 ? p.offT + pending_slot : nullptr;
-    if (pending_slot < 0)
-        hipLaunchKernelGGL((k_ef_hist<false, 0>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
-                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
-    else if (g.fmt == kFmtBf16)
+    if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
-                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, p.ring, g.row_bytes, p.offT,
+                           g.m, g.slice, p.step);
     else
         hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
-                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, pidx, poff, g.m, g.slice);
+                           g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, p.ring, g.row_bytes, p.offT,
+                           g.m, g.slice, p.step);
     return hipGetLastError();
 }
 
-hipError_t launch_select(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
+hipError_t launch_select(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
     const int32_t nb = g.n_slices;
     // one wave per candidate segment until every private histogram is in use
     const int32_t groups = (nb + 15) / 16 < kHistGroups ? (nb + 15) / 16 : kHistGroups;
     hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
-                       (uint32_t)g.k, p.rowmax + slot);
+                       (uint32_t)g.k, p.rowmax, g.m, p.step);
     hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kEfThreads), 0, stream, (const float *)nullptr,
-                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, (const uint8_t *)nullptr,
-                       (const int32_t *)nullptr, g.m, g.slice);
+                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, p.ring, g.row_bytes,
+                       p.offT, g.m, g.slice, p.step);
     hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
                        p.sel, p.hist2, 20, 10, g.slice, groups);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
-                       (uint32_t)g.k, p.rowmax + slot);
+                       (uint32_t)g.k, p.rowmax, g.m, p.step);
     hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
                        p.sel, p.hist3, 10, 0, g.slice, groups);
     hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist3, p.sel, 2,
-                       (uint32_t)g.k, p.rowmax + slot);
+                       (uint32_t)g.k, p.rowmax, g.m, p.step);
     hipLaunchKernelGGL(k_cand_count, dim3((nb + 3) / 4), dim3(kSelThreads), 0, stream, p.cand_val,
                        p.cand_cnt, nb, p.sel, p.cnt_gt, p.cnt_eq, g.slice);
     hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, stream, p.cnt_gt, p.cnt_eq, p.sel_off,
-                       p.eq_before, p.sel, nb, g.m, slot, p.offT,
+                       p.eq_before, p.sel, nb, g.m, p.step, p.offT,
                        (uint32_t)g.k, p.status);
     return hipGetLastError();
 }
 
-hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, int32_t slot, hipStream_t stream)
+hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
     if (g.fmt == kFmtBf16)
         hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
-                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice, p.offT, g.m, slot);
+                           p.eq_before, p.ring, g.row_bytes, g.slice, p.offT, g.m, p.step);
     else
         hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
                            stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
-                           p.eq_before, p.ring + (int64_t)slot * g.row_bytes, g.slice, p.offT, g.m, slot);
+                           p.eq_before, p.ring, g.row_bytes, g.slice, p.offT, g.m, p.step);
     return hipGetLastError();
 }
 

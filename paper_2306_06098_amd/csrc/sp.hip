@@ -77,12 +77,16 @@ enum : int { kXDense = 0, kXNewest = 1, kXOnly = 2 };
 // new slice issued before the last two.
 template <int FMT, int XM>
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
-                                             int32_t n_filled, int32_t slot, int64_t row_stride,
+                                             const StepState *__restrict__ step, int64_t row_stride,
                                              int64_t k, int32_t slice, int32_t nsl, int32_t cpx,
                                              const uint8_t *__restrict__ ring,
                                              const int32_t *__restrict__ offT,
                                              double2 *__restrict__ partial)
 {
+    // a step's SP pass runs before the step is counted, efcp_apply's on the window as it stands
+    const StepView sv = step_view(step, m, XM == kXOnly ? kAfter : kBefore);
+    const int32_t n_filled = sv.n_filled, slot = sv.slot;
+    const int32_t r_last = max(n_filled, 1) - 1;      // rows past the end repeat this one (row 0 of an empty window)
     using idx_t = typename Fmt<FMT>::idx_t;
     using val_t = typename Fmt<FMT>::val_t;
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     RunBatch<FMT> ba, bb;
     auto first = [&](RunBatch<FMT> &b) {
         b.r = grp;
-        const int32_t rc = min(b.r, n_filled - 1);
+        const int32_t rc = min(b.r, r_last);
         b.p0 = off0[rc]; b.p1 = off1[rc];
         b.pcs = b.p0 & ~(EPL - 1);
     };
@@ -177,14 +181,14 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
         const int32_t cont = a.pcs + kBatch * kChunk;
         const bool same = cont < a.p1;
         b.r = same ? a.r : a.r + kRowGroups;
-        const int32_t rc = min(b.r, n_filled - 1);                // past the end: repeat of the last row
+        const int32_t rc = min(b.r, r_last);                      // past the end: repeat of the last row
         const int32_t q0 = off0[rc], q1 = off1[rc];
         b.p0 = same ? a.p0 : q0;
         b.p1 = same ? a.p1 : q1;
         b.pcs = same ? cont : (q0 & ~(EPL - 1));
     };
     auto load = [&](RunBatch<FMT> &b) {
-        const int32_t rc = min(b.r, n_filled - 1);
+        const int32_t rc = min(b.r, r_last);
         const uint8_t *row = ring + (uint64_t)(uint32_t)rc * (uint32_t)row_stride * (uint64_t)kEntryBytes;
 #pragma unroll
         for (int c = 0; c < kBatch; c++) {
@@ -266,9 +270,20 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 // sq[r] = sum over workgroups of partial[b][r], in a fixed order: block bx
 // owns 64 rows; thread (bl, rl) adds workgroups bl, bl+16, ...; the 16
 // partial sums are then added in order.  Unfilled rows give exactly 0.
+// commit != 0: the "before" part of a step ends here (every kernel that needed t_done = t - 1 has
+// finished: they precede this one on the stream, and the eviction update on the side stream has
+// been joined), so one thread counts the step: t_done = t, and with the global Top-k the new row
+// becomes the one whose entries are still to be taken out of e.
 __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ partial, int32_t m,
-                                                    int32_t nwg, double2 *__restrict__ sq)
+                                                    int32_t nwg, double2 *__restrict__ sq,
+                                                    StepState *__restrict__ step, int32_t commit,
+                                                    int32_t pend_rows)
 {
+    if (commit && blockIdx.x == 0 && threadIdx.x == 0) {
+        const long long td = step->t_done;
+        step->pend_slot = pend_rows ? (int32_t)(td % m) : -1;
+        step->t_done = td + 1;
+    }
     __shared__ double2 sh[16][64];
     const int rl = threadIdx.x & 63, bl = threadIdx.x >> 6;
     const int32_t r = blockIdx.x * 64 + rl;
@@ -296,21 +311,19 @@ __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ 
 namespace {
 
 template <int FMT, int XM>
-void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled, int32_t slot,
-                  hipStream_t stream)
+void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, hipStream_t stream)
 {
-    hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, n_filled,
-                       slot, g.row_stride, g.k, g.slice, g.n_slices, g.sp_grid / 8,
+    hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, p.step,
+                       g.row_stride, g.k, g.slice, g.n_slices, g.sp_grid / 8,
                        p.ring, p.offT, p.partial);
 }
 
 template <int FMT>
-void launch_sp_fmt(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled, int32_t slot,
-                   int32_t xmode, hipStream_t stream)
+void launch_sp_fmt(const Geometry &g, const DevicePtrs &p, const float *x, int32_t xmode, hipStream_t stream)
 {
-    if (xmode == kXNewest) launch_sp_as<FMT, kXNewest>(g, p, x, n_filled, slot, stream);
-    else if (xmode == kXOnly) launch_sp_as<FMT, kXOnly>(g, p, x, n_filled, slot, stream);
-    else launch_sp_as<FMT, kXDense>(g, p, x, n_filled, slot, stream);
+    if (xmode == kXNewest) launch_sp_as<FMT, kXNewest>(g, p, x, stream);
+    else if (xmode == kXOnly) launch_sp_as<FMT, kXOnly>(g, p, x, stream);
+    else launch_sp_as<FMT, kXDense>(g, p, x, stream);
 }
 
 template <int FMT, int XM>
@@ -322,20 +335,20 @@ hipError_t set_lds_sp(const Geometry &g)
 
 }  // namespace
 
-// x_source: 0 = dense x plus the newest row (slot), 1 = the newest row is x (x unused),
-// 2 = dense x only (slot unused; the Gram half of the result is meaningless).
-hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t n_filled,
-                     int32_t slot, int32_t x_source, hipStream_t stream)
+// x_source: 0 = dense x plus the newest row, 1 = the newest row is x (x unused),
+// 2 = dense x only, window as it stands (the Gram half of the result is meaningless).
+hipError_t launch_sp(const Geometry &g, const DevicePtrs &p, const float *x, int32_t x_source,
+                     hipStream_t stream)
 {
-    if (g.fmt == kFmtBf16) launch_sp_fmt<kFmtBf16>(g, p, x, n_filled, slot, x_source, stream);
-    else launch_sp_fmt<kFmtF32>(g, p, x, n_filled, slot, x_source, stream);
+    if (g.fmt == kFmtBf16) launch_sp_fmt<kFmtBf16>(g, p, x, x_source, stream);
+    else launch_sp_fmt<kFmtF32>(g, p, x, x_source, stream);
     return hipGetLastError();
 }
 
-hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, int32_t n_filled, hipStream_t stream)
+hipError_t launch_sp_reduce(const Geometry &g, const DevicePtrs &p, bool commit, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_sp_reduce, dim3((g.m + 63) / 64), dim3(1024), 0, stream, p.partial, g.m,
-                       g.sp_grid, p.sq);
+                       g.sp_grid, p.sq, p.step, commit ? 1 : 0, g.kb ? 0 : 1);
     return hipGetLastError();
 }
 

@@ -773,6 +773,72 @@ def test_step_and_apply_under_hip_graph_capture(env):
             b.destroy()
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(values=1), dict(topk_block=16_384, k=40),
+                                dict(compressed=True), dict(update=True), dict(ggt=True, values=1)])
+def test_one_captured_step_replays_as_every_later_step(env, kw):
+    """No kernel argument of a step depends on the step number (slot, rows filled and whether a
+    row is evicted are read from device memory, which the step itself advances), so ONE HIP
+    graph captured from the very first step of a context is every later step as well: replayed
+    m + 7 times with new gradient contents in the captured buffer -- through the fill of the
+    window and on into steps that evict -- it must leave bit for bit what the same number of
+    eager efcp_step calls leave in a twin context: output (or updated parameters), every stored
+    row, e, S, q, coef, the step count.  Eager work and synchronisations sit between replays."""
+    torch, _, binding = env
+    dev = torch.device("cuda:0")
+    kw = dict(kw)
+    compressed, update = kw.pop("compressed", False), kw.pop("update", False)
+    d, m, lam = 150_011, 5, 1e-3
+    k = kw.pop("k", 1200)
+    a = binding.Efcp(d, m, k, lam, **kw)
+    b = binding.Efcp(d, m, k, lam, **kw)
+    xs = binding.X_COMPRESSED if compressed else binding.X_GRAD
+    try:
+        s = torch.cuda.Stream()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(3)
+        scale = torch.exp(torch.randn(d, device=dev, generator=gen))
+        g = torch.empty(d, device=dev)
+        oa, ob = torch.zeros(d, device=dev), torch.zeros(d, device=dev)
+
+        def call(ctx, out):
+            if update:
+                ctx.step_ex(g, xs, param=out, lr=1e-4, weight_decay=0.1, stream=s)
+            else:
+                ctx.step_ex(g, xs, out=out, stream=s)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):          # recorded, not run: b is still at step 0
+            call(b, ob)
+        assert b.get_small()["step"] == 0
+        for t in range(1, m + 8):
+            g.normal_(generator=gen)
+            g.mul_(scale)
+            torch.cuda.synchronize()
+            call(a, oa)
+            s.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(oa, ob), f"replay {t} differs from eager step {t}"
+            sa, sb = a.get_small(), b.get_small()
+            assert sa["step"] == sb["step"] == t
+            for key in ("S", "q", "coef"):
+                assert np.array_equal(sa[key], sb[key]), f"replay {t}: {key} differs"
+            slot = (t - 1) % m
+            (ia, va), (ib, vb) = a.get_row(slot), b.get_row(slot)
+            assert np.array_equal(ia, ib) and np.array_equal(bits(va), bits(vb))
+            assert np.array_equal(bits(a.get_error()), bits(b.get_error()))
+        # the context that only ever replayed its graph goes on eagerly, still in step with its twin
+        g.normal_(generator=gen)
+        torch.cuda.synchronize()
+        call(a, oa)
+        call(b, ob)
+        s.synchronize()
+        assert torch.equal(oa, ob) and b.get_small()["step"] == m + 8
+    finally:
+        a.destroy()
+        b.destroy()
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_caller_workspace_full_of_nan_patterns(env, bf16):
     """The library must not depend on what a workspace held before: entries outside
