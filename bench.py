@@ -9,15 +9,16 @@ FULL 1024-row window: the window is filled with 1024 untimed steps first.
 
 Prints one JSON line:
   value / ms_per_step   steps per second and milliseconds per step: wall clock over exactly --steps steps
-  step_ms               median / min / max / mean of the individual step times (HIP events on the step's
-                        stream, one before every step) over max(--steps, 50) steps: the --steps timed
-                        ones and, if those are fewer than 50, further steps run right after them
+  step_ms               median / min / max / mean of individual step times: max(--steps, 50) further steps
+                        right after the timed region, one HIP event before each on the steps' stream
+                        (the event itself costs a few microseconds per step, so these run slightly
+                        above ms_per_step)
+  kernel_ms             from 20 more steps with the library's HIP events around every kernel group
   step_bytes            algorithmic bytes of one step, 16*n*k + 24*d + 8*k (n rows filled): the method's
                         format, an int32 index and an fp32 value per window entry
   achieved_GBps, hbm_frac   step_bytes / median step time, and that over the 8 TB/s HBM peak
   stored_step_bytes, stored_GBps, hbm_frac_stored   the same with the bytes the library really keeps per
                         entry (a 16-bit in-slice index next to the value): what HBM has to deliver
-  kernel_ms             HIP-event time per step of each kernel group (events on the step's stream)
   roofline              the slower of the two window passes (k_sp, k_lcg): algorithmic bytes per
                         launch / HIP-event time per launch, against the HBM peak (`achieved`, `frac`);
                         achieved_stored / frac_stored: the same with the stored entry size, i.e. the
@@ -167,6 +168,10 @@ def main():
     ap.add_argument("--precond", choices=["mfac", "ggt"], default="mfac",
                     help="mfac = Sparse M-FAC (the benchmark's definition); ggt = Sparse GGT on the same "
                          "window with m = 100 and epsilon = 1e-3 (the paper runs it at the resnet20 size)")
+    ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
+                    help="eager: every step is an efcp_step call (its kernel launches); graph: one step per "
+                         "resident gradient buffer is captured into a HIP graph once (no kernel argument of a "
+                         "step depends on the step number) and the timed steps are replays of those graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -221,33 +226,58 @@ def main():
         stream.next_into(g)
     torch.cuda.synchronize()
 
-    def one_step(i):
+    def eager_step(i):
         if args.mode == "grad":
             ctx.step(pool[i % len(pool)], out)
         else:
             ctx.step_ex(pool[i % len(pool)], xsrc, **dest)
 
-    # Exactly --steps steps between two synchronisations give value / ms_per_step.  One HIP event
-    # before every step (on torch's current stream, which is the stream the steps run on) gives
-    # the individual step times; if --steps is below MIN_TIMED_STEPS, more steps follow the timed
-    # region so that the median rests on at least that many.
-    n_events = max(args.steps, MIN_TIMED_STEPS)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_events + 1)]
-    ctx.profile_enable(True)
+    one_step = eager_step
+    if args.launch == "graph":
+        # one graph per resident gradient buffer; capturing records the launches and runs nothing
+        graphs = []
+        cap_stream = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for j in range(len(pool)):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=cap_stream):
+                if args.mode == "grad":
+                    ctx.step(pool[j], out, stream=cap_stream)
+                else:
+                    ctx.step_ex(pool[j], xsrc, stream=cap_stream, **dest)
+            graphs.append(gr)
+        torch.cuda.synchronize()
+
+        def one_step(i):
+            graphs[i % len(graphs)].replay()
+        for i in range(args.warmup):
+            one_step(i)
+        torch.cuda.synchronize()
+
+    # (1) The timed region: exactly --steps steps between two synchronisations, nothing else on
+    # the stream (an event record between kernels costs several microseconds of its own).
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        marks[i].record()
         one_step(i)
-    marks[args.steps].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for i in range(args.steps, n_events):
+    # (2) Individual step times: max(--steps, MIN_TIMED_STEPS) further steps with one HIP event
+    # before each (on torch's current stream, which is the stream the steps run on).
+    n_events = max(args.steps, MIN_TIMED_STEPS)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_events + 1)]
+    for i in range(n_events):
+        marks[i].record()
         one_step(i)
-        marks[i + 1].record()
+    marks[n_events].record()
     torch.cuda.synchronize()
     per_step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(n_events)]
     stats = step_time_stats(per_step_ms)
+    # (3) Time per kernel group: 20 more eager steps with the library's own events around each group.
+    ctx.profile_enable(True)
+    for i in range(20):
+        eager_step(i)
+    torch.cuda.synchronize()
     ms_groups, covered = ctx.profile_read()
     ctx.profile_enable(False)
     sm = ctx.get_small()                 # raises if the library flagged a numeric problem
@@ -275,7 +305,7 @@ def main():
                    "window_format": ("bf16 value" if bf16 else "fp32 value") + " + 16-bit in-slice index "
                                     "(int32 indices at the interface)",
                    "mode": args.mode, "topk": args.topk,
-                   "preconditioner": args.precond},
+                   "preconditioner": args.precond, "launch": args.launch},
         "step_ms": stats,
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_med * 1e-3) / 1e9,

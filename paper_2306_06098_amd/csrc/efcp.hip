@@ -118,7 +118,7 @@ size_t row_payload_bytes(const Geometry &g)
 
 struct Layout {
     size_t e, ring, offT, S, W, partial, sq, zw, q, coef, rowmax, hist, sel, cnt_gt,
-        cnt_eq, sel_off, eq_before, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
+        cnt_eq, blk_gt, blk_eq, status, cand_idx, cand_val, cand_cnt, blk_max, blk_tlo, lam, rot,
         n_stages, col, step, total;
 };
 
@@ -145,8 +145,8 @@ Layout make_layout(const Geometry &g)
     l.sel = take(sizeof(SelState));
     l.cnt_gt = take((size_t)g.n_slices * sizeof(uint32_t));
     l.cnt_eq = take((size_t)g.n_slices * sizeof(uint32_t));
-    l.sel_off = take((size_t)g.n_slices * sizeof(uint32_t));
-    l.eq_before = take((size_t)g.n_slices * sizeof(uint32_t));
+    l.blk_gt = take((size_t)g.n_slices * sizeof(uint32_t));
+    l.blk_eq = take((size_t)g.n_slices * sizeof(uint32_t));
     l.cand_cnt = take((size_t)g.n_slices * sizeof(uint32_t));
     l.blk_max = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
     l.blk_tlo = take(g.kb ? (size_t)g.n_slices * sizeof(uint32_t) : 0);
@@ -388,8 +388,8 @@ extern "C" int efcp_create_opts(efcp_ctx **out, int64_t d, int32_t m, int64_t k,
     p.sel = reinterpret_cast<SelState *>(b + l.sel);
     p.cnt_gt = reinterpret_cast<uint32_t *>(b + l.cnt_gt);
     p.cnt_eq = reinterpret_cast<uint32_t *>(b + l.cnt_eq);
-    p.sel_off = reinterpret_cast<uint32_t *>(b + l.sel_off);
-    p.eq_before = reinterpret_cast<uint32_t *>(b + l.eq_before);
+    p.blk_gt = reinterpret_cast<uint32_t *>(b + l.blk_gt);
+    p.blk_eq = reinterpret_cast<uint32_t *>(b + l.blk_eq);
     p.cand_idx = reinterpret_cast<int32_t *>(b + l.cand_idx);
     p.cand_val = reinterpret_cast<float *>(b + l.cand_val);
     p.cand_cnt = reinterpret_cast<uint32_t *>(b + l.cand_cnt);

@@ -38,7 +38,6 @@ namespace efcp {
 constexpr int kCandBlock = 16384;    // widest d-slice (its accumulators fill the LDS); block of the block-wise Top-k
 constexpr int kMinSlice = 1024;      // narrowest slice chosen automatically
 constexpr int kMaxWgs = 256;         // persistent SP / LCG workgroups at most: 32 on each of 8 XCDs
-constexpr int kSelThreads = 256;     // threads per candidate count / compaction block (a wave per segment)
 constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
 constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
@@ -135,16 +134,17 @@ __device__ __forceinline__ uint32_t bf16_bits(float a)
     return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
 }
 
-// Device-resident state of the radix select of the current step.
+// Device-resident state of the radix select of the current step.  Each field has one writer
+// (workgroup 0 of the pass that settles it) and is read only by later kernels.
 struct SelState {
-    uint32_t prefix;     // key bits fixed so far
-    uint32_t kr;         // how many of the remaining candidates are still to take
+    uint32_t p1, kr1;    // digit 1 (key bits 30..20) and the rank still wanted inside that bin
+    uint32_t p2, kr2;    // digits 1 and 2 (bits 30..10), rank inside that bin
     uint32_t tau;        // final threshold key (k-th largest magnitude key)
     uint32_t quota;      // how many keys == tau are selected (lowest indices first)
     uint32_t n_gt;       // number of keys > tau
     uint32_t total;      // entries written to the new row (must equal k)
     uint32_t t_lo;       // keys >= t_lo are copied to the candidate list by the first pass
-    uint32_t redo;       // 1: the threshold bin lies below t_lo, candidates must be rebuilt
+    uint32_t redo;       // 1: the threshold bin lies below t_lo, the passes read the accumulator
 };
 
 enum : uint32_t { kStatusPivot = 1u, kStatusCount = 2u, kStatusRange = 4u };
@@ -211,7 +211,8 @@ struct DevicePtrs {
     uint32_t *rowmax;
     uint32_t *hist1, *hist2, *hist3;
     SelState *sel;
-    uint32_t *cnt_gt, *cnt_eq, *sel_off, *eq_before;
+    uint32_t *cnt_gt, *cnt_eq;       // [n_slices] keys > tau / == tau per candidate segment
+    uint32_t *blk_gt, *blk_eq;       // the same per workgroup of 16 segments
     int32_t *cand_idx;       // [n_slices][slice] candidate indices, ascending per segment
     float *cand_val;         // [n_slices][slice] candidate values
     uint32_t *cand_cnt;      // [n_slices] entries used per segment

@@ -18,9 +18,10 @@
 // inserted last (a bitmap in LDS, one bit per coordinate of the block).  Host code
 // that reads e in between applies the same rule.  The first-digit histogram
 // is exact, so it tells whether the threshold bin lies at or above t_lo; if it
-// does not (the threshold dropped by more than two bins in one step), one
-// extra pass over a rebuilds the candidates from the now known bin.  The
-// result is exact either way; the prediction only saves traffic.
+// does not (the threshold dropped by more than two bins in one step), the
+// later passes of that step read the accumulator itself instead of the
+// candidate lists.  The result is exact either way; the prediction only saves
+// traffic.
 //
 // Histograms are merged with integer atomics (order independent), candidates
 // and rows are written at positions computed by prefix sums, so every output
@@ -66,9 +67,6 @@ __device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t
 }
 
 // a = e + g (written over e), histogram of key bits 30..20, candidates.
-// REDO = true: the pass that rebuilds the candidates from a (already in e)
-// with the threshold bin found by the first digit; it exits at once unless
-// the select state asks for it.
 // PEND (first pass only; 1: fp32 window, 2: bfloat16 window): if the step state names a pending
 // slot, `e` still holds the previous step's accumulator; the entries of the row inserted then (the
 // run of this block given by two entries of its offset column) count as +0, or as the rounding
@@ -77,7 +75,7 @@ constexpr int kEfThreads = 512;                  // threads of a first-pass bloc
 constexpr int kEfWaves = kEfThreads / 64;
 constexpr int kEfChunk = kEfWaves * 1024;        // coordinates the block streams at a time
 
-template <bool REDO, int PEND>
+template <int PEND>
 __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict__ g,
                                                          float *__restrict__ e, int64_t d,
                                                          uint32_t *__restrict__ hist,
@@ -90,33 +88,27 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
                                                          const int32_t *__restrict__ offT, int32_t m,
                                                          int32_t blk, const StepState *__restrict__ step)
 {
-    __shared__ uint32_t lh[REDO ? 1 : kBins1];
+    __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t s_cnt[2][kEfWaves];
     __shared__ uint32_t pend[PEND ? kCandBlock / 32 : 1];       // one bit per coordinate of the block
-    uint32_t t_lo;
-    if (REDO) {
-        if (!sel->redo) return;
-        t_lo = sel->prefix << 20;
-    } else {
-        t_lo = sel->t_lo;
-        for (int i = threadIdx.x; i < kBins1; i += kEfThreads) lh[i] = 0;
-        if (PEND) {
-            for (int i = threadIdx.x; i < kCandBlock / 32; i += kEfThreads) pend[i] = 0;
-            __syncthreads();
-            const int32_t ps = step->pend_slot;               // uniform
-            if (ps >= 0) {
-                const uint8_t *pend_row = ring + (int64_t)ps * row_bytes;
-                const int32_t *pend_off = offT + ps;
-                const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
-                for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kEfThreads) {
-                    constexpr int PF = PEND == 2 ? kFmtBf16 : kFmtF32;
-                    const uint32_t pos = *entry_idx_ptr<PF>(const_cast<uint8_t *>(pend_row), (uint32_t)p);
-                    atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
-                }
+    const uint32_t t_lo = sel->t_lo;
+    for (int i = threadIdx.x; i < kBins1; i += kEfThreads) lh[i] = 0;
+    if (PEND) {
+        for (int i = threadIdx.x; i < kCandBlock / 32; i += kEfThreads) pend[i] = 0;
+        __syncthreads();
+        const int32_t ps = step->pend_slot;               // uniform
+        if (ps >= 0) {
+            const uint8_t *pend_row = ring + (int64_t)ps * row_bytes;
+            const int32_t *pend_off = offT + ps;
+            const int32_t p0 = pend_off[(int64_t)blockIdx.x * m], p1 = pend_off[(int64_t)(blockIdx.x + 1) * m];
+            for (int32_t p = p0 + (int32_t)threadIdx.x; p < p1; p += kEfThreads) {
+                constexpr int PF = PEND == 2 ? kFmtBf16 : kFmtF32;
+                const uint32_t pos = *entry_idx_ptr<PF>(const_cast<uint8_t *>(pend_row), (uint32_t)p);
+                atomicOr(&pend[pos >> 5], 1u << (pos & 31u));
             }
         }
-        __syncthreads();
     }
+    __syncthreads();
     // value of e at a coordinate whose pending bit is set
     // a - c as written (Algorithm 1, line 7): +0 for every finite a, NaN for an infinite one
     auto settled = [](float a) {
@@ -147,7 +139,7 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
                 gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (it < nit) {
                     ev[it] = load_stream_f4(e + wave_base + it * 256);
-                    if (!REDO) gv[it] = load_stream_f4(g + wave_base + it * 256);
+                    gv[it] = load_stream_f4(g + wave_base + it * 256);
                 }
             }
 #pragma unroll
@@ -161,17 +153,13 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
                     if (bits4 & 4u) ev[it].z = settled(ev[it].z);
                     if (bits4 & 8u) ev[it].w = settled(ev[it].w);
                 }
-                if (REDO) {
-                    a[it][0] = ev[it].x; a[it][1] = ev[it].y; a[it][2] = ev[it].z; a[it][3] = ev[it].w;
-                } else {
-                    a[it][0] = ev[it].x + gv[it].x;
-                    a[it][1] = ev[it].y + gv[it].y;
-                    a[it][2] = ev[it].z + gv[it].z;
-                    a[it][3] = ev[it].w + gv[it].w;
-                    if (it < nit)
-                        store_stream_f4(e + wave_base + it * 256,
-                                        make_float4(a[it][0], a[it][1], a[it][2], a[it][3]));
-                }
+                a[it][0] = ev[it].x + gv[it].x;
+                a[it][1] = ev[it].y + gv[it].y;
+                a[it][2] = ev[it].z + gv[it].z;
+                a[it][3] = ev[it].w + gv[it].w;
+                if (it < nit)
+                    store_stream_f4(e + wave_base + it * 256,
+                                    make_float4(a[it][0], a[it][1], a[it][2], a[it][3]));
             }
         };
         if (rem >= 1024) {
@@ -195,8 +183,8 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
                             const uint32_t q = (uint32_t)(j - block_first);
                             if ((pend[q >> 5] >> (q & 31u)) & 1u) ej = settled(ej);
                         }
-                        t = REDO ? ej : ej + g[j];
-                        if (!REDO) e[j] = t;
+                        t = ej + g[j];
+                        e[j] = t;
                         inmask |= 1u << (it * 4 + c);
                     }
                     a[it][c] = t;
@@ -210,7 +198,7 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
             for (int c = 0; c < 4; c++) {
                 const uint32_t key = mag_key(a[it][c]);
                 if ((inmask >> (it * 4 + c)) & 1u) {
-                    if (!REDO) atomicAdd(&lh[key >> 20], 1u);
+                    atomicAdd(&lh[key >> 20], 1u);
                     if (key >= t_lo) flags |= 1u << (it * 4 + c);
                 }
             }
@@ -229,271 +217,327 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
         used += total;
     }
     if (threadIdx.x == 0) cand_cnt[blockIdx.x] = used;
-    if (!REDO) {
-        __syncthreads();
-        // Most keys fall into a few dozen bins, which every block adds to at about the same time:
-        // the adds to one address queue up, so the blocks are spread over kHist1Copies histograms.
-        uint32_t *mine = hist + (blockIdx.x % kHist1Copies) * kBins1;
-        for (int i = threadIdx.x; i < kBins1; i += kEfThreads) {
-            const uint32_t c = lh[i];
-            if (c) atomicAdd(&mine[i], c);
-        }
+    __syncthreads();
+    // Most keys fall into a few dozen bins, which every block adds to at about the same time:
+    // the adds to one address queue up, so the blocks are spread over kHist1Copies histograms.
+    uint32_t *mine = hist + (blockIdx.x % kHist1Copies) * kBins1;
+    for (int i = threadIdx.x; i < kBins1; i += kEfThreads) {
+        const uint32_t c = lh[i];
+        if (c) atomicAdd(&mine[i], c);
     }
 }
 
 // ------------------------------------------------------------------
-// Histogram of the next 10-bit digit over the candidates whose higher key
-// bits equal the prefix found so far.  `groups` (at most kHistGroups) workgroups of 16 waves; a
-// wave takes one candidate segment at a time.  Every workgroup counts in its own
-// 1024-bin histogram in LDS (device-scope atomics on a few hot addresses from
-// thousands of waves serialise) and adds it once, at the end, into one of
-// kHist1Copies histograms in memory; k_pick_digit adds those up and clears them.
+// The passes after the first one.  Each is ONE kernel of 1024-thread workgroups that starts by
+// settling the previous digit itself: every workgroup adds up the kHist1Copies histograms that
+// the pass before left in memory and locates the bin of the kr-th largest remaining key (a few
+// KB of loads and one block-wide scan, the same in every workgroup, so all agree), workgroup 0
+// records the outcome in the select state, and the body goes on with it.  A histogram is
+// cleared by the pass after the one that read it.  Compared with one-workgroup kernels between
+// the passes this halves the number of dependent launches of a step (four instead of nine).
+//
+//   k_cand_hist<1>   settles digit 1 (bits 30..20); histogram of digit 2 (bits 19..10)
+//   k_cand_hist<2>   settles digit 2; histogram of digit 3 (bits 9..0); clears histogram 1
+//   k_cand_count     settles digit 3 = the threshold tau and the tie quota; counts keys > tau
+//                    and == tau per segment and per workgroup; clears histogram 2
+//   k_cand_compact   prefix sums of those counts (workgroup totals, then the 16 segments of
+//                    the workgroup), ordered compaction into the ring; clears histogram 3
+//
+// If the threshold bin turns out to lie below t_lo (the threshold fell by more than two bins in
+// one step), the candidate lists do not hold every key that matters.  The passes then read the
+// accumulator itself (it is in `e`), a whole slice in place of its candidate segment: the
+// result is the same, the step moves 16 more bytes per coordinate.
 
-__global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ cand_val,
-                                                    const uint32_t *__restrict__ cand_cnt, int32_t nb,
-                                                    const SelState *__restrict__ sel,
-                                                    uint32_t *__restrict__ hist_priv, int shift_hi,
-                                                    int shift_lo, int32_t blk, int32_t groups)
+constexpr int kSegsPerBlock = 16;        // one wave per segment
+
+// One segment as the passes see it: values in index order, and where each one sits.
+struct Segment {
+    const float *val;
+    const int32_t *idx;      // coordinates, or nullptr: value i is coordinate first + i
+    uint32_t cnt;
+    int32_t first;           // first coordinate of the slice
+};
+
+__device__ __forceinline__ Segment segment_of(int32_t b, int32_t blk, int64_t d, uint32_t redo,
+                                              const float *__restrict__ e,
+                                              const float *__restrict__ cand_val,
+                                              const int32_t *__restrict__ cand_idx,
+                                              const uint32_t *__restrict__ cand_cnt)
 {
-    __shared__ uint32_t lh[kBins2];
-    lh[threadIdx.x] = 0;
-    __syncthreads();
-    const uint32_t prefix = sel->prefix;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    // The count of the wave's next segment is fetched while the current one is processed, and
-    // eight loads per lane are issued before any is used (unconditional, clamped addresses).
-    int32_t b = blockIdx.x * 16 + w;
-    uint32_t cnt = b < nb ? cand_cnt[b] : 0u;
-    while (b < nb) {
-        const int32_t bn = b + groups * 16;
-        const uint32_t cnt_next = cand_cnt[min(bn, nb - 1)];
-        const float *seg = cand_val + (int64_t)b * blk;
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 512) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; u++) v[u] = seg[min(i0 + u * 64 + lane, cnt - 1)];
-#pragma unroll
-            for (int u = 0; u < 8; u++) {
-                const uint32_t kk = mag_key(v[u]);
-                if (i0 + u * 64 + lane < cnt && (kk >> shift_hi) == prefix)
-                    atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
-            }
-        }
-        b = bn;
-        cnt = cnt_next;
+    Segment sg;
+    const int64_t first = (int64_t)b * blk;
+    sg.first = (int32_t)first;
+    if (redo) {
+        sg.val = e + first;
+        sg.idx = nullptr;
+        sg.cnt = (uint32_t)(d - first < (int64_t)blk ? d - first : (int64_t)blk);
+    } else {
+        sg.val = cand_val + first;
+        sg.idx = cand_idx + first;
+        sg.cnt = cand_cnt[b];
     }
-    __syncthreads();
-    const uint32_t c = lh[threadIdx.x];
-    if (c) atomicAdd(&hist_priv[(blockIdx.x % kHist1Copies) * kBins2 + threadIdx.x], c);
+    return sg;
 }
 
-// ------------------------------------------------------------------
-// One workgroup: locate the digit in which the kr-th largest remaining key
-// falls and update the select state.
-// pass 0: 2048 bins (bits 30..20); pass 1, 2: 1024 bins.
+// Which of the NB bins of a digit holds the kr-th largest remaining key: the bins are walked
+// from the largest digit down.  `hist`: kHist1Copies histograms of NB bins each.  All 1024
+// threads call it and all get the result.  res: 3 words of LDS; tmp: 33 words of LDS.
+//   bin      the digit
+//   kr_rem   rank of the wanted key among the keys of that bin
+//   top      the highest occupied bin
 template <int NB>
-__global__ __launch_bounds__(1024) void k_pick_digit(uint32_t *__restrict__ hist,
-                                                     SelState *__restrict__ sel, int pass,
-                                                     uint32_t k, uint32_t *__restrict__ rowmax, int32_t m,
-                                                     const StepState *__restrict__ step)
+__device__ __forceinline__ void settle_digit(const uint32_t *__restrict__ hist, uint32_t kr, uint32_t *tmp,
+                                             uint32_t *res, uint32_t &bin_out, uint32_t &kr_rem,
+                                             uint32_t &top)
 {
-    __shared__ uint32_t tmp[33];
-    __shared__ int top_bin;
-    if (threadIdx.x == 0) top_bin = 0;
-    __syncthreads();
     constexpr int PER = NB / 1024;
-    const uint32_t kr = (pass == 0) ? k : sel->kr;
-    const uint32_t prefix = (pass == 0) ? 0u : sel->prefix;
-    const uint32_t t_lo = sel->t_lo;
-
-    // Walk the bins from the largest digit down: rb = NB-1-bin.  `hist` holds kHist1Copies
-    // histograms filled by atomics; they are added up here and cleared for the next step.
+    if (threadIdx.x < 3) res[threadIdx.x] = 0;
     uint32_t c[PER];
     uint32_t local = 0;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int bin = NB - 1 - (threadIdx.x * PER + i);
-        uint32_t v[kHist1Copies];
-#pragma unroll
-        for (int u = 0; u < kHist1Copies; u++) v[u] = hist[u * NB + bin];
         uint32_t t = 0;
 #pragma unroll
-        for (int u = 0; u < kHist1Copies; u++) {
-            t += v[u];
-            if (v[u]) hist[u * NB + bin] = 0;
-        }
+        for (int u = 0; u < kHist1Copies; u++) t += hist[u * NB + bin];
         c[i] = t;
-        if (pass == 0 && t) atomicMax(&top_bin, bin);
-        local += c[i];
+        local += t;
     }
     uint32_t total;
-    uint32_t above = block_excl_scan_u32(local, tmp, &total);   // count in larger digits
+    uint32_t above = block_excl_scan_u32(local, tmp, &total);     // count in larger digits; syncs
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int bin = NB - 1 - (threadIdx.x * PER + i);
+        if (c[i]) atomicMax(&res[2], (uint32_t)bin);
         if (above < kr && kr <= above + c[i]) {
-            const uint32_t np = (pass == 0) ? (uint32_t)bin : ((prefix << 10) | (uint32_t)bin);
-            sel->prefix = np;
-            sel->kr = kr - above;
-            if (pass == 0) {
-                // candidates hold every key >= t_lo: enough iff the threshold bin starts at or above t_lo
-                sel->redo = ((uint32_t)bin << 20) < t_lo ? 1u : 0u;
-            }
-            if (pass == 2) {
-                sel->tau = np;
-                sel->quota = kr - above;
-                sel->n_gt = k - (kr - above);
-                const uint32_t tb = np >> 20;             // next step collects from two bins below
-                sel->t_lo = (tb >= 2 ? tb - 2 : 0u) << 20;
-            }
+            res[0] = (uint32_t)bin;
+            res[1] = kr - above;
         }
         above += c[i];
     }
-    if (pass == 0 && threadIdx.x == 0) {
-        // every |a_j| of this step is below the upper edge of the highest occupied bin:
-        // an upper bound on the largest stored magnitude, enough to scale the LCG sum
-        const uint32_t edge = ((uint32_t)top_bin + 1u) << 20;
-        rowmax[step_view(step, m, kBefore).slot] = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
-    }
+    __syncthreads();
+    bin_out = res[0];
+    kr_rem = res[1];
+    top = res[2];
+    __syncthreads();
 }
 
-// ------------------------------------------------------------------
-// Per candidate segment: how many keys are > tau and == tau.  One wave per segment.
-__global__ __launch_bounds__(kSelThreads) void k_cand_count(const float *__restrict__ cand_val,
-                                                            const uint32_t *__restrict__ cand_cnt,
-                                                            int32_t nb, const SelState *__restrict__ sel,
-                                                            uint32_t *__restrict__ cnt_gt,
-                                                            uint32_t *__restrict__ cnt_eq, int32_t blk)
+__device__ __forceinline__ void clear_histogram(uint32_t *__restrict__ hist, int words)
 {
+    for (int i = blockIdx.x * 1024 + threadIdx.x; i < words; i += gridDim.x * 1024) hist[i] = 0;
+}
+
+// LEVEL 1: digit 1 is settled from hist_prev (2048 bins) and the histogram of digit 2 is built;
+// LEVEL 2: digit 2 is settled from hist_prev (1024 bins), histogram of digit 3; `hist_clear`
+// (the histogram the previous pass read) is zeroed.
+// `groups` workgroups (at most kHistGroups); a wave takes one segment at a time.  Every workgroup
+// counts in its own 1024-bin histogram in LDS (device-scope atomics on a few hot addresses from
+// thousands of waves serialise) and adds it once, at the end, into one of kHist1Copies
+// histograms in memory.
+template <int LEVEL>
+__global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e, int64_t d,
+                                                    const float *__restrict__ cand_val,
+                                                    const int32_t *__restrict__ cand_idx,
+                                                    const uint32_t *__restrict__ cand_cnt, int32_t nb,
+                                                    SelState *__restrict__ sel,
+                                                    const uint32_t *__restrict__ hist_prev,
+                                                    uint32_t *__restrict__ hist_out,
+                                                    uint32_t *__restrict__ hist_clear, uint32_t k,
+                                                    int32_t blk, int32_t groups,
+                                                    uint32_t *__restrict__ rowmax, int32_t m,
+                                                    const StepState *__restrict__ step)
+{
+    __shared__ uint32_t lh[kBins2];
+    __shared__ uint32_t tmp[33], res[3];
+    lh[threadIdx.x] = 0;
+    uint32_t prefix, redo;
+    if (LEVEL == 1) {
+        uint32_t bin, kr1, top;
+        settle_digit<kBins1>(hist_prev, k, tmp, res, bin, kr1, top);
+        prefix = bin;
+        // candidates hold every key >= t_lo: enough iff the threshold bin starts at or above t_lo
+        redo = (bin << 20) < sel->t_lo ? 1u : 0u;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            sel->p1 = bin;
+            sel->kr1 = kr1;
+            sel->redo = redo;
+            // every |a_j| of this step is below the upper edge of the highest occupied bin:
+            // an upper bound on the largest stored magnitude, enough to scale the LCG sum
+            const uint32_t edge = (top + 1u) << 20;
+            rowmax[step_view(step, m, kBefore).slot] = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
+        }
+    } else {
+        uint32_t bin, kr2, top;
+        settle_digit<kBins2>(hist_prev, sel->kr1, tmp, res, bin, kr2, top);
+        prefix = (sel->p1 << 10) | bin;
+        redo = sel->redo;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            sel->p2 = prefix;
+            sel->kr2 = kr2;
+        }
+        clear_histogram(hist_clear, kHist1Copies * kBins1);
+    }
+    constexpr int shift_hi = LEVEL == 1 ? 20 : 10, shift_lo = LEVEL == 1 ? 10 : 0;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int32_t b = blockIdx.x * 4 + w;
-    if (b >= nb) return;
-    const uint32_t tau = sel->tau;
-    const uint32_t cnt = cand_cnt[b];
-    const float *seg = cand_val + (int64_t)b * blk;
-    uint32_t g = 0, q = 0;
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 512) {
-        float v[8];
+    // eight loads per lane are issued before any is used (unconditional, clamped addresses)
+    for (int32_t b = blockIdx.x * kSegsPerBlock + w; b < nb; b += groups * kSegsPerBlock) {
+        const Segment sg = segment_of(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt);
+        for (uint32_t i0 = 0; i0 < sg.cnt; i0 += 512) {
+            float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; u++) v[u] = seg[min(i0 + u * 64 + lane, cnt - 1)];
+            for (int u = 0; u < 8; u++) v[u] = sg.val[min(i0 + u * 64 + lane, sg.cnt - 1)];
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const uint32_t key = mag_key(v[u]);
-            const bool in = i0 + u * 64 + lane < cnt;
-            g += in && key > tau;
-            q += in && key == tau;
-        }
-    }
-    g = wave_sum_u32(g);
-    q = wave_sum_u32(q);
-    if (lane == 0) { cnt_gt[b] = g; cnt_eq[b] = q; }
-}
-
-// ------------------------------------------------------------------
-// One workgroup: exclusive scans over the candidate segments.
-//   eq_before[b] = number of keys == tau in segments before b
-//   sel_off[b]   = number of selected entries in segments before b
-// and the end of the new row's offset column, offT[n_slices][slot] = k; the other entries of
-// the column (offT[s][slot] = sel_off[s]: a segment is a slice) are strided single stores, which
-// the compaction kernel spreads over its waves.
-__global__ __launch_bounds__(1024) void k_scan_blocks(const uint32_t *__restrict__ cnt_gt,
-                                                      const uint32_t *__restrict__ cnt_eq,
-                                                      uint32_t *__restrict__ sel_off,
-                                                      uint32_t *__restrict__ eq_before,
-                                                      SelState *__restrict__ sel, int32_t nb,
-                                                      int32_t m, const StepState *__restrict__ step,
-                                                      int32_t *__restrict__ offT, uint32_t k,
-                                                      uint32_t *__restrict__ status)
-{
-    __shared__ uint32_t tmp[33];
-    const uint32_t quota = sel->quota;
-    uint32_t carry_eq = 0, carry_sel = 0;
-    for (int32_t tile = 0; tile < nb; tile += 4096) {
-        const int32_t b = tile + (int32_t)threadIdx.x * 4;
-        uint32_t ce[4] = {0, 0, 0, 0}, cg[4] = {0, 0, 0, 0};
-        if (b + 3 < nb) {
-            const uint4 t0 = *reinterpret_cast<const uint4 *>(cnt_eq + b);
-            const uint4 t1 = *reinterpret_cast<const uint4 *>(cnt_gt + b);
-            ce[0] = t0.x; ce[1] = t0.y; ce[2] = t0.z; ce[3] = t0.w;
-            cg[0] = t1.x; cg[1] = t1.y; cg[2] = t1.z; cg[3] = t1.w;
-        } else {
-            for (int i = 0; i < 4; i++)
-                if (b + i < nb) { ce[i] = cnt_eq[b + i]; cg[i] = cnt_gt[b + i]; }
-        }
-        uint32_t total_eq, total_sel;
-        uint32_t run = carry_eq + block_excl_scan_u32(ce[0] + ce[1] + ce[2] + ce[3], tmp, &total_eq);
-        uint32_t sc[4], eb[4];
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            eb[i] = run;
-            const uint32_t take = run >= quota ? 0u : min(quota - run, ce[i]);
-            sc[i] = cg[i] + take;
-            run += ce[i];
-        }
-        uint32_t run2 = carry_sel + block_excl_scan_u32(sc[0] + sc[1] + sc[2] + sc[3], tmp, &total_sel);
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if (b + i < nb) {
-                eq_before[b + i] = eb[i];
-                sel_off[b + i] = run2;           // k_cand_compact copies it into the offset table
+            for (int u = 0; u < 8; u++) {
+                const uint32_t kk = mag_key(v[u]);
+                if (i0 + u * 64 + lane < sg.cnt && (kk >> shift_hi) == prefix)
+                    atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
             }
-            run2 += sc[i];
         }
-        carry_eq += total_eq;
-        carry_sel += total_sel;
     }
+    __syncthreads();
+    const uint32_t c = lh[threadIdx.x];
+    if (c) atomicAdd(&hist_out[(blockIdx.x % kHist1Copies) * kBins2 + threadIdx.x], c);
+}
+
+// ------------------------------------------------------------------
+// Settles the last digit: tau, the tie quota, where the next step starts collecting candidates.
+// Then, per segment, how many keys are > tau and == tau, and the same per workgroup (its 16
+// segments), which is what the compaction's prefix sums start from.
+__global__ __launch_bounds__(1024) void k_cand_count(const float *__restrict__ e, int64_t d,
+                                                     const float *__restrict__ cand_val,
+                                                     const int32_t *__restrict__ cand_idx,
+                                                     const uint32_t *__restrict__ cand_cnt, int32_t nb,
+                                                     SelState *__restrict__ sel,
+                                                     const uint32_t *__restrict__ hist_prev,
+                                                     uint32_t *__restrict__ hist_clear, uint32_t k,
+                                                     uint32_t *__restrict__ cnt_gt,
+                                                     uint32_t *__restrict__ cnt_eq,
+                                                     uint32_t *__restrict__ blk_gt,
+                                                     uint32_t *__restrict__ blk_eq, int32_t blk)
+{
+    __shared__ uint32_t tmp[33], res[3];
+    __shared__ uint32_t s_g[kSegsPerBlock], s_q[kSegsPerBlock];
+    uint32_t bin, quota, top;
+    settle_digit<kBins2>(hist_prev, sel->kr2, tmp, res, bin, quota, top);
+    const uint32_t tau = (sel->p2 << 10) | bin;
+    const uint32_t redo = sel->redo;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sel->tau = tau;
+        sel->quota = quota;
+        sel->n_gt = k - quota;
+        const uint32_t tb = tau >> 20;                // next step collects from two bins below
+        sel->t_lo = (tb >= 2 ? tb - 2 : 0u) << 20;
+    }
+    clear_histogram(hist_clear, kHist1Copies * kBins2);
+
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int32_t b = blockIdx.x * kSegsPerBlock + w;
+    uint32_t g = 0, q = 0;
+    if (b < nb) {
+        const Segment sg = segment_of(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt);
+        for (uint32_t i0 = 0; i0 < sg.cnt; i0 += 512) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) v[u] = sg.val[min(i0 + u * 64 + lane, sg.cnt - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const uint32_t key = mag_key(v[u]);
+                const bool in = i0 + u * 64 + lane < sg.cnt;
+                g += in && key > tau;
+                q += in && key == tau;
+            }
+        }
+        g = wave_sum_u32(g);
+        q = wave_sum_u32(q);
+        if (lane == 0) { cnt_gt[b] = g; cnt_eq[b] = q; }
+    }
+    if (lane == 0) { s_g[w] = g; s_q[w] = q; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        offT[(int64_t)nb * m + step_view(step, m, kBefore).slot] = (int32_t)carry_sel;
-        sel->total = carry_sel;
-        if (carry_sel != k) atomicOr(status, kStatusCount);
+        uint32_t tg = 0, tq = 0;
+#pragma unroll
+        for (int i = 0; i < kSegsPerBlock; i++) { tg += s_g[i]; tq += s_q[i]; }
+        blk_gt[blockIdx.x] = tg;
+        blk_eq[blockIdx.x] = tq;
     }
 }
 
 // ------------------------------------------------------------------
-// Ordered compaction of the selected candidates of segment b into the ring
-// row (16-bit positions inside the segment = slice; fp32 or bfloat16 values).
-// The error buffer is left as it is: see the top of this file.
-// One wave per segment; candidates are already in index order.
+// Ordered compaction of the selected candidates of segment b into the ring row (16-bit
+// positions inside the segment = slice; fp32 or bfloat16 values), one wave per segment,
+// candidates already in index order.  Where a segment's entries go follows from the counts of
+// the pass before: the ties taken among the first E keys == tau (in index order) are
+// min(quota, E), so
+//   entries before segment b = (keys > tau before b) + min(quota, keys == tau before b),
+// with "before b" = the totals of the workgroups before this one plus the segments of this
+// workgroup before b.  The error buffer is left as it is: see the top of this file.
 template <int FMT>
-__global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__restrict__ cand_idx,
-                                                              const float *__restrict__ cand_val,
-                                                              const uint32_t *__restrict__ cand_cnt,
-                                                              int32_t nb,
-                                                              const SelState *__restrict__ sel,
-                                                              const uint32_t *__restrict__ sel_off,
-                                                              const uint32_t *__restrict__ eq_before,
-                                                              uint8_t *__restrict__ ring,
-                                                              int64_t row_bytes, int32_t blk,
-                                                              int32_t *__restrict__ offT, int32_t m,
-                                                              const StepState *__restrict__ step)
+__global__ __launch_bounds__(1024) void k_cand_compact(const float *__restrict__ e, int64_t d,
+                                                       const float *__restrict__ cand_val,
+                                                       const int32_t *__restrict__ cand_idx,
+                                                       const uint32_t *__restrict__ cand_cnt,
+                                                       int32_t nb, SelState *__restrict__ sel,
+                                                       const uint32_t *__restrict__ cnt_gt,
+                                                       const uint32_t *__restrict__ cnt_eq,
+                                                       const uint32_t *__restrict__ blk_gt,
+                                                       const uint32_t *__restrict__ blk_eq,
+                                                       uint32_t *__restrict__ hist_clear,
+                                                       uint8_t *__restrict__ ring, int64_t row_bytes,
+                                                       int32_t blk, int32_t *__restrict__ offT,
+                                                       int32_t m, const StepState *__restrict__ step,
+                                                       uint32_t k, uint32_t *__restrict__ status)
 {
+    __shared__ uint32_t s_part[2][16];
+    clear_histogram(hist_clear, kHist1Copies * kBins2);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int32_t b = blockIdx.x * 4 + w;
+    // totals of the workgroups before this one (fixed shape: integer sums, any order is exact)
+    uint32_t pg = 0, pq = 0;
+    for (int32_t j = threadIdx.x; j < (int32_t)blockIdx.x; j += 1024) {
+        pg += blk_gt[j];
+        pq += blk_eq[j];
+    }
+    pg = wave_sum_u32(pg);
+    pq = wave_sum_u32(pq);
+    if (lane == 0) { s_part[0][w] = pg; s_part[1][w] = pq; }
+    __syncthreads();
+    uint32_t gt_before = 0, eq_before = 0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) { gt_before += s_part[0][i]; eq_before += s_part[1][i]; }
+
+    const int32_t b = blockIdx.x * kSegsPerBlock + w;
     if (b >= nb) return;
+    for (int32_t i = blockIdx.x * kSegsPerBlock; i < b; i++) {      // segments of this workgroup before b
+        gt_before += cnt_gt[i];
+        eq_before += cnt_eq[i];
+    }
+    const uint32_t tau = sel->tau, quota = sel->quota;
     const int32_t slot = step_view(step, m, kBefore).slot;
     uint8_t *row = ring + (int64_t)slot * row_bytes;
-    const int32_t seg_first = b * blk;
-    const uint32_t tau = sel->tau, quota = sel->quota;
-    const uint32_t cnt = cand_cnt[b];
-    const int32_t *sidx = cand_idx + (int64_t)b * blk;
-    const float *sval = cand_val + (int64_t)b * blk;
-    uint32_t eq_run = eq_before[b];
-    uint32_t out_run = sel_off[b];
+    const Segment sg = segment_of(b, blk, d, sel->redo, e, cand_val, cand_idx, cand_cnt);
+    uint32_t eq_run = eq_before;
+    uint32_t out_run = gt_before + min(quota, eq_before);
     if (lane == 0) offT[(int64_t)b * m + slot] = (int32_t)out_run;     // where this slice's run starts
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 256) {
+    if (b == nb - 1 && lane == 0) {
+        // the end of the row: everything before the last segment plus the last segment's own share
+        const uint32_t eq_end = eq_before + cnt_eq[b];
+        const uint32_t total = gt_before + cnt_gt[b] + min(quota, eq_end);
+        offT[(int64_t)nb * m + slot] = (int32_t)total;
+        sel->total = total;
+        if (total != k) atomicOr(status, kStatusCount);
+    }
+    for (uint32_t i0 = 0; i0 < sg.cnt; i0 += 256) {
         float vv[4];
         int32_t jj[4];
 #pragma unroll
         for (int u = 0; u < 4; u++) {          // unconditional loads, clamped addresses
-            const uint32_t ic = min(i0 + u * 64 + lane, cnt - 1);
-            vv[u] = sval[ic];
-            jj[u] = sidx[ic];
+            const uint32_t ic = min(i0 + u * 64 + lane, sg.cnt - 1);
+            vv[u] = sg.val[ic];
+            jj[u] = sg.idx ? sg.idx[ic] - sg.first : (int32_t)ic;     // position inside the slice
         }
 #pragma unroll
         for (int u = 0; u < 4; u++) {
-            const bool in = i0 + u * 64 + lane < cnt;
+            const bool in = i0 + u * 64 + lane < sg.cnt;
             const float v = vv[u];
-            const int32_t j = jj[u];
             const uint32_t key = mag_key(v);
             const bool is_eq = in && key == tau;
             const uint64_t eq_mask = __ballot(is_eq);
@@ -502,7 +546,7 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
             const uint64_t take_mask = __ballot(take);
             if (take) {
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
-                *entry_idx_ptr<FMT>(row, pos) = (uint16_t)(j - seg_first);     // position inside the slice
+                *entry_idx_ptr<FMT>(row, pos) = (uint16_t)jj[u];
                 if constexpr (FMT == kFmtF32) *entry_val_ptr<FMT>(row, pos) = v;
                 else *entry_val_ptr<FMT>(row, pos) = (uint16_t)bf16_bits(v);
             }
@@ -517,11 +561,11 @@ __global__ __launch_bounds__(kSelThreads) void k_cand_compact(const int32_t *__r
 hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream)
 {
     if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL((k_ef_hist<false, 2>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
+        hipLaunchKernelGGL((k_ef_hist<2>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
                            g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, p.ring, g.row_bytes, p.offT,
                            g.m, g.slice, p.step);
     else
-        hipLaunchKernelGGL((k_ef_hist<false, 1>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
+        hipLaunchKernelGGL((k_ef_hist<1>), dim3(g.n_slices), dim3(kEfThreads), 0, stream, grad, p.e,
                            g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, p.ring, g.row_bytes, p.offT,
                            g.m, g.slice, p.step);
     return hipGetLastError();
@@ -530,39 +574,32 @@ hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *g
 hipError_t launch_select(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
     const int32_t nb = g.n_slices;
-    // one wave per candidate segment until every private histogram is in use
-    const int32_t groups = (nb + 15) / 16 < kHistGroups ? (nb + 15) / 16 : kHistGroups;
-    hipLaunchKernelGGL(k_pick_digit<kBins1>, dim3(1), dim3(1024), 0, stream, p.hist1, p.sel, 0,
-                       (uint32_t)g.k, p.rowmax, g.m, p.step);
-    hipLaunchKernelGGL((k_ef_hist<true, 0>), dim3(nb), dim3(kEfThreads), 0, stream, (const float *)nullptr,
-                       p.e, g.d, p.hist1, p.sel, p.cand_idx, p.cand_val, p.cand_cnt, p.ring, g.row_bytes,
-                       p.offT, g.m, g.slice, p.step);
-    hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
-                       p.sel, p.hist2, 20, 10, g.slice, groups);
-    hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist2, p.sel, 1,
-                       (uint32_t)g.k, p.rowmax, g.m, p.step);
-    hipLaunchKernelGGL(k_cand_hist, dim3(groups), dim3(1024), 0, stream, p.cand_val, p.cand_cnt, nb,
-                       p.sel, p.hist3, 10, 0, g.slice, groups);
-    hipLaunchKernelGGL(k_pick_digit<kBins2>, dim3(1), dim3(1024), 0, stream, p.hist3, p.sel, 2,
-                       (uint32_t)g.k, p.rowmax, g.m, p.step);
-    hipLaunchKernelGGL(k_cand_count, dim3((nb + 3) / 4), dim3(kSelThreads), 0, stream, p.cand_val,
-                       p.cand_cnt, nb, p.sel, p.cnt_gt, p.cnt_eq, g.slice);
-    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, stream, p.cnt_gt, p.cnt_eq, p.sel_off,
-                       p.eq_before, p.sel, nb, g.m, p.step, p.offT,
-                       (uint32_t)g.k, p.status);
+    const int32_t nblk = (nb + kSegsPerBlock - 1) / kSegsPerBlock;
+    // one wave per candidate segment until every workgroup of a histogram pass is in use
+    const int32_t groups = nblk < kHistGroups ? nblk : kHistGroups;
+    hipLaunchKernelGGL(k_cand_hist<1>, dim3(groups), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
+                       p.cand_cnt, nb, p.sel, p.hist1, p.hist2, (uint32_t *)nullptr, (uint32_t)g.k, g.slice,
+                       groups, p.rowmax, g.m, p.step);
+    hipLaunchKernelGGL(k_cand_hist<2>, dim3(groups), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
+                       p.cand_cnt, nb, p.sel, p.hist2, p.hist3, p.hist1, (uint32_t)g.k, g.slice, groups,
+                       p.rowmax, g.m, p.step);
+    hipLaunchKernelGGL(k_cand_count, dim3(nblk), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
+                       p.cand_cnt, nb, p.sel, p.hist3, p.hist2, (uint32_t)g.k, p.cnt_gt, p.cnt_eq, p.blk_gt,
+                       p.blk_eq, g.slice);
     return hipGetLastError();
 }
 
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
+    const int32_t nblk = (g.n_slices + kSegsPerBlock - 1) / kSegsPerBlock;
     if (g.fmt == kFmtBf16)
-        hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
-                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
-                           p.eq_before, p.ring, g.row_bytes, g.slice, p.offT, g.m, p.step);
+        hipLaunchKernelGGL(k_cand_compact<kFmtBf16>, dim3(nblk), dim3(1024), 0, stream, p.e, g.d, p.cand_val,
+                           p.cand_idx, p.cand_cnt, g.n_slices, p.sel, p.cnt_gt, p.cnt_eq, p.blk_gt, p.blk_eq,
+                           p.hist3, p.ring, g.row_bytes, g.slice, p.offT, g.m, p.step, (uint32_t)g.k, p.status);
     else
-        hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3((g.n_slices + 3) / 4), dim3(kSelThreads), 0,
-                           stream, p.cand_idx, p.cand_val, p.cand_cnt, g.n_slices, p.sel, p.sel_off,
-                           p.eq_before, p.ring, g.row_bytes, g.slice, p.offT, g.m, p.step);
+        hipLaunchKernelGGL(k_cand_compact<kFmtF32>, dim3(nblk), dim3(1024), 0, stream, p.e, g.d, p.cand_val,
+                           p.cand_idx, p.cand_cnt, g.n_slices, p.sel, p.cnt_gt, p.cnt_eq, p.blk_gt, p.blk_eq,
+                           p.hist3, p.ring, g.row_bytes, g.slice, p.offT, g.m, p.step, (uint32_t)g.k, p.status);
     return hipGetLastError();
 }
 
