@@ -170,12 +170,17 @@ __global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, const StepS
     if (row >= m) return;
     double az = 0.0, aw = 0.0;
     if (row != slot) {
+        // all loads of the row are issued at once (m <= 1024: at most 16 per lane); a column
+        // past the end is read again from the last one and meets an exact zero in s_sq
         const double *wr = W + (int64_t)row * ldm;
-        for (int j = lane; j < m; j += 64) {
-            const double v = wr[j];
-            const double2 t = s_sq[j];
-            aw = fma(v, t.x, aw);
-            az = fma(v, t.y, az);
+        double v[kMaxM / 64];
+#pragma unroll
+        for (int u = 0; u < kMaxM / 64; u++) v[u] = wr[min(lane + 64 * u, m - 1)];
+#pragma unroll
+        for (int u = 0; u < kMaxM / 64; u++) {
+            const double2 t = s_sq[lane + 64 * u];
+            aw = fma(v[u], t.x, aw);
+            az = fma(v[u], t.y, az);
         }
     }
     az = wave_sum_f64(az);
@@ -228,11 +233,18 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const Step
     const int col = blockIdx.x * kBwdCols + cl;
     const int colc = min(col, m - 1);
     double ac = 0.0, ay = 0.0;
-    // row `slot` needs no skip: s_r[slot] = s_z[slot] = 0 and the row holds finite values
-    for (int i = rg; i < m; i += 64) {
-        const double v = W[(int64_t)i * ldm + colc];
-        ac = fma(v, s_r[i], ac);
-        ay = fma(v, s_z[i], ay);
+    // row `slot` needs no skip: s_r[slot] = s_z[slot] = 0 and the row holds finite values; rows
+    // past the end are read again from the last one and meet exact zeros.  All 16 loads of a
+    // thread are issued at once.
+    {
+        double v[kMaxM / 64];
+#pragma unroll
+        for (int u = 0; u < kMaxM / 64; u++) v[u] = W[(int64_t)min(rg + 64 * u, m - 1) * ldm + colc];
+#pragma unroll
+        for (int u = 0; u < kMaxM / 64; u++) {
+            ac = fma(v[u], s_r[rg + 64 * u], ac);
+            ay = fma(v[u], s_z[rg + 64 * u], ay);
+        }
     }
     red[rg][cl] = make_double2(ac, ay);
     __syncthreads();

@@ -327,6 +327,68 @@ __device__ __forceinline__ void clear_histogram(uint32_t *__restrict__ hist, int
     for (int i = blockIdx.x * 1024 + threadIdx.x; i < words; i += gridDim.x * 1024) hist[i] = 0;
 }
 
+// The passes are a handful of dependent memory round trips long, so each one asks for
+// everything it can before it knows anything: a wave requests the size and the first 512 values
+// of its (first) candidate segment together with the histogram of the previous digit, and only
+// then settles that digit.  The candidate buffer of a segment is as long as the slice (at least
+// 256 entries), so a read clamped to the slice is in bounds whatever the segment holds; entries
+// past its size are masked afterwards.  (The accumulator fallback cannot use the early read
+// and starts over from `e`.)
+struct FirstBatch {
+    float v[8];
+    uint32_t cnt;
+};
+
+__device__ __forceinline__ void request_first_batch(int32_t b, int32_t nb, int32_t blk,
+                                                    const float *__restrict__ cand_val,
+                                                    const uint32_t *__restrict__ cand_cnt, int lane,
+                                                    FirstBatch &fb)
+{
+    const int32_t bc = min(b, nb - 1);
+    fb.cnt = cand_cnt[bc];
+    const float *seg = cand_val + (int64_t)bc * blk;
+#pragma unroll
+    for (int u = 0; u < 8; u++) fb.v[u] = seg[min(u * 64 + lane, blk - 1)];
+    if (b >= nb) fb.cnt = 0;
+}
+
+// f(key, exists) for the entries [i_begin, cnt) of a segment, 512 at a time: eight loads per lane
+// are issued before any is used (unconditional, clamped addresses).
+template <class F>
+__device__ __forceinline__ void for_each_key(const Segment &sg, int lane, uint32_t i_begin, F f)
+{
+    for (uint32_t i0 = i_begin; i0 < sg.cnt; i0 += 512) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = sg.val[min(i0 + u * 64 + lane, sg.cnt - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; u++) f(mag_key(v[u]), i0 + u * 64 + lane < sg.cnt);
+    }
+}
+
+// Segment b through f: the early read first if it is usable.
+template <class F>
+__device__ __forceinline__ void first_segment(int32_t b, int32_t blk, int64_t d, uint32_t redo,
+                                              const float *__restrict__ e,
+                                              const float *__restrict__ cand_val,
+                                              const int32_t *__restrict__ cand_idx,
+                                              const uint32_t *__restrict__ cand_cnt,
+                                              const FirstBatch &fb, int lane, F f)
+{
+    if (redo) {
+        for_each_key(segment_of(b, blk, d, 1u, e, cand_val, cand_idx, cand_cnt), lane, 0u, f);
+        return;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; u++) f(mag_key(fb.v[u]), (uint32_t)(u * 64 + lane) < fb.cnt);
+    Segment sg;
+    sg.first = (int32_t)((int64_t)b * blk);
+    sg.val = cand_val + (int64_t)b * blk;
+    sg.idx = cand_idx + (int64_t)b * blk;
+    sg.cnt = fb.cnt;
+    for_each_key(sg, lane, 512u, f);
+}
+
 // LEVEL 1: digit 1 is settled from hist_prev (2048 bins) and the histogram of digit 2 is built;
 // LEVEL 2: digit 2 is settled from hist_prev (1024 bins), histogram of digit 3; `hist_clear`
 // (the histogram the previous pass read) is zeroed.
@@ -349,14 +411,19 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
 {
     __shared__ uint32_t lh[kBins2];
     __shared__ uint32_t tmp[33], res[3];
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    int32_t b = blockIdx.x * kSegsPerBlock + w;
+    FirstBatch fb;
+    request_first_batch(b, nb, blk, cand_val, cand_cnt, lane, fb);
     lh[threadIdx.x] = 0;
     uint32_t prefix, redo;
     if (LEVEL == 1) {
+        const uint32_t t_lo = sel->t_lo;
         uint32_t bin, kr1, top;
         settle_digit<kBins1>(hist_prev, k, tmp, res, bin, kr1, top);
         prefix = bin;
         // candidates hold every key >= t_lo: enough iff the threshold bin starts at or above t_lo
-        redo = (bin << 20) < sel->t_lo ? 1u : 0u;
+        redo = (bin << 20) < t_lo ? 1u : 0u;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             sel->p1 = bin;
             sel->kr1 = kr1;
@@ -367,10 +434,11 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
             rowmax[step_view(step, m, kBefore).slot] = edge < 0x7f7fffffu ? edge : 0x7f7fffffu;
         }
     } else {
-        uint32_t bin, kr2, top;
-        settle_digit<kBins2>(hist_prev, sel->kr1, tmp, res, bin, kr2, top);
-        prefix = (sel->p1 << 10) | bin;
+        const uint32_t kr1 = sel->kr1, p1 = sel->p1;
         redo = sel->redo;
+        uint32_t bin, kr2, top;
+        settle_digit<kBins2>(hist_prev, kr1, tmp, res, bin, kr2, top);
+        prefix = (p1 << 10) | bin;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             sel->p2 = prefix;
             sel->kr2 = kr2;
@@ -378,21 +446,13 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
         clear_histogram(hist_clear, kHist1Copies * kBins1);
     }
     constexpr int shift_hi = LEVEL == 1 ? 20 : 10, shift_lo = LEVEL == 1 ? 10 : 0;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    // eight loads per lane are issued before any is used (unconditional, clamped addresses)
-    for (int32_t b = blockIdx.x * kSegsPerBlock + w; b < nb; b += groups * kSegsPerBlock) {
-        const Segment sg = segment_of(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt);
-        for (uint32_t i0 = 0; i0 < sg.cnt; i0 += 512) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; u++) v[u] = sg.val[min(i0 + u * 64 + lane, sg.cnt - 1)];
-#pragma unroll
-            for (int u = 0; u < 8; u++) {
-                const uint32_t kk = mag_key(v[u]);
-                if (i0 + u * 64 + lane < sg.cnt && (kk >> shift_hi) == prefix)
-                    atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
-            }
-        }
+    auto count_key = [&](uint32_t kk, bool exists) {
+        if (exists && (kk >> shift_hi) == prefix) atomicAdd(&lh[(kk >> shift_lo) & (kBins2 - 1)], 1u);
+    };
+    if (b < nb) {
+        first_segment(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt, fb, lane, count_key);
+        for (b += groups * kSegsPerBlock; b < nb; b += groups * kSegsPerBlock)
+            for_each_key(segment_of(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt), lane, 0u, count_key);
     }
     __syncthreads();
     const uint32_t c = lh[threadIdx.x];
@@ -417,10 +477,14 @@ __global__ __launch_bounds__(1024) void k_cand_count(const float *__restrict__ e
 {
     __shared__ uint32_t tmp[33], res[3];
     __shared__ uint32_t s_g[kSegsPerBlock], s_q[kSegsPerBlock];
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int32_t b = blockIdx.x * kSegsPerBlock + w;
+    FirstBatch fb;
+    request_first_batch(b, nb, blk, cand_val, cand_cnt, lane, fb);
+    const uint32_t kr2 = sel->kr2, p2 = sel->p2, redo = sel->redo;
     uint32_t bin, quota, top;
-    settle_digit<kBins2>(hist_prev, sel->kr2, tmp, res, bin, quota, top);
-    const uint32_t tau = (sel->p2 << 10) | bin;
-    const uint32_t redo = sel->redo;
+    settle_digit<kBins2>(hist_prev, kr2, tmp, res, bin, quota, top);
+    const uint32_t tau = (p2 << 10) | bin;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         sel->tau = tau;
         sel->quota = quota;
@@ -430,23 +494,13 @@ __global__ __launch_bounds__(1024) void k_cand_count(const float *__restrict__ e
     }
     clear_histogram(hist_clear, kHist1Copies * kBins2);
 
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int32_t b = blockIdx.x * kSegsPerBlock + w;
     uint32_t g = 0, q = 0;
     if (b < nb) {
-        const Segment sg = segment_of(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt);
-        for (uint32_t i0 = 0; i0 < sg.cnt; i0 += 512) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; u++) v[u] = sg.val[min(i0 + u * 64 + lane, sg.cnt - 1)];
-#pragma unroll
-            for (int u = 0; u < 8; u++) {
-                const uint32_t key = mag_key(v[u]);
-                const bool in = i0 + u * 64 + lane < sg.cnt;
-                g += in && key > tau;
-                q += in && key == tau;
-            }
-        }
+        first_segment(b, blk, d, redo, e, cand_val, cand_idx, cand_cnt, fb, lane,
+                      [&](uint32_t key, bool exists) {
+                          g += exists && key > tau;
+                          q += exists && key == tau;
+                      });
         g = wave_sum_u32(g);
         q = wave_sum_u32(q);
         if (lane == 0) { cnt_gt[b] = g; cnt_eq[b] = q; }
@@ -488,55 +542,65 @@ __global__ __launch_bounds__(1024) void k_cand_compact(const float *__restrict__
                                                        uint32_t k, uint32_t *__restrict__ status)
 {
     __shared__ uint32_t s_part[2][16];
-    clear_histogram(hist_clear, kHist1Copies * kBins2);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    // totals of the workgroups before this one (fixed shape: integer sums, any order is exact)
+    const int32_t b0 = blockIdx.x * kSegsPerBlock, b = b0 + w;
+    // everything this wave will need is requested first: the segment's size and its first 256
+    // entries, the counts of the workgroup's segments, the totals of the workgroups before it
+    const int32_t bc = min(b, nb - 1);
+    const uint32_t cnt_early = cand_cnt[bc];
+    float v0[4];
+    int32_t j0[4];
+    {
+        const float *sv = cand_val + (int64_t)bc * blk;
+        const int32_t *si = cand_idx + (int64_t)bc * blk;
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int32_t ic = min(u * 64 + lane, blk - 1);
+            v0[u] = sv[ic];
+            j0[u] = si[ic];
+        }
+    }
+    const int32_t bl = min(b0 + (lane & 15), nb - 1);
+    uint32_t cg = cnt_gt[bl], ce = cnt_eq[bl];
+    const uint32_t tau = sel->tau, quota = sel->quota, redo = sel->redo;
     uint32_t pg = 0, pq = 0;
     for (int32_t j = threadIdx.x; j < (int32_t)blockIdx.x; j += 1024) {
         pg += blk_gt[j];
         pq += blk_eq[j];
     }
+    clear_histogram(hist_clear, kHist1Copies * kBins2);
+    // totals of the workgroups before this one (integer sums: exact in any order)
     pg = wave_sum_u32(pg);
     pq = wave_sum_u32(pq);
     if (lane == 0) { s_part[0][w] = pg; s_part[1][w] = pq; }
     __syncthreads();
+    if (b >= nb) return;
     uint32_t gt_before = 0, eq_before = 0;
 #pragma unroll
     for (int i = 0; i < 16; i++) { gt_before += s_part[0][i]; eq_before += s_part[1][i]; }
+    // the segments of this workgroup before b, and b's own counts
+    const bool earlier = lane < w && b0 + lane < nb;
+    const uint32_t own_g = __shfl(cg, w, 64), own_q = __shfl(ce, w, 64);
+    gt_before += wave_sum_u32(earlier ? cg : 0u);
+    eq_before += wave_sum_u32(earlier ? ce : 0u);
 
-    const int32_t b = blockIdx.x * kSegsPerBlock + w;
-    if (b >= nb) return;
-    for (int32_t i = blockIdx.x * kSegsPerBlock; i < b; i++) {      // segments of this workgroup before b
-        gt_before += cnt_gt[i];
-        eq_before += cnt_eq[i];
-    }
-    const uint32_t tau = sel->tau, quota = sel->quota;
     const int32_t slot = step_view(step, m, kBefore).slot;
     uint8_t *row = ring + (int64_t)slot * row_bytes;
-    const Segment sg = segment_of(b, blk, d, sel->redo, e, cand_val, cand_idx, cand_cnt);
     uint32_t eq_run = eq_before;
     uint32_t out_run = gt_before + min(quota, eq_before);
     if (lane == 0) offT[(int64_t)b * m + slot] = (int32_t)out_run;     // where this slice's run starts
     if (b == nb - 1 && lane == 0) {
         // the end of the row: everything before the last segment plus the last segment's own share
-        const uint32_t eq_end = eq_before + cnt_eq[b];
-        const uint32_t total = gt_before + cnt_gt[b] + min(quota, eq_end);
+        const uint32_t total = gt_before + own_g + min(quota, eq_before + own_q);
         offT[(int64_t)nb * m + slot] = (int32_t)total;
         sel->total = total;
         if (total != k) atomicOr(status, kStatusCount);
     }
-    for (uint32_t i0 = 0; i0 < sg.cnt; i0 += 256) {
-        float vv[4];
-        int32_t jj[4];
-#pragma unroll
-        for (int u = 0; u < 4; u++) {          // unconditional loads, clamped addresses
-            const uint32_t ic = min(i0 + u * 64 + lane, sg.cnt - 1);
-            vv[u] = sg.val[ic];
-            jj[u] = sg.idx ? sg.idx[ic] - sg.first : (int32_t)ic;     // position inside the slice
-        }
+    // 256 entries: which are taken, and where they go
+    auto place = [&](const float (&vv)[4], const int32_t (&pp)[4], uint32_t i0, uint32_t cnt) {
 #pragma unroll
         for (int u = 0; u < 4; u++) {
-            const bool in = i0 + u * 64 + lane < sg.cnt;
+            const bool in = i0 + u * 64 + lane < cnt;
             const float v = vv[u];
             const uint32_t key = mag_key(v);
             const bool is_eq = in && key == tau;
@@ -546,13 +610,39 @@ __global__ __launch_bounds__(1024) void k_cand_compact(const float *__restrict__
             const uint64_t take_mask = __ballot(take);
             if (take) {
                 const uint32_t pos = out_run + __popcll(take_mask & ((1ull << lane) - 1ull));
-                *entry_idx_ptr<FMT>(row, pos) = (uint16_t)jj[u];
+                *entry_idx_ptr<FMT>(row, pos) = (uint16_t)pp[u];                   // position inside the slice
                 if constexpr (FMT == kFmtF32) *entry_val_ptr<FMT>(row, pos) = v;
                 else *entry_val_ptr<FMT>(row, pos) = (uint16_t)bf16_bits(v);
             }
             eq_run += __popcll(eq_mask);
             out_run += __popcll(take_mask);
         }
+    };
+    Segment sg;
+    uint32_t i_begin = 0;
+    if (redo) {
+        sg = segment_of(b, blk, d, 1u, e, cand_val, cand_idx, cand_cnt);
+    } else {
+        sg.first = (int32_t)((int64_t)b * blk);
+        sg.val = cand_val + (int64_t)b * blk;
+        sg.idx = cand_idx + (int64_t)b * blk;
+        sg.cnt = cnt_early;
+        int32_t p0[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) p0[u] = j0[u] - sg.first;
+        place(v0, p0, 0u, sg.cnt);
+        i_begin = 256;
+    }
+    for (uint32_t i0 = i_begin; i0 < sg.cnt; i0 += 256) {
+        float vv[4];
+        int32_t pp[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {          // unconditional loads, clamped addresses
+            const uint32_t ic = min(i0 + u * 64 + lane, sg.cnt - 1);
+            vv[u] = sg.val[ic];
+            pp[u] = sg.idx ? sg.idx[ic] - sg.first : (int32_t)ic;
+        }
+        place(vv, pp, i0, sg.cnt);
     }
 }
 

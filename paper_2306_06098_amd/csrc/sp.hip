@@ -289,10 +289,15 @@ __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ 
     const int32_t r = blockIdx.x * 64 + rl;
     double ax = 0.0, ay = 0.0;
     if (r < m) {
-        for (int32_t b = bl; b < nwg; b += 16) {
-            const double2 t = partial[(int64_t)b * m + r];
-            ax += t.x;
-            ay += t.y;
+        // at most kMaxWgs / 16 = 16 partial sums per thread, all requested at once
+        double2 t[kMaxWgs / 16];
+#pragma unroll
+        for (int u = 0; u < kMaxWgs / 16; u++) t[u] = partial[(int64_t)min(bl + 16 * u, nwg - 1) * m + r];
+#pragma unroll
+        for (int u = 0; u < kMaxWgs / 16; u++) {
+            const bool in = bl + 16 * u < nwg;
+            ax += in ? t[u].x : 0.0;
+            ay += in ? t[u].y : 0.0;
         }
     }
     sh[bl][rl] = make_double2(ax, ay);
