@@ -172,6 +172,9 @@ def main():
                     help="eager: every step is an efcp_step call (its kernel launches); graph: one step per "
                          "resident gradient buffer is captured into a HIP graph once (no kernel argument of a "
                          "step depends on the step number) and the timed steps are replays of those graphs")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="efcp_options.single_stream: the eviction update on the step's own stream, no second "
+                         "queue (for counter collection with rocprofv3 --pmc)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -191,10 +194,11 @@ def main():
     if args.topk == "block":
         kb = -(-binding.TOPK_BLOCK * wl.k // wl.d)
         ctx = binding.Efcp(wl.d, wl.m, kb, wl.lam, values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32,
-                           topk_block=binding.TOPK_BLOCK, ggt=ggt)
+                           topk_block=binding.TOPK_BLOCK, ggt=ggt, single_stream=args.single_stream)
     else:
         ctx = binding.Efcp(wl.d, wl.m, wl.k, wl.lam,
-                           values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32, ggt=ggt)
+                           values=binding.VALUES_BF16 if bf16 else binding.VALUES_FP32, ggt=ggt,
+                           single_stream=args.single_stream)
     k_row = ctx.k
     stream = synth.TorchGradientStream(wl.d, wl.rho, wl.seed, dev)
     out = torch.empty(wl.d, dtype=torch.float32, device=dev)
@@ -305,7 +309,8 @@ def main():
                    "window_format": ("bf16 value" if bf16 else "fp32 value") + " + 16-bit in-slice index "
                                     "(int32 indices at the interface)",
                    "mode": args.mode, "topk": args.topk,
-                   "preconditioner": args.precond, "launch": args.launch},
+                   "preconditioner": args.precond, "launch": args.launch,
+                   "single_stream": bool(args.single_stream)},
         "step_ms": stats,
         "step_bytes": by["total"],
         "achieved_GBps": by["total"] / (ms_med * 1e-3) / 1e9,

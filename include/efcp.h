@@ -118,7 +118,8 @@ size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_f
 
 /* The general constructor: everything the calls above choose, as one structure, plus the
  * d-slice width.  opts == NULL means all zeros (fp32 values, global Top-k, Sparse M-FAC,
- * automatic width); the calls above are this one with slice_width = 0. */
+ * automatic width, second stream used); the calls above are this one with slice_width = 0 and
+ * single_stream = 0. */
 typedef enum { EFCP_SPARSE_MFAC = 0, EFCP_SPARSE_GGT = 1 } efcp_preconditioner;
 typedef struct efcp_options {
     int32_t value_format;    /* efcp_value_format */
@@ -133,6 +134,13 @@ typedef struct efcp_options {
                                 depend on the width; S, q, coef and with them F^-1 x do in the last bits
                                 (order of the fp64 sums).  A state exported under one width is refused by
                                 a context created under another. */
+    int32_t single_stream;   /* 0: the update of the coefficient factor that a full window needs on every
+                                step (deleting the oldest row) runs on a stream of the library's own, beside
+                                the step's first passes, forked from and joined to the caller's stream with
+                                events.  1: it runs on the caller's stream, in front of them: no second
+                                stream, no events; a step then takes that update's time longer.  Results are
+                                bit for bit the same.  For tools that want one queue (counter collection
+                                with rocprofv3 --pmc, for one) and for callers who keep their own overlap. */
 } efcp_options;
 int efcp_create_opts(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double damping,
                      const efcp_options *opts, void *workspace, size_t workspace_bytes);

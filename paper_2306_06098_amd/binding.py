@@ -36,7 +36,8 @@ _lib = None
 class Options(ctypes.Structure):
     """struct efcp_options."""
     _fields_ = [("value_format", ctypes.c_int32), ("topk_block", ctypes.c_int32),
-                ("preconditioner", ctypes.c_int32), ("slice_width", ctypes.c_int32)]
+                ("preconditioner", ctypes.c_int32), ("slice_width", ctypes.c_int32),
+                ("single_stream", ctypes.c_int32)]
 
 
 class EfcpError(RuntimeError):
@@ -117,7 +118,7 @@ TOPK_BLOCK = 16384      # EFCP_TOPK_BLOCK
 
 def efcp_workspace_bytes(d: int, m: int, k: int, values: int = VALUES_FP32, topk_block: int = 0,
                          ggt: bool = False, slice_width: int = 0) -> int:
-    o = Options(values, topk_block, 1 if ggt else 0, slice_width)
+    o = Options(values, topk_block, 1 if ggt else 0, slice_width, 0)
     return int(load_library().efcp_workspace_bytes_opts(d, m, k, ctypes.byref(o)))
 
 
@@ -125,12 +126,13 @@ class Efcp:
     """One libefcp context: efcp_create / efcp_step / efcp_destroy."""
 
     def __init__(self, d: int, m: int, k: int, lam: float, workspace=None, values: int = VALUES_FP32,
-                 topk_block: int = 0, ggt: bool = False, slice_width: int = 0):
+                 topk_block: int = 0, ggt: bool = False, slice_width: int = 0, single_stream: bool = False):
         """topk_block = 0: global Top-k of k entries; TOPK_BLOCK: Top-k applied in
         blocks of that many coordinates, k entries per block (self.k is then the
         resulting row length, self.k_arg what was passed).  ggt: Sparse GGT
         (EFCP_SPARSE_GGT), `lam` is then its epsilon and m <= 128.  slice_width: coordinates
-        per d-slice, 0 = chosen by the library (efcp_options)."""
+        per d-slice, 0 = chosen by the library (efcp_options).  single_stream: no internal
+        second stream (efcp_options.single_stream)."""
         self._lib = load_library()
         self.d, self.m, self.lam = int(d), int(m), float(lam)
         self.k_arg, self.topk_block = int(k), int(topk_block)
@@ -141,7 +143,7 @@ class Efcp:
         ws_ptr, ws_bytes = None, 0
         if workspace is not None:
             ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-        opts = Options(self.values, self.topk_block, 1 if ggt else 0, int(slice_width))
+        opts = Options(self.values, self.topk_block, 1 if ggt else 0, int(slice_width), 1 if single_stream else 0)
         rc = self._lib.efcp_create_opts(ctypes.byref(self._ctx), self.d, self.m, self.k_arg, self.lam,
                                         ctypes.byref(opts), ws_ptr, ws_bytes)
         if rc != EFCP_OK:

@@ -221,6 +221,7 @@ struct efcp_ctx {
     // (p.step) and are advanced by the step's kernels; host code reads them only in the
     // inspection calls, after synchronising.
     bool broken;                     // a launch failed part-way: the state is undefined
+    bool single_stream;              // the eviction update runs on the caller's stream (no fork)
     hipStream_t last_stream;
     // The eviction update of the inverse factor depends on the previous step only; it runs on
     // this stream next to the d-sized passes of the step and is joined before k_fwd.
@@ -256,6 +257,7 @@ static efcp_options options_of(int32_t value_format, int32_t topk_block, int32_t
     o.topk_block = topk_block;
     o.preconditioner = preconditioner;
     o.slice_width = 0;
+    o.single_stream = 0;
     return o;
 }
 
@@ -346,6 +348,7 @@ extern "C" int efcp_create_opts(efcp_ctx **out, int64_t d, int32_t m, int64_t k,
     ctx->g = g;
     ctx->lambda = lambda;
     ctx->broken = false;
+    ctx->single_stream = o.single_stream != 0;
     ctx->last_stream = nullptr;
     ctx->err = "no error";
     ctx->prof_on = false;
@@ -411,7 +414,7 @@ extern "C" int efcp_create_opts(efcp_ctx **out, int64_t d, int32_t m, int64_t k,
     if (rc == hipSuccess) rc = hipMemcpy(p.step, &first_state, sizeof first_state, hipMemcpyHostToDevice);
     ctx->side = nullptr;
     ctx->ev_fork = ctx->ev_join = nullptr;
-    if (rc == hipSuccess) rc = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+    if (rc == hipSuccess && !ctx->single_stream) rc = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
     if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (rc == hipSuccess) rc = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
     ctx->static_scratch = nullptr;
@@ -478,7 +481,11 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     hipError_t rc = hipSuccess;
     auto mark = [&](int i) { if (ev && rc == hipSuccess) rc = hipEventRecord(ev[i], stream); };
 
-    if (factor) {       // fork: delete the oldest row from the inverse factor while the d-sized passes run
+    const bool fork = factor && !ctx->single_stream;
+    if (factor && !fork) {
+        if (rc == hipSuccess) rc = launch_evict(g, p, stream);
+    }
+    if (fork) {         // delete the oldest row from the inverse factor while the d-sized passes run
         if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_fork, stream);
         if (rc == hipSuccess) rc = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
         if (rc == hipSuccess) rc = launch_evict(g, p, ctx->side);      // returns at once until the window is full
@@ -500,7 +507,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     if (rc == hipSuccess) rc = launch_sp(g, p, grad, x_is_row ? 1 : 0, stream);
     mark(4);
     // join before the reduction: it counts the step, and the eviction kernel reads the old count
-    if (factor && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);
+    if (fork && rc == hipSuccess) rc = hipStreamWaitEvent(stream, ctx->ev_join, 0);
     if (rc == hipSuccess) rc = launch_sp_reduce(g, p, true, stream);
     if (rc == hipSuccess)
         rc = g.ggt ? launch_ggt_step(g, p, ctx->lambda, stream) : launch_coef(g, p, ctx->lambda, stream);
@@ -592,7 +599,7 @@ extern "C" int efcp_destroy(efcp_ctx *ctx)
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
-    (void)hipStreamDestroy(ctx->side);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->own_ws && hipFree(ctx->ws) != hipSuccess) rcode = EFCP_EHIP;
     if (cur != ctx->device) (void)hipSetDevice(cur);
     delete ctx;

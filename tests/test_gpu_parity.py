@@ -773,6 +773,30 @@ def test_step_and_apply_under_hip_graph_capture(env):
             b.destroy()
 
 
+def test_single_stream_option_gives_the_same_bits(env):
+    """efcp_options.single_stream = 1 runs the eviction update on the caller's stream instead
+    of the library's second stream: same kernels, other order of launches, identical results
+    through the fill of the window and on into evicting steps."""
+    torch, _, binding = env
+    d, m, k, lam = 90_001, 6, 700, 1e-3
+    a = binding.Efcp(d, m, k, lam)
+    b = binding.Efcp(d, m, k, lam, single_stream=True)
+    s = synth.GradientStream(d, 0.9, 8)
+    g = torch.empty(d, dtype=torch.float32, device="cuda:0")
+    oa, ob = torch.empty_like(g), torch.empty_like(g)
+    for t in range(1, m + 9):
+        g.copy_(torch.from_numpy(s.next()))
+        a.step(g, oa)
+        b.step(g, ob)
+        torch.cuda.synchronize()
+        assert torch.equal(oa, ob), f"step {t}"
+        sa, sb = a.get_small(), b.get_small()
+        assert all(np.array_equal(sa[key], sb[key]) for key in ("S", "q", "coef"))
+    assert np.array_equal(bits(a.get_error()), bits(b.get_error()))
+    a.destroy()
+    b.destroy()
+
+
 @pytest.mark.parametrize("kw", [dict(), dict(values=1), dict(topk_block=16_384, k=40),
                                 dict(compressed=True), dict(update=True), dict(ggt=True, values=1)])
 def test_one_captured_step_replays_as_every_later_step(env, kw):
