@@ -211,12 +211,15 @@ def test_forced_ties_integer_gradients(env):
 
 def test_threshold_jumps_between_steps(env):
     """The candidate filter of the first pass is seeded by the previous step's
-    threshold.  Make the threshold collapse by orders of magnitude (the
-    candidates must be rebuilt), stay put, and jump up again; with k < d and
+    threshold.  Make the threshold collapse by orders of magnitude (the later
+    passes then read the accumulator instead of the candidate lists), stay put, and jump up again; with k < d and
     with k = d (no residual left in e)."""
     torch, oracle_mod, binding = env
     rng = np.random.default_rng(77)
-    for d, m, k in ((60_000, 6, 600), (20_000, 4, 20_000)):
+    # the last shape: 245 slices, i.e. 16 workgroups of 16 segments in the passes that fall back to
+    # the accumulator, a ragged last slice, and the bfloat16 window
+    for d, m, k, bf16 in ((60_000, 6, 600, False), (20_000, 4, 20_000, False), (1_000_003, 5, 10_000, False),
+                          (1_000_003, 5, 10_000, True)):
         base = rng.standard_normal(d).astype(np.float32)
         probe = oracle_mod.Oracle(d, m, k, 1e-2)
         probe.step(base)
@@ -229,8 +232,8 @@ def test_threshold_jumps_between_steps(env):
                  (50.0 * noise[3]).astype(np.float32),              # jumps up
                  (1e-2 * noise[4]).astype(np.float32),
                  noise[5], (3e-3 * noise[6]).astype(np.float32), noise[7]]
-        w = run_parity(torch, oracle_mod, binding, d, m, k, 1e-2, grads)
-        print("jumps", (d, m, k), w)
+        w = run_parity(torch, oracle_mod, binding, d, m, k, 1e-2, grads, bf16=bf16)
+        print("jumps", (d, m, k, bf16), w)
 
 
 def test_degenerate_vectors(env):
