@@ -776,6 +776,45 @@ def test_step_and_apply_under_hip_graph_capture(env):
             b.destroy()
 
 
+def test_two_contexts_on_two_streams_do_not_share_state(env):
+    """Two contexts of different shapes (and slice widths) stepping at the same time on two streams,
+    no synchronisation in between: each must leave exactly what a twin leaves that ran alone.
+    (Nothing in the library is process-wide except the scratch array of efcp_apply_noalloc.)"""
+    torch, _, binding = env
+    dev = torch.device("cuda:0")
+    shapes = [dict(d=180_001, m=7, k=1_500, lam=1e-3), dict(d=50_000, m=4, k=900, lam=1e-2, slice_width=512)]
+    T = 14
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    grads = [[torch.randn(sh["d"], device=dev, generator=gen) * torch.exp(torch.randn(sh["d"], device=dev, generator=gen))
+              for _ in range(T)] for sh in shapes]
+    torch.cuda.synchronize()
+
+    def run(concurrent):
+        ctxs = [binding.Efcp(sh["d"], sh["m"], sh["k"], sh["lam"], slice_width=sh.get("slice_width", 0)) for sh in shapes]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        outs = [[torch.empty(sh["d"], device=dev) for _ in range(T)] for sh in shapes]
+        if concurrent:
+            for t in range(T):
+                for i in (0, 1):
+                    ctxs[i].step(grads[i][t], outs[i][t], stream=streams[i])
+        else:
+            for i in (0, 1):
+                for t in range(T):
+                    ctxs[i].step(grads[i][t], outs[i][t], stream=streams[i])
+                streams[i].synchronize()
+        torch.cuda.synchronize()
+        res = [(torch.stack(outs[i]).cpu().numpy(), ctxs[i].get_error(), ctxs[i].get_small()) for i in (0, 1)]
+        for c in ctxs:
+            c.destroy()
+        return res
+    alone, together = run(False), run(True)
+    for (oa, ea, sa), (ob, eb, sb) in zip(alone, together):
+        assert np.array_equal(bits(oa), bits(ob))
+        assert np.array_equal(bits(ea), bits(eb))
+        assert sa["step"] == sb["step"] == T and np.array_equal(sa["S"], sb["S"]) and np.array_equal(sa["coef"], sb["coef"])
+
+
 def test_single_stream_option_gives_the_same_bits(env):
     """efcp_options.single_stream = 1 runs the eviction update on the caller's stream instead
     of the library's second stream: same kernels, other order of launches, identical results
