@@ -28,8 +28,9 @@ Prints one JSON line:
                         figure for this kernel and configuration)
   device_copy_GBps      a plain torch device copy of d floats on the same box (bytes read + written / time):
                         what a simple streaming kernel reaches here, for context
-  cpu_baseline          the CPU oracle timed on this host: one measured step at the full d from the
-                        empty state, and the full-window step scaled up from a d/100 sample (`sample`)
+  cpu_baseline          the CPU oracle timed on this host at the full d: one measured step from the empty
+                        state, the measured cost of one more window row, the coefficient recursion alone;
+                        `value` = the full-window step put together from them (`sample` says how)
 """
 from __future__ import annotations
 
@@ -94,20 +95,21 @@ def step_time_stats(ms):
     return {"median": med, "min": v[0], "max": v[-1], "mean": sum(v) / n, "n": n}
 
 
-def cpu_baseline(wl, bf16=False):
-    """The oracle as it stands (one thread), on this host, two bounded legs:
-    (1) measured at the full size: one step at the workload's d from the empty state (window of
-        one row afterwards) -- the sort of d pairs and the d-sized passes at their real size;
-    (2) the full-window step the headline is quoted on, from a sample: d/100 with all m rows
-        preloaded with seeded random sparse rows, a few steps of the workload's own gradient
-        recipe.  Every cost of a step is linear in d except the O(m^3) coefficient recursion,
-        which is timed on its own (on the sample's Gram matrix) and counted once, not 100 times.
-    `value` is leg (2) in the metric's unit."""
+def cpu_baseline(wl, bf16=False, rows=32):
+    """The oracle as it stands (one thread) on this host, every piece timed at the workload's
+    full d, bounded to about half a minute:
+      T1    one full step from the empty state: error feedback, the sort of d pairs, one row
+      r     what one more window row costs a step: its share of the Gram row (the time of loading
+            a row into a window of `rows` rows, per row) and of q and the LCG sum (apply() on
+            `rows` rows minus apply() on one row, per row)
+      c     the O(m^3) coefficient recursion on an m x m Gram matrix, timed alone
+    The step with the full m-row window, which is what `value` stands for, is T1 + (m-1)*r + c:
+    every cost of a step is linear in the number of rows except the recursion."""
     import numpy as np
     import oracle
     from paper_2306_06098_amd import synth
     oracle.build()
-    # leg 1
+    rows = max(1, min(rows, wl.m))
     s = synth.GradientStream(wl.d, wl.rho, wl.seed)
     g = s.next()
     del s
@@ -115,37 +117,46 @@ def cpu_baseline(wl, bf16=False):
     t0 = time.perf_counter()
     o.step(g)
     t_first = time.perf_counter() - t0
+
+    def t_apply():
+        best = float("inf")
+        for _ in range(2):
+            t0 = time.perf_counter()
+            o.apply(g)
+            best = min(best, time.perf_counter() - t0)
+        return best
+    a1 = t_apply()
+    rng = np.random.default_rng(1234)
+    t_load = 0.0
+    for _ in range(rows - 1):
+        row = synth.random_sparse_row(wl.d, wl.k, rng)
+        t0 = time.perf_counter()
+        o.load_row(*row)
+        t_load = time.perf_counter() - t0          # the last one: Gram products with `rows` rows
+    an = t_apply() if rows > 1 else a1
     o.close()
     del o, g
-    # leg 2
-    scale = 100
-    d, k = wl.d // scale, wl.k // scale
-    o = oracle.Oracle(d, wl.m, k, wl.lam, values_bf16=bf16)
-    rng = np.random.default_rng(1234)
-    for _ in range(wl.m):
-        o.load_row(*synth.random_sparse_row(d, k, rng))
-    s = synth.GradientStream(d, wl.rho, wl.seed)
-    gs = [s.next() for _ in range(3)]
+    gram_row = t_load / rows
+    ql_row = max(an - a1, 0.0) / max(rows - 1, 1)
+    B = rng.standard_normal((wl.m, 48))
+    S = B @ B.T + np.eye(wl.m)
     t0 = time.perf_counter()
-    for g in gs:
-        o.step(g)
-    t_sample = (time.perf_counter() - t0) / len(gs)
-    S, q = o.gram.copy(), o.q.copy()
-    t0 = time.perf_counter()
-    oracle.coefficients(S, q, wl.m, wl.lam)
+    oracle.coefficients(S, rng.standard_normal(wl.m), wl.m, wl.lam)
     t_coef = time.perf_counter() - t0
-    o.close()
-    t_full = max(t_sample - t_coef, 0.0) * scale + t_coef
+    t_full = t_first + (wl.m - 1) * (gram_row + ql_row) + t_coef
     return {
         "value": 1.0 / t_full, "unit": "steps/s", "cores": 1, "host_cores": os.cpu_count(), "kind": "oracle",
-        "seconds_per_step_full_window_scaled": t_full,
+        "seconds_per_step_full_window": t_full,
         "seconds_per_step_first_step_measured": t_first,
-        "sample": (f"(1) measured: 1 oracle step at the full d={wl.d:,}, k={wl.k:,} from the empty state: "
-                   f"{t_first:.2f} s. (2) value: full-window step (m={wl.m} rows) scaled from {len(gs)} oracle "
-                   f"steps at d={d:,}, k={k:,} (1/{scale} of the workload) on a window preloaded with seeded "
-                   f"random sparse rows: {t_sample:.3f} s/step, of which the O(m^3) coefficient recursion "
-                   f"(timed alone) {t_coef:.3f} s; ({t_sample:.3f} - {t_coef:.3f}) * {scale} + {t_coef:.3f} "
-                   f"= {t_full:.2f} s/step. One thread of {os.cpu_count()} host cores."),
+        "seconds_per_window_row": gram_row + ql_row,
+        "seconds_coefficient_recursion": t_coef,
+        "sample": (f"all at the full d={wl.d:,}, k={wl.k:,}: one oracle step from the empty state {t_first:.2f} s "
+                   f"(measured); one more window row costs {gram_row + ql_row:.4f} s (Gram row: loading a row into a "
+                   f"window of {rows} rows, per row {gram_row:.4f} s; q and LCG: apply() on {rows} rows minus apply() "
+                   f"on 1 row, per row {ql_row:.4f} s); the O(m^3) coefficient recursion for m={wl.m}, alone, "
+                   f"{t_coef:.3f} s. value = 1 / ({t_first:.2f} + {wl.m - 1} * {gram_row + ql_row:.4f} + {t_coef:.3f}) "
+                   f"= 1 / {t_full:.1f} s: the step with the full {wl.m}-row window. One thread of {os.cpu_count()} "
+                   "host cores."),
     }
 
 

@@ -65,6 +65,9 @@ def test_cpu_baseline_reports_host_cores_and_both_legs():
     cb = bench.cpu_baseline(wl)
     assert cb["kind"] == "oracle" and cb["unit"] == "steps/s" and cb["cores"] == 1
     assert cb["host_cores"] == os.cpu_count()
-    assert cb["value"] > 0 and abs(cb["value"] * cb["seconds_per_step_full_window_scaled"] - 1) < 1e-9
+    assert cb["value"] > 0 and abs(cb["value"] * cb["seconds_per_step_full_window"] - 1) < 1e-9
     assert cb["seconds_per_step_first_step_measured"] > 0
-    assert "measured" in cb["sample"] and "scaled" in cb["sample"]
+    t = cb["seconds_per_step_first_step_measured"] + (wl.m - 1) * cb["seconds_per_window_row"] \
+        + cb["seconds_coefficient_recursion"]
+    assert abs(t - cb["seconds_per_step_full_window"]) < 1e-9
+    assert "measured" in cb["sample"] and "full" in cb["sample"]
