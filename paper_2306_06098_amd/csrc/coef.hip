@@ -160,22 +160,25 @@ __global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, const StepS
                                              const double2 *__restrict__ sq,
                                              double2 *__restrict__ zw)
 {
-    const int32_t slot = whole ? -1 : step_view(step, m, kAfter).slot;
     __shared__ double2 s_sq[kMaxM];
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // The row of W is requested first, before anything is known about the step: all its loads at
+    // once (m <= 1024: at most 16 per lane); a column past the end is read again from the last
+    // one and meets an exact zero in s_sq, a row past the end is the last row and is dropped.
+    double v[kMaxM / 64];
+    {
+        const double *wr = W + (int64_t)min(row, m - 1) * ldm;
+#pragma unroll
+        for (int u = 0; u < kMaxM / 64; u++) v[u] = wr[min(lane + 64 * u, m - 1)];
+    }
+    const int32_t slot = whole ? -1 : step_view(step, m, kAfter).slot;
     for (int j = threadIdx.x; j < kMaxM; j += 256)
         s_sq[j] = (j < m && j != slot) ? sq[j] : make_double2(0.0, 0.0);
     __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (row >= m) return;
     double az = 0.0, aw = 0.0;
     if (row != slot) {
-        // all loads of the row are issued at once (m <= 1024: at most 16 per lane); a column
-        // past the end is read again from the last one and meets an exact zero in s_sq
-        const double *wr = W + (int64_t)row * ldm;
-        double v[kMaxM / 64];
-#pragma unroll
-        for (int u = 0; u < kMaxM / 64; u++) v[u] = wr[min(lane + 64 * u, m - 1)];
 #pragma unroll
         for (int u = 0; u < kMaxM / 64; u++) {
             const double2 t = s_sq[lane + 64 * u];
@@ -205,8 +208,16 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const Step
     __shared__ double buf[16];
     __shared__ double2 red[64][kBwdCols];
 
-    const int32_t slot = step_view(step, m, kAfter).slot;         // the slot written by this step
     const int tid = threadIdx.x;
+    const int cl = tid & (kBwdCols - 1), rg = tid >> 4;          // 16 columns x 64 row groups
+    const int col = blockIdx.x * kBwdCols + cl;
+    const int colc = min(col, m - 1);
+    // This thread's 16 entries of W are requested first (they depend on nothing): rows past the
+    // end are read again from the last one and meet exact zeros below.
+    double wv[kMaxM / 64];
+#pragma unroll
+    for (int u = 0; u < kMaxM / 64; u++) wv[u] = W[(int64_t)min(rg + 64 * u, m - 1) * ldm + colc];
+    const int32_t slot = step_view(step, m, kAfter).slot;         // the slot written by this step
     double z = 0.0, w = 0.0;
     if (tid < m && tid != slot) {
         const double2 t = zw[tid];
@@ -229,22 +240,12 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const Step
     s_r[tid] = (tid < m && tid != slot) ? (w - z * f) : 0.0;
     __syncthreads();
 
-    const int cl = tid & (kBwdCols - 1), rg = tid >> 4;          // 16 columns x 64 row groups
-    const int col = blockIdx.x * kBwdCols + cl;
-    const int colc = min(col, m - 1);
     double ac = 0.0, ay = 0.0;
-    // row `slot` needs no skip: s_r[slot] = s_z[slot] = 0 and the row holds finite values; rows
-    // past the end are read again from the last one and meet exact zeros.  All 16 loads of a
-    // thread are issued at once.
-    {
-        double v[kMaxM / 64];
+    // row `slot` needs no skip: s_r[slot] = s_z[slot] = 0 and the row holds finite values
 #pragma unroll
-        for (int u = 0; u < kMaxM / 64; u++) v[u] = W[(int64_t)min(rg + 64 * u, m - 1) * ldm + colc];
-#pragma unroll
-        for (int u = 0; u < kMaxM / 64; u++) {
-            ac = fma(v[u], s_r[rg + 64 * u], ac);
-            ay = fma(v[u], s_z[rg + 64 * u], ay);
-        }
+    for (int u = 0; u < kMaxM / 64; u++) {
+        ac = fma(wv[u], s_r[rg + 64 * u], ac);
+        ay = fma(wv[u], s_z[rg + 64 * u], ay);
     }
     red[rg][cl] = make_double2(ac, ay);
     __syncthreads();
