@@ -76,3 +76,19 @@ def test_row_length_arithmetic_matches_the_oracle(oracle_mod):
     assert lib.efcp_step_ex(None, None, 0, None, None, 0.0, 0.0, None) == binding.EFCP_EINVAL
     assert lib.efcp_apply(None, None, None, None) == binding.EFCP_EINVAL
     assert lib.efcp_state_bytes(None) == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/efcp.h is a C header: it must compile as C99 and as C++11 with nothing but itself."""
+    import shutil
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "efcp.h"\nint main(void) { efcp_options o = {0, 0, 0, 0, 0}; (void)o; '
+                   'return efcp_destroy(0) == EFCP_OK ? 0 : 1; }\n')
+    inc = os.path.join(ROOT, "include")
+    if shutil.which("gcc"):
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", inc, str(src)], check=True)
+    if shutil.which("g++"):
+        subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-x", "c++", "-I", inc, str(src)], check=True)
