@@ -128,7 +128,7 @@ typedef struct efcp_options {
     int32_t slice_width;     /* Coordinates per d-slice (the LDS tile of the SP and LCG kernels and the
                                 block of the Top-k passes).  0: chosen from d so that the persistent
                                 SP / LCG workgroups all get the same number of slices.  Otherwise a
-                                multiple of 256 in [256, 16384]; a width too small for d (more than 512
+                                multiple of 64 in [256, 16384]; a width too small for d (more than 512
                                 slices per workgroup) is EFCP_EINVAL.  Ignored with Top-k in blocks,
                                 where the slice is the block.  The Top-k, the stored rows and e do not
                                 depend on the width; S, q, coef and with them F^-1 x do in the last bits
@@ -271,7 +271,7 @@ int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes);
 
 /* Geometry chosen at creation; any pointer may be NULL.
  *   slice      coordinates per d-slice staged in LDS by the SP and LCG kernels
- *              (a multiple of 256, at most 16384)
+ *              (a multiple of 64, at most 16384)
  *   n_slices   ceil(d / slice)
  *   row_stride entries between consecutive rows of I and V (k rounded up) */
 int efcp_get_geometry(efcp_ctx *ctx, int32_t *slice, int32_t *n_slices, int64_t *row_stride);

@@ -31,13 +31,16 @@ int64_t block_row_length(int64_t d, int64_t kb)
 // Width of the d-slices that the SP and LCG workgroups stage in LDS, which are also the blocks of
 // the Top-k passes.  With Top-k in blocks it is the block.  Otherwise: the widest slice leaves
 // the persistent workgroups with unequal numbers of slices (684 slices of 16,384 over 256
-// workgroups: three rounds, the last one two thirds empty; 1,288 slices: six rounds, the last one
-// with 8 slices), which costs up to 1/rounds of the SP and LCG passes.  When the rounds would hold
-// at least 4 % more slices than there are, the vector is therefore cut into a multiple of
-// kMaxWgs nearly equal slices: the fewest rounds that the LDS allows, every workgroup in every
-// round; short vectors get narrow slices by the same rule, all workgroups take part.  Below 4 %
-// the widest slice stays: the first Top-k pass pays a fixed cost per block (measured at
-// d = 110M, 2.9 %: SP 1.5 % faster, that pass 5 % slower with 16,128-wide blocks, no net gain).
+// workgroups: three rounds, the last one two thirds empty; 6,714 slices: 26 rounds and 58 slices),
+// and a last round costs the SP and the LCG pass almost a whole round however little it holds
+// (measured at d = 110M: 40 and 44 us of the 47 and 55 us of a full one).  When the rounds would
+// hold at least 2 % more slices than there are, the vector is therefore cut into nearly equal
+// slices, a multiple of 64 coordinates each, as narrow as the same number of rounds allows, so that
+// every workgroup takes part in every round (d = 110M: 6,903 slices of 15,936 = 27 rounds, 9 places
+// empty: SP 1.243 -> 1.216 ms, LCG 1.356 -> 1.344, the first Top-k pass, which pays a fixed cost
+// per block, 0.258 -> 0.261).  Below 2 % the widest slice stays (d = 340M, 1.1 %: equal slices
+// measured 0.4 % slower overall).  A vector short enough for a single round gets a multiple of
+// 256 (more, narrower slices only add workgroups there), at least kMinSlice coordinates.
 // No result depends on the width except the order of the fp64 sums of the SP pass.
 // forced: the width asked for in efcp_options (0 = choose as described).
 int32_t pick_slice_width(int64_t d, int32_t kb, int32_t forced)
@@ -46,9 +49,10 @@ int32_t pick_slice_width(int64_t d, int32_t kb, int32_t forced)
     if (forced) return forced;
     const int64_t widest = (d + kCandBlock - 1) / kCandBlock;
     const int64_t rounds = (widest + kMaxWgs - 1) / kMaxWgs;
-    if ((rounds * kMaxWgs - widest) * 25 < widest) return kCandBlock;
+    if ((rounds * kMaxWgs - widest) * 50 < rounds * kMaxWgs) return kCandBlock;
+    const int64_t unit = rounds == 1 ? 256 : 64;
     int64_t w = (d + kMaxWgs * rounds - 1) / (kMaxWgs * rounds);
-    w = (w + 255) / 256 * 256;
+    w = (w + unit - 1) / unit * unit;
     if (w < kMinSlice) w = kMinSlice;
     if (w > kCandBlock) w = kCandBlock;
     return (int32_t)w;
@@ -60,8 +64,8 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
 {
     g.ggt = ggt ? 1 : 0;
     if (ggt != 0 && ggt != 1) { *why = "unknown preconditioner"; return false; }
-    if (slice_width != 0 && (slice_width < 256 || slice_width > kCandBlock || slice_width % 256 != 0)) {
-        *why = "slice_width must be 0 or a multiple of 256 in [256, 16384]";
+    if (slice_width != 0 && (slice_width < 256 || slice_width > kCandBlock || slice_width % 64 != 0)) {
+        *why = "slice_width must be 0 or a multiple of 64 in [256, 16384]";
         return false;
     }
     if (ggt && m > kGgtMaxM) { *why = "Sparse GGT: m out of range [1, 128]"; return false; }

@@ -15,7 +15,7 @@
 //                                        index is >= s*slice (slice-major so one
 //                                        workgroup reads its m offsets contiguously).
 //                                        slice = Geometry::slice coordinates, a multiple of
-//                                        256 and at most 16,384, fixed when the context is made
+//                                        64 and at most 16,384, fixed when the context is made
 //   S         double [m][m]              Gram matrix by slot
 //   W         double [m rows][ldm]       inverse of the Cholesky factor of
 //                                        m*lambda*I + S (rows in age order), stored
@@ -196,7 +196,7 @@ struct Geometry {
     int32_t ggt;             // 0: Sparse M-FAC coefficients; 1: Sparse GGT
     int32_t m, ldm;
     int32_t fmt;             // kFmtF32 / kFmtBf16
-    int32_t slice, n_slices; // coordinates per d-slice (multiple of 256, <= kCandBlock), number of slices
+    int32_t slice, n_slices; // coordinates per d-slice (multiple of 64, <= kCandBlock), number of slices
     int32_t sp_grid;         // persistent SP workgroups: 8 * (workgroups per XCD)
     size_t lds_sp, lds_lcg;
 };

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const int32_t r_last = max(n_filled, 1) - 1;      // rows past the end repeat this one
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
-    // `slice` coordinates (a multiple of 256, at most kCandBlock) are live; the LDS layout is that
+    // `slice` coordinates (a multiple of 64, at most kCandBlock) are live; the LDS layout is that
     // of the widest slice
     unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem);   // [kCandBlock]
     double *cf = reinterpret_cast<double *>(acc + kCandBlock);                // [1024]
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
                                      UPDATE ? th[u].w : 0.f};
 #pragma unroll
                 for (int q = 0; q < 4; q++) o[q] = result(xv[q], tv[q], acc[i + q]);
-                if (i < slice)                // the same for all lanes of a wave
+                if (i < slice)                // whole 16-byte pieces: the slice is a multiple of 4
                     store_stream_f4(out + base64 + i, make_float4(o[0], o[1], o[2], o[3]));
             } else {
 #pragma unroll

@@ -31,7 +31,7 @@
 namespace efcp {
 
 // Streaming layout of a d-sized pass: a block owns one d-slice (`blk`
-// consecutive coordinates, a multiple of 256 and at most 16,384), walked in
+// consecutive coordinates, a multiple of 64 and at most 16,384), walked in
 // chunks of 8,192 by 512 threads (measured against 256 and 1024 threads per
 // block: 0.252 / 0.250 / 0.291 ms at d = 110M); inside a chunk wave w
 // owns 1,024 consecutive coordinates and lane l holds, for it = 0..3, the four
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
         const int64_t wave_first = block_first + cch * kEfChunk + w * 1024;
         const int64_t wave_base = wave_first + lane * 4;
         // Lanes hold whole 16-byte pieces wherever the wave's part of the block ends on a multiple
-        // of 256 coordinates (always, except in the last block of a vector of ragged length):
-        // nit of the wave's four 256-coordinate pieces exist.
+        // of 4 coordinates (always, except in the last block of a vector of ragged length): of a
+        // lane's four pieces, 256 coordinates apart, the first nit exist.
         const int64_t rem = block_end - wave_first;        // scalar
         float a[4][4];
         uint32_t inmask;                                   // bit it*4+c: the coordinate exists
@@ -165,8 +165,9 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
         if (rem >= 1024) {
             vector_pieces(4);
             inmask = 0xffffu;
-        } else if (rem <= 0 || (rem & 255) == 0) {
-            const int nit = rem <= 0 ? 0 : (int)(rem >> 8);
+        } else if (rem <= 0 || (rem & 3) == 0) {
+            const int left = (int)rem - lane * 4;              // coordinates from this lane's first piece on
+            const int nit = left <= 0 ? 0 : (left + 255) >> 8;
             vector_pieces(nit);
             inmask = (1u << (4 * nit)) - 1u;
         } else {

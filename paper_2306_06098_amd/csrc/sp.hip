@@ -91,7 +91,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     using val_t = typename Fmt<FMT>::val_t;
     constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
     extern __shared__ __align__(16) unsigned char smem[];
-    // `slice` coordinates (a multiple of 256, at most kCandBlock) are live; the LDS layout is that
+    // `slice` coordinates (a multiple of 64, at most kCandBlock) are live; the LDS layout is that
     // of the widest slice
     float2 *xc = reinterpret_cast<float2 *>(smem);       // [kCandBlock]: (x_j, c_new_j); [kCandBlock] = (0, 0)
     double2 *racc = reinterpret_cast<double2 *>(xc + kCandBlock + 2);   // [1024] per-row sums

@@ -87,12 +87,13 @@ def test_shapes_and_edges(env, d, m, k, lam, T, bf16):
     print((d, m, k, bf16), w)
 
 
-@pytest.mark.parametrize("width", [256, 1024, 4352, 12_544, 16_384])
+@pytest.mark.parametrize("width", [256, 1024, 4352, 12_544, 15_936, 16_384])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_slice_widths(env, width, bf16):
     """The d-slice width is an option of the context (efcp_options.slice_width): slices of 256 up to 16,384
-    coordinates, widths that end in the middle of a wave's part of a block and in the middle of a
-    4,096-coordinate chunk, d not a multiple of any of them; every variant of the step."""
+    coordinates, widths that end in the middle of a wave's part of a block, in the middle of a
+    4,096-coordinate chunk and (15,936) in the middle of a wave's 256-coordinate piece, d not a
+    multiple of any of them; every variant of the step."""
     torch, oracle_mod, binding = env
     d, m, k, lam, T = 150_011, 6, 1_500, 1e-3, 14
     rng = np.random.default_rng(width)
@@ -116,13 +117,13 @@ def test_slice_widths(env, width, bf16):
 
 def test_slice_width_is_chosen_from_d(env):
     """Automatic width: short vectors are cut into (up to) 256 slices of at least 1,024
-    coordinates; longer ones into a multiple of 256 equal slices when rounds of 256 widest
-    slices would be at least 4 % empty, else into widest slices; Top-k in blocks keeps the
-    block."""
+    coordinates (a multiple of 256); longer ones into nearly equal slices (a multiple of 64) that
+    fill every round of 256 workgroups when rounds of widest slices would be at least 2 % empty,
+    else into widest slices; Top-k in blocks keeps the block."""
     torch, oracle_mod, binding = env
     for d, kw, want in [(5_000, {}, 1024), (272_474, {}, 1280), (11_200_000, {}, 14_592),
-                        (4_194_304, {}, 16_384), (4_194_305, {}, 8_448),
-                        (21_100_000, {}, 13_824), (110_000_000, {}, 16_384),
+                        (4_194_304, {}, 16_384), (4_194_305, {}, 8_256),
+                        (21_100_000, {}, 13_760), (110_000_000, {}, 15_936), (340_000_000, {}, 16_384),
                         (272_474, dict(topk_block=binding.TOPK_BLOCK), 16_384)]:
         g = binding.Efcp(d, 2, 3, 1e-3, **kw)
         geo = g.geometry()
@@ -405,7 +406,7 @@ def test_argument_checks(env):
         with pytest.raises(binding.EfcpError) as ei:
             binding.Efcp(*bad)
         assert ei.value.code == binding.EFCP_EINVAL
-    for width in (-256, 1, 128, 255, 1000, 16_640, 32_768):         # not a multiple of 256 in [256, 16384]
+    for width in (-256, 1, 128, 255, 1000, 16_640, 32_768):         # not a multiple of 64 in [256, 16384]
         with pytest.raises(binding.EfcpError) as ei:
             binding.Efcp(100_000, 4, 10, 1e-3, slice_width=width)
         assert ei.value.code == binding.EFCP_EINVAL
