@@ -112,7 +112,7 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
 }
 
 size_t value_bytes(const Geometry &g) { return g.fmt == kFmtBf16 ? 2 : 4; }
-int group_entries(const Geometry &g) { return g.fmt == kFmtBf16 ? 8 : 4; }
+int group_entries(const Geometry &) { return 4; }
 // Bytes of a row that hold its k entries (whole groups).
 size_t row_payload_bytes(const Geometry &g)
 {
@@ -733,7 +733,7 @@ extern "C" int efcp_get_small(efcp_ctx *ctx, double *S_host, double *q_host, dou
 namespace {
 
 struct StateHeader {
-    uint64_t magic;          // "EFCPST04"
+    uint64_t magic;          // "EFCPST05"
     int64_t d, k, row_stride, t;
     int32_t m, ldm, slice, n_slices;
     double lambda;
@@ -741,7 +741,7 @@ struct StateHeader {
     int32_t filled, fmt;
     int32_t kb, ggt;
 };
-constexpr uint64_t kStateMagic = 0x3430545350434645ull;
+constexpr uint64_t kStateMagic = 0x3530545350434645ull;
 
 size_t state_bytes(const efcp_ctx *ctx, int64_t t_done)
 {

@@ -65,8 +65,11 @@ template <> struct Fmt<kFmtF32> {
 template <> struct Fmt<kFmtBf16> {
     using idx_t = uint16_t;
     using val_t = uint16_t;
-    using iraw_t = int4;     // 8 x uint16
-    static constexpr int EPL = 8, kChunk = 128, kBatch = 2, kEntryBytes = 4;
+    using iraw_t = int2;     // 4 x uint16
+    // A group is 4 entries = 16 bytes: one load per lane and chunk.  (Groups of 8, two 16-byte
+    // loads per lane, left 36 % of the lanes idle on the ~164-entry runs of a 1 % window: a run
+    // then needs two 128-entry chunks, and these passes are bound by vector-ALU work.)
+    static constexpr int EPL = 4, kChunk = 64, kBatch = 3, kEntryBytes = 4;
 };
 
 // Entry p of a row lives in group p / EPL: [EPL x uint16 index][EPL x value].
@@ -92,12 +95,14 @@ template <int FMT>
 __device__ __forceinline__ void load_group(const uint8_t *row, uint32_t p, typename Fmt<FMT>::iraw_t &iv, int4 &vv)
 {
     const uint8_t *g = row + (uint64_t)p * Fmt<FMT>::kEntryBytes;
-    iv = *reinterpret_cast<const typename Fmt<FMT>::iraw_t *>(g);
     if constexpr (FMT == kFmtF32) {
+        iv = *reinterpret_cast<const int2 *>(g);
         // 16 bytes at an 8-byte boundary: the compiler picks the widest load the target allows
         __builtin_memcpy(&vv, __builtin_assume_aligned(g + 8, 8), 16);
     } else {
-        vv = *reinterpret_cast<const int4 *>(g + 16);
+        const int4 t = *reinterpret_cast<const int4 *>(g);       // indices and values of the group at once
+        iv = make_int2(t.x, t.y);
+        vv = make_int4(t.z, t.w, 0, 0);
     }
 }
 
@@ -105,13 +110,8 @@ __device__ __forceinline__ void load_group(const uint8_t *row, uint32_t p, typen
 template <int FMT>
 __device__ __forceinline__ int32_t entry_pos(const typename Fmt<FMT>::iraw_t &raw, int c, int32_t mask)
 {
-    if constexpr (FMT == kFmtF32) {
-        const int32_t w[2] = {raw.x, raw.y};
-        return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
-    } else {
-        const int32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-        return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
-    }
+    const int32_t w[2] = {raw.x, raw.y};
+    return (int32_t)(((uint32_t)w[c >> 1] >> ((c & 1) * 16)) & 0xffffu) & mask;
 }
 
 template <int FMT>
