@@ -287,3 +287,28 @@ def test_step_without_output_leaves_the_state_of_a_full_step(oracle_mod, bf16, b
             assert np.array_equal(ia, ib) and np.array_equal(va.view(np.uint32), vb.view(np.uint32))
     C = _dense_rows(b)
     assert _rel(yb, _dense_solve(C, m, lam, g)) < 1e-9
+
+
+def test_step_against_dense_inversion_property_search(oracle_mod):
+    """hypothesis varies shape, window size, density, damping, the number of steps and the
+    gradient values (small integers: repeated and zero entries, ties in the selection, identical
+    consecutive rows); after every step y must be F^-1 g for F = lambda*I + (1/m) sum c_r c_r^T
+    built densely from the rows the oracle holds."""
+    hypothesis = pytest.importorskip("hypothesis")
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(st.integers(1, 40), st.integers(1, 6), st.floats(0.02, 1.0), st.sampled_from([1e-3, 1e-1, 1.0]),
+           st.integers(1, 12), st.integers(0, 2 ** 31 - 1))
+    def check(d, m, density, lam, T, seed):
+        k = max(1, min(d, int(round(density * d))))
+        rng = np.random.default_rng(seed)
+        o = oracle_mod.Oracle(d, m, k, lam)
+        for _ in range(T):
+            g = rng.integers(-3, 4, size=d).astype(np.float32)
+            y = o.step(g)
+            C = _dense_rows(o)
+            ref = _dense_solve(C, m, lam, g)
+            assert np.linalg.norm(y - ref) <= 1e-9 * max(np.linalg.norm(ref), 1e-30)
+        o.close()
+    check()

@@ -282,3 +282,28 @@ def test_blockwise_differs_from_global_when_mass_is_concentrated(oracle_mod):
     assert list(idx[:kb]) == [0, 1, 2, 3]
     assert np.array_equal(idx[kb:], np.concatenate([np.arange(B * b, B * b + kb) for b in (1, 2, 3)]))
     assert np.array_equal(o.error[4:16], g[4:16])
+
+
+def test_topk_property_search(oracle_mod):
+    """hypothesis searches for a vector on which eo_topk is not the k largest magnitudes with ties
+    to the lower index: the selected set must be exactly what repeated arg-max picks, whatever
+    mix of ties, signed zeros, subnormals, huge values and lengths it comes up with."""
+    hypothesis = pytest.importorskip("hypothesis")
+    from hypothesis import given, settings, strategies as st
+    pool = [0.0, -0.0, 1.0, -1.0, 1.5, -1.5, 2.0, 1e-45, -1e-45, 1e-38, 3e38, -3e38, 0.1, -0.1, 7.0]
+    vec = st.lists(st.one_of(st.sampled_from(pool), st.floats(width=32, allow_nan=False, allow_infinity=False)),
+                   min_size=1, max_size=96)
+
+    @settings(max_examples=300, deadline=None)
+    @given(vec, st.data())
+    def check(values, data):
+        a = np.array(values, dtype=np.float32)
+        k = data.draw(st.integers(1, a.size))
+        idx, val = oracle_mod.topk(a, k)
+        assert np.array_equal(idx, _brute_topk(a, k))
+        assert np.array_equal(val.view(np.uint32), a[idx].view(np.uint32))
+        key = _key(a)
+        rest = np.setdiff1d(np.arange(a.size), idx)
+        if rest.size:
+            assert key[idx].min() >= key[rest].max()
+    check()
