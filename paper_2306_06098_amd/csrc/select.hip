@@ -8,7 +8,7 @@
 //
 // Only the first pass touches the whole vector.  While it forms a = e + g and
 // the histogram of the first digit, it also copies every element whose key is
-// at least t_lo -- a bin edge two bins below the previous step's threshold --
+// at least t_lo -- the lower edge of the bin below the previous step's threshold bin --
 // to a candidate list, in index order, one segment per block (a d-slice, at
 // most 16,384 coordinates).  All later passes (two digit histograms, per-block counts and
 // the ordered compaction into the ring) read the candidates only: a few
@@ -18,7 +18,7 @@
 // inserted last (a bitmap in LDS, one bit per coordinate of the block).  Host code
 // that reads e in between applies the same rule.  The first-digit histogram
 // is exact, so it tells whether the threshold bin lies at or above t_lo; if it
-// does not (the threshold dropped by more than two bins in one step), the
+// does not (the threshold fell into a bin at least two below the previous one), the
 // later passes of that step read the accumulator itself instead of the
 // candidate lists.  The result is exact either way; the prediction only saves
 // traffic.
@@ -244,8 +244,8 @@ __global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict_
 //   k_cand_compact   prefix sums of those counts (workgroup totals, then the 16 segments of
 //                    the workgroup), ordered compaction into the ring; clears histogram 3
 //
-// If the threshold bin turns out to lie below t_lo (the threshold fell by more than two bins in
-// one step), the candidate lists do not hold every key that matters.  The passes then read the
+// If the threshold bin turns out to lie below t_lo (the threshold fell by two bins or more in
+// one step: a bin is an eighth of an octave), the candidate lists do not hold every key that matters.  The passes then read the
 // accumulator itself (it is in `e`), a whole slice in place of its candidate segment: the
 // result is the same, the step moves 16 more bytes per coordinate.
 
@@ -490,8 +490,11 @@ __global__ __launch_bounds__(1024) void k_cand_count(const float *__restrict__ e
         sel->tau = tau;
         sel->quota = quota;
         sel->n_gt = k - quota;
-        const uint32_t tb = tau >> 20;                // next step collects from two bins below
-        sel->t_lo = (tb >= 2 ? tb - 2 : 0u) << 20;
+        // The next step collects from one bin below this threshold's bin.  (Two bins: a third more
+        // candidates to write and to read four times; d = 340M: 9.06 -> 8.96 ms per step.  The
+        // accumulator fallback then needs a threshold that falls by 9-19 % in one step.)
+        const uint32_t tb = tau >> 20;
+        sel->t_lo = (tb >= 1 ? tb - 1 : 0u) << 20;
     }
     clear_histogram(hist_clear, kHist1Copies * kBins2);
 
