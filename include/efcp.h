@@ -269,6 +269,12 @@ int efcp_export_state(efcp_ctx *ctx, void *host_buf, size_t bytes);
  * state is replaced. */
 int efcp_import_state(efcp_ctx *ctx, const void *host_buf, size_t bytes);
 
+/* The d-slice width that slice_width = 0 stands for (host arithmetic only, no device needed):
+ * the widest slice, 16384, unless rounds of 256 widest slices would be at least 2 % empty; then
+ * nearly equal slices that fill every round, a multiple of 64 (of 256 and at least 1024 when one
+ * round suffices).  0 if d or topk_block is invalid. */
+int32_t efcp_default_slice_width(int64_t d, int32_t topk_block);
+
 /* Geometry chosen at creation; any pointer may be NULL.
  *   slice      coordinates per d-slice staged in LDS by the SP and LCG kernels
  *              (a multiple of 64, at most 16384)

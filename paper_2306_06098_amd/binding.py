@@ -23,7 +23,7 @@ EXPORTS = (
     "efcp_workspace_bytes_ex", "efcp_row_length", "efcp_create_ggt", "efcp_workspace_bytes_ggt", "efcp_step", "efcp_step_ex", "efcp_apply",
     "efcp_apply_noalloc",
     "efcp_destroy", "efcp_get_row",
-    "efcp_get_error", "efcp_get_small", "efcp_create_opts", "efcp_workspace_bytes_opts", "efcp_get_geometry", "efcp_state_bytes",
+    "efcp_get_error", "efcp_get_small", "efcp_default_slice_width", "efcp_create_opts", "efcp_workspace_bytes_opts", "efcp_get_geometry", "efcp_state_bytes",
     "efcp_export_state", "efcp_import_state", "efcp_profile_enable",
     "efcp_profile_read", "efcp_last_error",
 )
@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.efcp_create_ggt.argtypes = [ctypes.POINTER(vp), i64, i32, i64, dbl, i32, i32, vp, ctypes.c_size_t]
     lib.efcp_workspace_bytes_ggt.restype = ctypes.c_size_t
     lib.efcp_workspace_bytes_ggt.argtypes = [i64, i32, i64, i32, i32]
+    lib.efcp_default_slice_width.restype = i32
+    lib.efcp_default_slice_width.argtypes = [i64, i32]
     lib.efcp_row_length.restype = i64
     lib.efcp_row_length.argtypes = [i64, i64, i32]
     lib.efcp_step.restype = ctypes.c_int

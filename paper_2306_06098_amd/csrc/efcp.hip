@@ -293,6 +293,12 @@ extern "C" size_t efcp_workspace_bytes_fmt(int64_t d, int32_t m, int64_t k, int3
     return efcp_workspace_bytes_ex(d, m, k, value_format, 0);
 }
 
+extern "C" int32_t efcp_default_slice_width(int64_t d, int32_t topk_block)
+{
+    if (d < 1 || d >= ((int64_t)1 << 31) || (topk_block != 0 && topk_block != kCandBlock)) return 0;
+    return pick_slice_width(d, topk_block ? 1 : 0, 0);
+}
+
 extern "C" int64_t efcp_row_length(int64_t d, int64_t k, int32_t topk_block)
 {
     if (topk_block == 0) return (k >= 1 && k <= d) ? k : 0;

@@ -92,3 +92,34 @@ def test_header_is_plain_c(tmp_path):
     if shutil.which("g++"):
         subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
                         "-x", "c++", "-I", inc, str(src)], check=True)
+
+
+def test_default_slice_width_invariants():
+    """The automatic d-slice width (host arithmetic): a multiple of 64 in [1024, 16384]; either the
+    widest slice, with less than 2 % of the places of its rounds of 256 empty, or slices that fit
+    the same number of rounds as the widest would need and leave less than one slice per
+    workgroup of slack; never more slices per workgroup than the SP kernel has room for; the
+    values the GPU tests and the design notes quote."""
+    lib = binding.load_library()
+    import numpy as np
+    rng = np.random.default_rng(5)
+    ds = [1, 3, 1023, 1024, 5_000, 65_536, 272_474, 4_194_304, 4_194_305, 11_200_000, 21_100_000, 110_000_000,
+          340_000_000, 2 ** 31 - 1] + [int(x) for x in np.exp(rng.uniform(0, np.log(2.0 ** 31 - 1), 400))]
+    for d in ds:
+        w = lib.efcp_default_slice_width(d, 0)
+        assert 1024 <= w <= 16384 and w % 64 == 0, (d, w)
+        n = -(-d // w)
+        widest = -(-d // 16384)
+        rounds = -(-widest // 256)
+        if w == 16384:
+            assert (rounds * 256 - widest) * 50 < rounds * 256 or d <= 1024 * 256 // 1, (d, w)
+        else:
+            assert n <= rounds * 256 or w == 1024, (d, w, n)
+            assert rounds * 256 - n < 256 or w == 1024, (d, w, n)
+        assert -(-(-(-n // 8)) // 32) <= 512
+        assert lib.efcp_default_slice_width(d, binding.TOPK_BLOCK) == 16384
+    for d, want in [(5_000, 1024), (272_474, 1280), (11_200_000, 14_592), (4_194_304, 16_384), (4_194_305, 8_256),
+                    (21_100_000, 13_760), (110_000_000, 15_936), (340_000_000, 16_384)]:
+        assert lib.efcp_default_slice_width(d, 0) == want
+    assert lib.efcp_default_slice_width(0, 0) == 0 and lib.efcp_default_slice_width(2 ** 31, 0) == 0
+    assert lib.efcp_default_slice_width(1000, 4096) == 0
