@@ -184,8 +184,9 @@ def main():
                          "resident gradient buffer is captured into a HIP graph once (no kernel argument of a "
                          "step depends on the step number) and the timed steps are replays of those graphs")
     ap.add_argument("--single-stream", action="store_true",
-                    help="efcp_options.single_stream: the eviction update on the step's own stream, no second "
-                         "queue (for counter collection with rocprofv3 --pmc)")
+                    help="efcp_options.single_stream: with --topk block, the eviction update on the step's own "
+                         "stream, no second queue (for counter collection with rocprofv3 --pmc); the global "
+                         "Top-k never uses a second stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:

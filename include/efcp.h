@@ -134,13 +134,16 @@ typedef struct efcp_options {
                                 depend on the width; S, q, coef and with them F^-1 x do in the last bits
                                 (order of the fp64 sums).  A state exported under one width is refused by
                                 a context created under another. */
-    int32_t single_stream;   /* 0: the update of the coefficient factor that a full window needs on every
-                                step (deleting the oldest row) runs on a stream of the library's own, beside
-                                the step's first passes, forked from and joined to the caller's stream with
-                                events.  1: it runs on the caller's stream, in front of them: no second
-                                stream, no events; a step then takes that update's time longer.  Results are
-                                bit for bit the same.  For tools that want one queue (counter collection
-                                with rocprofv3 --pmc, for one) and for callers who keep their own overlap. */
+    int32_t single_stream;   /* Only matters with Top-k in blocks.  There the update of the coefficient
+                                factor that a full window needs on every step (deleting the oldest row) is a
+                                kernel of its own.  0: it runs on a stream of the library's own, beside the
+                                step's first pass, forked from and joined to the caller's stream with events.
+                                1: it runs on the caller's stream, in front of that pass: no second stream,
+                                no events; a step then takes that kernel's time longer.  Results are bit for
+                                bit the same.  For tools that want one queue (counter collection with
+                                rocprofv3 --pmc, for one) and for callers who keep their own overlap.  With
+                                the global Top-k that update is part of a kernel of the selection and every
+                                step stays on the caller's stream whatever this says. */
 } efcp_options;
 int efcp_create_opts(efcp_ctx **ctx, int64_t d, int32_t m, int64_t k, double damping,
                      const efcp_options *opts, void *workspace, size_t workspace_bytes);

@@ -28,6 +28,7 @@
 //
 // All reductions have a fixed shape, so results do not depend on scheduling.
 #include "efcp_internal.h"
+#include "evict.h"
 
 namespace efcp {
 
@@ -52,103 +53,15 @@ __device__ __forceinline__ double block_sum_f64_1024(double v, double *buf)
 }
 
 // ------------------------------------------------------------------
-// Delete the oldest row (slot `old`) from the inverse factor.
-// Ages a = 0..m-2 of the surviving rows map to slots (old + 1 + a) mod m.
-// With sigma_a = 1 + sum_{b<a} p_b^2:
-//   K_aa = sqrt(sigma_{a+1}/sigma_a),  K_ab = p_a p_b / sqrt(sigma_b sigma_{b+1})  (a > b)
-// and Y = K^-1 W22 row by row:  Y_a = (W_a - p_a R_a) / K_aa,
-//   R_{a+1} = R_a + p_a / sqrt(sigma_a sigma_{a+1}) * Y_a,  R_0 = 0.
-// The recurrence is affine in R: R_{a+1} = (sigma_a/sigma_{a+1}) R_a + (...) W_a,
-// so a block splits the rows into 16 chunks of 64 ages, one per wave: every
-// wave first runs its chunk from R = 0 (all its loads independent of the other
-// chunks), the chunk results are chained through LDS with the closed-form
-// factor sigma_start/sigma_end, and a second sweep recomputes the chunk from
-// the right starting value and stores it.  Block b owns columns [64b, 64b+64);
-// column `old` is left alone (k_bwd clears it).
-// The kernel is part of every step; it returns at once while the window is not yet full.
+// Delete the oldest row from the inverse factor (evict.h) as a kernel of its own: the step with
+// Top-k in blocks, which has no selection kernels to carry it.  It is part of every such step
+// and returns at once while the window is not yet full.
 __global__ __launch_bounds__(1024) void k_evict(int32_t m, int32_t ldm, const StepState *__restrict__ step,
                                                 double *__restrict__ W)
 {
     const StepView sv = step_view(step, m, kBefore);
     if (!sv.evict) return;                    // uniform: nothing is replaced by this step
-    const int32_t old = sv.slot;
-    __shared__ double s_p[kMaxM], s_ik[kMaxM], s_g[kMaxM], s_sig[kMaxM + 1];
-    __shared__ double s_wave[16];
-    __shared__ double s_B[16][64];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform
-    const int n = m - 1;                      // surviving rows
-    const double w00 = W[(int64_t)old * ldm + old];
-
-    // thread a: p_a, then sigma by an exclusive scan of p^2 in age order
-    double p = 0.0;
-    if (tid < n) p = -W[(int64_t)((old + 1 + tid) % m) * ldm + old] / w00;
-    const double p2 = p * p;
-    double incl = p2;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const double t = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += t;
-    }
-    if (lane == 63) s_wave[wv] = incl;
-    __syncthreads();
-    double before = 1.0;                      // sigma_0 = 1
-    for (int i = 0; i < wv; i++) before += s_wave[i];
-    const double sigma = before + (incl - p2);
-    const double nxt = sigma + p2;
-    s_p[tid] = p;
-    s_ik[tid] = sqrt(sigma / nxt);
-    s_g[tid] = p / sqrt(sigma * nxt);
-    s_sig[tid] = sigma;
-    if (tid == 1023) s_sig[1024] = nxt;
-    __syncthreads();
-
-    const int col = blockIdx.x * 64 + lane;
-    const bool live = (col < m) && (col != old);
-    const int colc = min(col, m - 1);         // loads are unconditional (clamped), values masked:
-    const int a_lo = wv * 64;                 // conditional loads would be waited for one by one
-
-    // sweep 1: this wave's 64 ages starting from R = 0
-    double R = 0.0;
-    for (int a0 = a_lo; a0 < a_lo + 64; a0 += 16) {
-        double v[16];
-#pragma unroll
-        for (int u = 0; u < 16; u++) {
-            const int a = a0 + u;
-            const double t = W[(int64_t)((old + 1 + min(a, n)) % m) * ldm + colc];
-            v[u] = (live && a < n) ? t : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < 16; u++) {
-            const int a = a0 + u;
-            const double y = (v[u] - s_p[a] * R) * s_ik[a];
-            R = fma(s_g[a], y, R);
-        }
-    }
-    s_B[wv][lane] = R;
-    __syncthreads();
-    // chain the chunks before this one: R_in = sum_c B_c * sigma_end(c)/sigma_start(this)
-    R = 0.0;
-    for (int c = 0; c < wv; c++)
-        R = R * (s_sig[c * 64] / s_sig[c * 64 + 64]) + s_B[c][lane];
-
-    // sweep 2: recompute with the right start and store
-    for (int a0 = a_lo; a0 < a_lo + 64; a0 += 16) {
-        double v[16];
-#pragma unroll
-        for (int u = 0; u < 16; u++) {
-            const int a = a0 + u;
-            const double t = W[(int64_t)((old + 1 + min(a, n)) % m) * ldm + colc];
-            v[u] = (live && a < n) ? t : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < 16; u++) {
-            const int a = a0 + u;
-            const double y = (v[u] - s_p[a] * R) * s_ik[a];
-            R = fma(s_g[a], y, R);
-            if (live && a < n) W[(int64_t)((old + 1 + a) % m) * ldm + col] = y;
-        }
-    }
+    evict_block(blockIdx.x, m, ldm, sv.slot, W);
 }
 
 // ------------------------------------------------------------------
@@ -310,7 +223,7 @@ __global__ __launch_bounds__(1024) void k_apply_bwd(int32_t m, int32_t ldm, doub
 
 hipError_t launch_evict(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_evict, dim3((g.m + 63) / 64), dim3(1024), 0, stream, g.m, g.ldm, p.step, p.W);
+    hipLaunchKernelGGL(k_evict, dim3(evict_blocks(g.m)), dim3(1024), 0, stream, g.m, g.ldm, p.step, p.W);
     return hipGetLastError();
 }
 

@@ -491,14 +491,18 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     hipError_t rc = hipSuccess;
     auto mark = [&](int i) { if (ev && rc == hipSuccess) rc = hipEventRecord(ev[i], stream); };
 
-    const bool fork = factor && !ctx->single_stream;
-    if (factor && !fork) {
+    // Deleting the oldest row from the inverse factor (nothing happens until the window is full)
+    // depends on nothing in this step.  With the global Top-k it rides in the first kernel of the
+    // selection.  With Top-k in blocks it is a kernel of its own, on the side stream while the
+    // d-sized passes run, or in line when the context keeps to one stream.
+    const bool fork = factor && g.kb && !ctx->single_stream;
+    if (factor && g.kb && !fork) {
         if (rc == hipSuccess) rc = launch_evict(g, p, stream);
     }
-    if (fork) {         // delete the oldest row from the inverse factor while the d-sized passes run
+    if (fork) {
         if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_fork, stream);
         if (rc == hipSuccess) rc = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
-        if (rc == hipSuccess) rc = launch_evict(g, p, ctx->side);      // returns at once until the window is full
+        if (rc == hipSuccess) rc = launch_evict(g, p, ctx->side);
         if (rc == hipSuccess) rc = hipEventRecord(ctx->ev_join, ctx->side);
     }
     mark(0);
@@ -509,7 +513,7 @@ extern "C" int efcp_step_ex(efcp_ctx *ctx, const float *grad, int32_t x_source, 
     } else {
         if (rc == hipSuccess) rc = launch_ef_hist(g, p, grad, stream);
         mark(1);
-        if (rc == hipSuccess) rc = launch_select(g, p, stream);
+        if (rc == hipSuccess) rc = launch_select(g, p, factor, stream);
         mark(2);
         if (rc == hipSuccess) rc = launch_compact(g, p, stream);
     }

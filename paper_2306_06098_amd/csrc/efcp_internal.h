@@ -230,7 +230,7 @@ struct DevicePtrs {
 // No launcher takes the step number, the slot or the number of filled rows: the kernels read them
 // from p.step.
 hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
-hipError_t launch_select(const Geometry &g, const DevicePtrs &p, hipStream_t stream);
+hipError_t launch_select(const Geometry &g, const DevicePtrs &p, bool evict, hipStream_t stream);
 hipError_t launch_compact(const Geometry &g, const DevicePtrs &p, hipStream_t stream);
 hipError_t launch_block_topk(const Geometry &g, const DevicePtrs &p, const float *grad, hipStream_t stream);
 // x_source: 0 = dense x next to the newest row (a step), 1 = the newest row is x (a step),
@@ -312,23 +312,30 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v)
     return v;
 }
 
-// Sum of a double over each aligned group of 16 lanes, result in all 16 (rotations inside a DPP
-// row: no LDS traffic, fixed order).
+// A double moved between lanes by a DPP pattern that gives every lane a source lane (rotations,
+// mirrors and quad permutations inside a row of 16): no LDS traffic.
 template <int CTRL>
-__device__ __forceinline__ double dpp_rotated(double v)
+__device__ __forceinline__ double dpp_moved(double v)
 {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(v), CTRL, 0xf, 0xf, false);
     return __hiloint2double(hi, lo);
 }
 
-__device__ __forceinline__ double row16_sum_f64(double v)
+// Sums of TWO doubles over each aligned group of 16 lanes in four steps, fixed order: lanes 0-7
+// of the group end with the sum of a, lanes 8-15 with the sum of b.  In the first step each lane
+// hands the value it will not keep to the lane 8 away; the rest stays inside the halves (lane
+// i with 7 - i, then lane ^ 1, then lane ^ 2).
+__device__ __forceinline__ double row16_sum2_f64(double a, double b)
 {
-    v += dpp_rotated<0x128>(v);      // row_ror:8
-    v += dpp_rotated<0x124>(v);      // row_ror:4
-    v += dpp_rotated<0x122>(v);      // row_ror:2
-    v += dpp_rotated<0x121>(v);      // row_ror:1
-    return v;
+    const bool upper = (threadIdx.x & 8) != 0;
+    double keep = upper ? b : a;
+    const double give = upper ? a : b;
+    keep += dpp_moved<0x128>(give);      // row_ror:8
+    keep += dpp_moved<0x141>(keep);      // row_half_mirror
+    keep += dpp_moved<0xB1>(keep);       // quad_perm [1,0,3,2]
+    keep += dpp_moved<0x4E>(keep);       // quad_perm [2,3,0,1]
+    return keep;
 }
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)

@@ -27,6 +27,7 @@
 // and rows are written at positions computed by prefix sums, so every output
 // is deterministic.
 #include "efcp_internal.h"
+#include "evict.h"
 
 namespace efcp {
 
@@ -397,6 +398,11 @@ __device__ __forceinline__ void first_segment(int32_t b, int32_t blk, int64_t d,
 // counts in its own 1024-bin histogram in LDS (device-scope atomics on a few hot addresses from
 // thousands of waves serialise) and adds it once, at the end, into one of kHist1Copies
 // histograms in memory.
+// LEVEL 1 carries `n_evict` more workgroups in front of the `groups` that count: each deletes the
+// oldest row from 16 columns of the inverse factor W of the coefficient step (evict.h) when the
+// step replaces a row.  That work depends on nothing in this step and nothing here depends on
+// it; it sits in this kernel because the kernels of the selection leave most of the machine
+// idle, and as workgroups of a kernel of the stream it costs no second stream and no events.
 template <int LEVEL>
 __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e, int64_t d,
                                                     const float *__restrict__ cand_val,
@@ -408,12 +414,19 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
                                                     uint32_t *__restrict__ hist_clear, uint32_t k,
                                                     int32_t blk, int32_t groups,
                                                     uint32_t *__restrict__ rowmax, int32_t m,
-                                                    const StepState *__restrict__ step)
+                                                    const StepState *__restrict__ step, int32_t n_evict,
+                                                    int32_t ldm, double *__restrict__ W)
 {
+    if (LEVEL == 1 && (int32_t)blockIdx.x < n_evict) {            // uniform per workgroup
+        const StepView sv = step_view(step, m, kBefore);
+        if (sv.evict) evict_block((int32_t)blockIdx.x, m, ldm, sv.slot, W);
+        return;
+    }
+    const int32_t bid = (int32_t)blockIdx.x - (LEVEL == 1 ? n_evict : 0);    // among the workgroups that count
     __shared__ uint32_t lh[kBins2];
     __shared__ uint32_t tmp[33], res[3];
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    int32_t b = blockIdx.x * kSegsPerBlock + w;
+    int32_t b = bid * kSegsPerBlock + w;
     FirstBatch fb;
     request_first_batch(b, nb, blk, cand_val, cand_cnt, lane, fb);
     lh[threadIdx.x] = 0;
@@ -425,7 +438,7 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
         prefix = bin;
         // candidates hold every key >= t_lo: enough iff the threshold bin starts at or above t_lo
         redo = (bin << 20) < t_lo ? 1u : 0u;
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (bid == 0 && threadIdx.x == 0) {
             sel->p1 = bin;
             sel->kr1 = kr1;
             sel->redo = redo;
@@ -440,7 +453,7 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
         uint32_t bin, kr2, top;
         settle_digit<kBins2>(hist_prev, kr1, tmp, res, bin, kr2, top);
         prefix = (p1 << 10) | bin;
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (bid == 0 && threadIdx.x == 0) {
             sel->p2 = prefix;
             sel->kr2 = kr2;
         }
@@ -457,7 +470,7 @@ __global__ __launch_bounds__(1024) void k_cand_hist(const float *__restrict__ e,
     }
     __syncthreads();
     const uint32_t c = lh[threadIdx.x];
-    if (c) atomicAdd(&hist_out[(blockIdx.x % kHist1Copies) * kBins2 + threadIdx.x], c);
+    if (c) atomicAdd(&hist_out[(bid % kHist1Copies) * kBins2 + threadIdx.x], c);
 }
 
 // ------------------------------------------------------------------
@@ -665,18 +678,19 @@ hipError_t launch_ef_hist(const Geometry &g, const DevicePtrs &p, const float *g
     return hipGetLastError();
 }
 
-hipError_t launch_select(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
+hipError_t launch_select(const Geometry &g, const DevicePtrs &p, bool evict, hipStream_t stream)
 {
     const int32_t nb = g.n_slices;
     const int32_t nblk = (nb + kSegsPerBlock - 1) / kSegsPerBlock;
     // one wave per candidate segment until every workgroup of a histogram pass is in use
     const int32_t groups = nblk < kHistGroups ? nblk : kHistGroups;
-    hipLaunchKernelGGL(k_cand_hist<1>, dim3(groups), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
-                       p.cand_cnt, nb, p.sel, p.hist1, p.hist2, (uint32_t *)nullptr, (uint32_t)g.k, g.slice,
-                       groups, p.rowmax, g.m, p.step);
+    const int32_t n_evict = evict ? evict_blocks(g.m) : 0;
+    hipLaunchKernelGGL(k_cand_hist<1>, dim3(groups + n_evict), dim3(1024), 0, stream, p.e, g.d, p.cand_val,
+                       p.cand_idx, p.cand_cnt, nb, p.sel, p.hist1, p.hist2, (uint32_t *)nullptr, (uint32_t)g.k,
+                       g.slice, groups, p.rowmax, g.m, p.step, n_evict, g.ldm, p.W);
     hipLaunchKernelGGL(k_cand_hist<2>, dim3(groups), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
                        p.cand_cnt, nb, p.sel, p.hist2, p.hist3, p.hist1, (uint32_t)g.k, g.slice, groups,
-                       p.rowmax, g.m, p.step);
+                       p.rowmax, g.m, p.step, 0, g.ldm, (double *)nullptr);
     hipLaunchKernelGGL(k_cand_count, dim3(nblk), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
                        p.cand_cnt, nb, p.sel, p.hist3, p.hist2, (uint32_t)g.k, p.cnt_gt, p.cnt_eq, p.blk_gt,
                        p.blk_eq, g.slice);

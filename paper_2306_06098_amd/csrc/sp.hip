@@ -243,14 +243,9 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 #pragma unroll
             for (int c = 0; c < kBatch; c++)
                 sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, mask, xc, aq, ag);
-            aq = row16_sum_f64(aq);
-            ag = row16_sum_f64(ag);
-            if (gl == 0 && b.r < n_filled) {   // row r belongs to this group only: no race on racc[r]
-                double2 t = racc[b.r];
-                t.x += aq;
-                t.y += ag;
-                racc[b.r] = t;
-            }
+            const double sum = row16_sum2_f64(aq, ag);             // lanes 0-7: q part, lanes 8-15: Gram part
+            if ((gl & 7) == 0 && b.r < n_filled)                   // row r belongs to this group only: no race
+                reinterpret_cast<double *>(racc)[2 * b.r + (gl >> 3)] += sum;
         };
         while (__any(ba.r < n_filled)) {
             advance(ba, bb);
