@@ -68,6 +68,10 @@ __device__ __forceinline__ void emit_candidates(const float (&v)[4][4], uint32_t
 }
 
 // a = e + g (written over e), histogram of key bits 30..20, candidates.
+// (Launch bounds: at least 6 waves per SIMD, i.e. at most 80 vector registers, so that three
+// blocks share a CU: with two, a vector of 768 slices met 512 places and ran a round and a half.
+// Requesting the first chunk before the pending row is looked up was tried: the registers it
+// holds across that stretch spill at this bound, and the pass got a fifth slower.)
 // PEND (first pass only; 1: fp32 window, 2: bfloat16 window): if the step state names a pending
 // slot, `e` still holds the previous step's accumulator; the entries of the row inserted then (the
 // run of this block given by two entries of its offset column) count as +0, or as the rounding
@@ -77,7 +81,7 @@ constexpr int kEfWaves = kEfThreads / 64;
 constexpr int kEfChunk = kEfWaves * 1024;        // coordinates the block streams at a time
 
 template <int PEND>
-__global__ __launch_bounds__(kEfThreads) void k_ef_hist(const float *__restrict__ g,
+__global__ __launch_bounds__(kEfThreads, 6) void k_ef_hist(const float *__restrict__ g,
                                                          float *__restrict__ e, int64_t d,
                                                          uint32_t *__restrict__ hist,
                                                          const SelState *__restrict__ sel,
