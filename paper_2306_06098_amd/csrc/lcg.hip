@@ -203,24 +203,25 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
         const int32_t o1 = offT[(int64_t)(snx + 1) * m + trow];
         int32_t *offn = offs + (buf ^ 1) * 2 * kMaxM;
 
-        bool stored = false;
+        // Two batches per trip and no way out in the middle: a batch past the last row is an
+        // empty run read from the last row again.  (With an exit between the two halves the
+        // compiler sees a path on which the batch just requested is never waited for before its
+        // registers are written again, and answers with a wait for everything at the top of
+        // every trip: then the next batch is only requested once the current one has arrived.
+        // Without it the waits count: a batch is scattered piece by piece as it arrives while
+        // the next one stays in flight.  k_lcg 1.347 -> 1.331 ms at d = 110M.)
         while (__any(ba.r < n_filled)) {
             advance(ba, bb);
             load(bb);
+            __builtin_amdgcn_sched_barrier(0);    // request first, then wait: nothing of consume() moves up
             consume(ba);
-            const bool more = __any(bb.r < n_filled);
-            if (more) {
-                advance(bb, ba);
-                load(ba);
-                consume(bb);
-            }
-            if (!stored) {                    // offsets of the next slice into the other LDS buffer
-                offn[tid] = o0;
-                offn[kMaxM + tid] = o1;
-                stored = true;
-            }
-            if (!more) break;
+            advance(bb, ba);
+            load(ba);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(bb);
         }
+        offn[tid] = o0;             // offsets of the next slice into the other LDS buffer
+        offn[kMaxM + tid] = o1;
         float4 th[4];               // parameters of this slice: requested before the barrier
         if (FULL && UPDATE) {
 #pragma unroll
