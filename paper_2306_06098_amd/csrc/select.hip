@@ -689,9 +689,14 @@ hipError_t launch_select(const Geometry &g, const DevicePtrs &p, bool evict, hip
     // one wave per candidate segment until every workgroup of a histogram pass is in use
     const int32_t groups = nblk < kHistGroups ? nblk : kHistGroups;
     const int32_t n_evict = evict ? evict_blocks(g.m) : 0;
-    hipLaunchKernelGGL(k_cand_hist<1>, dim3(groups + n_evict), dim3(1024), 0, stream, p.e, g.d, p.cand_val,
+    // With the eviction update in it the first pass needs so many registers that one workgroup
+    // fills a CU: it gets no more workgroups than there are CUs (kMaxWgs), the counting ones
+    // taking several groups of segments each, rather than a second round behind the first.
+    int32_t groups1 = groups;
+    if (n_evict && groups1 + n_evict > kMaxWgs) groups1 = kMaxWgs - n_evict;       // n_evict <= 64
+    hipLaunchKernelGGL(k_cand_hist<1>, dim3(groups1 + n_evict), dim3(1024), 0, stream, p.e, g.d, p.cand_val,
                        p.cand_idx, p.cand_cnt, nb, p.sel, p.hist1, p.hist2, (uint32_t *)nullptr, (uint32_t)g.k,
-                       g.slice, groups, p.rowmax, g.m, p.step, n_evict, g.ldm, p.W);
+                       g.slice, groups1, p.rowmax, g.m, p.step, n_evict, g.ldm, p.W);
     hipLaunchKernelGGL(k_cand_hist<2>, dim3(groups), dim3(1024), 0, stream, p.e, g.d, p.cand_val, p.cand_idx,
                        p.cand_cnt, nb, p.sel, p.hist2, p.hist3, p.hist1, (uint32_t)g.k, g.slice, groups,
                        p.rowmax, g.m, p.step, 0, g.ldm, (double *)nullptr);
