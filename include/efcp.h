@@ -118,8 +118,8 @@ size_t efcp_workspace_bytes_ggt(int64_t d, int32_t m, int64_t k, int32_t value_f
 
 /* The general constructor: everything the calls above choose, as one structure, plus the
  * d-slice width.  opts == NULL means all zeros (fp32 values, global Top-k, Sparse M-FAC,
- * automatic width, second stream used); the calls above are this one with slice_width = 0 and
- * single_stream = 0. */
+ * automatic width, a second stream where the step has a use for one); the calls above are this one
+ * with slice_width = 0 and single_stream = 0. */
 typedef enum { EFCP_SPARSE_MFAC = 0, EFCP_SPARSE_GGT = 1 } efcp_preconditioner;
 typedef struct efcp_options {
     int32_t value_format;    /* efcp_value_format */

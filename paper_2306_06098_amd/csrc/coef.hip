@@ -13,7 +13,8 @@
 // solves of a step (a chain of m dependent column steps each) into plain
 // matrix-vector products that many workgroups share:
 //
-//   k_evict   (window already full)  delete the oldest row/column of A.
+//   evict     (window already full; evict.h, run by the first selection kernel or by k_evict)
+//             delete the oldest row/column of A.
 //             If A = [[a11, a^T], [a, A22]], L = [[l11, 0], [l, L22]] then
 //             A22 = L22 (I + p p^T) L22^T with p = L22^-1 l, and with the
 //             Cholesky factor K of I + p p^T (closed form, below) the new

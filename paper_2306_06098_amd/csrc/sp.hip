@@ -266,8 +266,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 // owns 64 rows; thread (bl, rl) adds workgroups bl, bl+16, ...; the 16
 // partial sums are then added in order.  Unfilled rows give exactly 0.
 // commit != 0: the "before" part of a step ends here (every kernel that needed t_done = t - 1 has
-// finished: they precede this one on the stream, and the eviction update on the side stream has
-// been joined), so one thread counts the step: t_done = t, and with the global Top-k the new row
+// finished: they precede this one on the stream, and where the eviction update runs on the side
+// stream it has been joined), so one thread counts the step: t_done = t, and with the global Top-k the new row
 // becomes the one whose entries are still to be taken out of e.
 __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ partial, int32_t m,
                                                     int32_t nwg, double2 *__restrict__ sq,

@@ -720,8 +720,7 @@ def test_sparse_ggt_duplicate_rows_checkpoint_and_limits(env):
 # synchronisation, no memset nodes), so a caller may capture them
 
 def test_step_and_apply_under_hip_graph_capture(env):
-    """A step (with the eviction update forked to the library's second stream)
-    captured into a graph and launched once equals the eager step of a twin
+    """A step captured into a graph and launched once equals the eager step of a twin
     context; efcp_apply captured once and replayed with new x contents equals
     the eager call every time (eager work and synchronisations in between)."""
     torch, _, binding = env
@@ -816,14 +815,18 @@ def test_two_contexts_on_two_streams_do_not_share_state(env):
         assert sa["step"] == sb["step"] == T and np.array_equal(sa["S"], sb["S"]) and np.array_equal(sa["coef"], sb["coef"])
 
 
-def test_single_stream_option_gives_the_same_bits(env):
+@pytest.mark.parametrize("topk_block", [16_384, 0])
+def test_single_stream_option_gives_the_same_bits(env, topk_block):
     """efcp_options.single_stream = 1 runs the eviction update on the caller's stream instead
     of the library's second stream: same kernels, other order of launches, identical results
-    through the fill of the window and on into evicting steps."""
+    through the fill of the window and on into evicting steps.  It decides something with Top-k
+    in blocks only (with the global Top-k the update is part of a selection kernel and the two
+    contexts enqueue the same launches)."""
     torch, _, binding = env
-    d, m, k, lam = 90_001, 6, 700, 1e-3
-    a = binding.Efcp(d, m, k, lam)
-    b = binding.Efcp(d, m, k, lam, single_stream=True)
+    d, m, lam = 90_001, 6, 1e-3
+    k = 120 if topk_block else 700
+    a = binding.Efcp(d, m, k, lam, topk_block=topk_block)
+    b = binding.Efcp(d, m, k, lam, topk_block=topk_block, single_stream=True)
     s = synth.GradientStream(d, 0.9, 8)
     g = torch.empty(d, dtype=torch.float32, device="cuda:0")
     oa, ob = torch.empty_like(g), torch.empty_like(g)
