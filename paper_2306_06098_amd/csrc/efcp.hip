@@ -106,6 +106,11 @@ bool make_geometry(int64_t d, int32_t m, int64_t k_in, int32_t fmt, int32_t topk
         // the SP kernel keeps two numbers per slice of a workgroup in a fixed piece of LDS
         if ((per + kMaxWgs / 8 - 1) / (kMaxWgs / 8) > 512) { *why = "slice width too small for this d"; return false; }
     }
+    // A row has k / n_slices entries per slice on average.  The SP / LCG workgroups give a row 16
+    // lanes (a batch of 192 entries) or, where that would leave nearly all of them idle, 4 lanes (48
+    // entries): the workgroup then works on 256 rows at once instead of 64, and the dependent
+    // batches per lane, which is what a small vector's passes consist of, fall by four.
+    g.row_lanes = g.k / g.n_slices <= 40 ? 4 : 16;
     g.lds_sp = ((size_t)8 << lg) + fixed_sp;
     g.lds_lcg = ((size_t)8 << lg) + fixed_lcg;
     return true;

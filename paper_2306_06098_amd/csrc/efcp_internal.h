@@ -39,7 +39,6 @@ constexpr int kCandBlock = 16384;    // widest d-slice (its accumulators fill th
 constexpr int kMinSlice = 1024;      // narrowest slice chosen automatically
 constexpr int kMaxWgs = 256;         // persistent SP / LCG workgroups at most: 32 on each of 8 XCDs
 constexpr int kMaxM = 1024;          // window slots == threads of the m x m kernel
-constexpr int kRowGroups = 64;       // 16-lane groups per 1024-thread workgroup
 constexpr int kBins1 = 2048;         // first radix digit: key bits 30..20
 constexpr int kHist1Copies = 4;      // copies of a digit's histogram that the blocks add into
 constexpr int kBins2 = 1024;         // second: bits 19..10, third: bits 9..0
@@ -51,8 +50,8 @@ constexpr int kGgtMaxSweeps = 30;    // Jacobi sweeps at most (a sweep without r
 // entry falls in (the slice follows from the row's offset table), values as fp32 or bfloat16:
 // 6 or 4 bytes per entry where an absolute int32 index next to an fp32 value would need 8.
 // EPL = entries one lane takes per chunk (one load per array: iraw_t of indices, vraw_t of
-// values); a chunk is what a 16-lane group reads with these; kBatch = chunks a lane keeps in
-// flight.
+// values); a chunk is what the GW lanes that share a row (16, or 4 where runs are short: see
+// Geometry::row_lanes) read with these, GW * EPL entries; kBatch = chunks a lane keeps in flight.
 enum : int { kFmtF32 = 0, kFmtBf16 = 1 };
 
 template <int FMT> struct Fmt;
@@ -60,7 +59,7 @@ template <> struct Fmt<kFmtF32> {
     using idx_t = uint16_t;
     using val_t = float;
     using iraw_t = int2;     // 4 x uint16
-    static constexpr int EPL = 4, kChunk = 64, kBatch = 3, kEntryBytes = 6;
+    static constexpr int EPL = 4, kBatch = 3, kEntryBytes = 6;
 };
 template <> struct Fmt<kFmtBf16> {
     using idx_t = uint16_t;
@@ -69,7 +68,7 @@ template <> struct Fmt<kFmtBf16> {
     // A group is 4 entries = 16 bytes: one load per lane and chunk.  (Groups of 8, two 16-byte
     // loads per lane, left 36 % of the lanes idle on the ~164-entry runs of a 1 % window: a run
     // then needs two 128-entry chunks, and these passes are bound by vector-ALU work.)
-    static constexpr int EPL = 4, kChunk = 64, kBatch = 3, kEntryBytes = 4;
+    static constexpr int EPL = 4, kBatch = 3, kEntryBytes = 4;
 };
 
 // Entry p of a row lives in group p / EPL: [EPL x uint16 index][EPL x value].
@@ -198,6 +197,8 @@ struct Geometry {
     int32_t fmt;             // kFmtF32 / kFmtBf16
     int32_t slice, n_slices; // coordinates per d-slice (multiple of 64, <= kCandBlock), number of slices
     int32_t sp_grid;         // persistent SP workgroups: 8 * (workgroups per XCD)
+    int32_t row_lanes;       // lanes of the SP / LCG workgroups that share a row: 16, or 4 where a row has few
+                             // entries per slice (a workgroup then works on 256 rows at once instead of 64)
     size_t lds_sp, lds_lcg;
 };
 
@@ -322,19 +323,26 @@ __device__ __forceinline__ double dpp_moved(double v)
     return __hiloint2double(hi, lo);
 }
 
-// Sums of TWO doubles over each aligned group of 16 lanes in four steps, fixed order: lanes 0-7
-// of the group end with the sum of a, lanes 8-15 with the sum of b.  In the first step each lane
-// hands the value it will not keep to the lane 8 away; the rest stays inside the halves (lane
-// i with 7 - i, then lane ^ 1, then lane ^ 2).
-__device__ __forceinline__ double row16_sum2_f64(double a, double b)
+// Sums of TWO doubles over each aligned group of GW lanes (16 or 4), fixed order: the lower half
+// of the group ends with the sum of a, the upper half with the sum of b.  In the first step each
+// lane hands the value it will not keep to the lane half a group away; the rest stays inside the
+// halves (16 lanes: lane i with 7 - i, then lane ^ 1, then lane ^ 2; 4 lanes: lane ^ 1).
+template <int GW>
+__device__ __forceinline__ double row_sum2_f64(double a, double b)
 {
-    const bool upper = (threadIdx.x & 8) != 0;
+    static_assert(GW == 16 || GW == 4, "group width");
+    const bool upper = (threadIdx.x & (GW / 2)) != 0;
     double keep = upper ? b : a;
     const double give = upper ? a : b;
-    keep += dpp_moved<0x128>(give);      // row_ror:8
-    keep += dpp_moved<0x141>(keep);      // row_half_mirror
-    keep += dpp_moved<0xB1>(keep);       // quad_perm [1,0,3,2]
-    keep += dpp_moved<0x4E>(keep);       // quad_perm [2,3,0,1]
+    if constexpr (GW == 16) {
+        keep += dpp_moved<0x128>(give);      // row_ror:8
+        keep += dpp_moved<0x141>(keep);      // row_half_mirror
+        keep += dpp_moved<0xB1>(keep);       // quad_perm [1,0,3,2]
+        keep += dpp_moved<0x4E>(keep);       // quad_perm [2,3,0,1]
+    } else {
+        keep += dpp_moved<0x4E>(give);       // quad_perm [2,3,0,1]
+        keep += dpp_moved<0xB1>(keep);       // quad_perm [1,0,3,2]
+    }
     return keep;
 }
 

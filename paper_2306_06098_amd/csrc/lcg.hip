@@ -5,7 +5,8 @@
 // Segmented by d-slice: one workgroup owns the coordinates of a slice and
 // keeps their accumulators in LDS, so no global-memory atomics exist and two
 // workgroups never touch the same output.  Inside the workgroup all 64
-// 16-lane groups stream different rows at once; to make the sum independent
+// 16-lane groups (256 4-lane groups where a row has few entries per slice)
+// stream different rows at once; to make the sum independent
 // of the order in which they arrive, every product coef_r * v is converted to
 // a 64-bit fixed-point integer (unit chosen per step from sum_r |coef_r| max|c_r|
 // so that the whole sum fits in 51 bits) and added with integer LDS
@@ -71,7 +72,7 @@ __device__ __forceinline__ void lcg_scatter(const typename Fmt<FMT>::iraw_t &iv,
 // UPDATE = true: `out` holds the parameters and receives the optimizer step with decoupled
 // weight decay, theta <- decay*theta - lr*(x/lambda - sum) (Algorithm 1 line 9), instead of
 // the preconditioned vector.
-template <int FMT, bool XDENSE, bool UPDATE>
+template <int FMT, bool XDENSE, bool UPDATE, int GW>
 __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float *__restrict__ out,
                                               int64_t d, int32_t m, const StepState *__restrict__ step,
                                               int64_t row_stride,
@@ -86,7 +87,8 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     const StepView sv = step_view(step, m, kAfter);
     const int32_t n_filled = sv.n_filled, x_row = sv.slot;
     const int32_t r_last = max(n_filled, 1) - 1;      // rows past the end repeat this one
-    constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
+    constexpr int EPL = Fmt<FMT>::EPL, kChunk = GW * EPL, kBatch = Fmt<FMT>::kBatch;
+    constexpr int kRowGroups = 1024 / GW;                // rows the workgroup works on at once
     extern __shared__ __align__(16) unsigned char smem[];
     // `slice` coordinates (a multiple of 64, at most kCandBlock) are live; the LDS layout is that
     // of the widest slice
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
     __shared__ double wsum[16];
 
     const int tid = threadIdx.x;
-    const int grp = tid >> 4, gl = tid & 15;
+    const int grp = tid / GW, gl = tid % GW;
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
     const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
@@ -290,14 +292,22 @@ __global__ __launch_bounds__(1024) void k_lcg(const float *__restrict__ x, float
 
 namespace {
 
+template <int FMT, bool XDENSE, bool UPDATE, int GW>
+void launch_lcg_gw(const Geometry &g, const DevicePtrs &p, const float *x, float *out, double lambda,
+                   const LcgMode &md, hipStream_t stream)
+{
+    hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE, GW>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
+                       g.d, g.m, p.step, g.row_stride, g.slice, g.n_slices, g.sp_grid / 8,
+                       p.ring, p.offT,
+                       p.coef, p.rowmax, p.status, 1.0 / lambda, md.decay, md.lr);
+}
+
 template <int FMT, bool XDENSE, bool UPDATE>
 void launch_lcg_as(const Geometry &g, const DevicePtrs &p, const float *x, float *out, double lambda,
                    const LcgMode &md, hipStream_t stream)
 {
-    hipLaunchKernelGGL((k_lcg<FMT, XDENSE, UPDATE>), dim3(g.sp_grid), dim3(1024), g.lds_lcg, stream, x, out,
-                       g.d, g.m, p.step, g.row_stride, g.slice, g.n_slices, g.sp_grid / 8,
-                       p.ring, p.offT,
-                       p.coef, p.rowmax, p.status, 1.0 / lambda, md.decay, md.lr);
+    if (g.row_lanes == 4) launch_lcg_gw<FMT, XDENSE, UPDATE, 4>(g, p, x, out, lambda, md, stream);
+    else launch_lcg_gw<FMT, XDENSE, UPDATE, 16>(g, p, x, out, lambda, md, stream);
 }
 
 template <int FMT>
@@ -314,8 +324,12 @@ void launch_lcg_fmt(const Geometry &g, const DevicePtrs &p, const float *x, floa
 template <int FMT, bool XDENSE, bool UPDATE>
 hipError_t set_lds_lcg(const Geometry &g)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<FMT, XDENSE, UPDATE>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<FMT, XDENSE, UPDATE, 16>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    if (rc == hipSuccess)
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lcg<FMT, XDENSE, UPDATE, 4>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_lcg);
+    return rc;
 }
 
 template <int FMT>

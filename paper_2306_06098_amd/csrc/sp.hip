@@ -6,9 +6,10 @@
 // newest row scattered to dense in LDS (interleaved float2, one 8-byte LDS
 // gather serves both products), then streams the index/value runs of all
 // filled rows that fall in the slice.  x is read from HBM once and every
-// gather is an LDS access.  A 16-lane group owns one row at a time and reads
-// its run chunk by chunk (per lane four 16-bit positions and four fp32 values,
-// or eight and eight in the bfloat16 format), one batch of chunks being
+// gather is an LDS access.  A group of GW lanes (16; 4 where a row has only a
+// few entries per slice, so that the workgroup works on 256 rows at once
+// instead of 64) owns one row at a time and reads its run chunk by chunk (per
+// lane four 16-bit positions and four fp32 or bfloat16 values), one batch of chunks being
 // consumed while the next is in flight; products of two fp32 values are exact
 // in fp64 and are accumulated in fp64.
 //
@@ -22,7 +23,7 @@
 
 namespace efcp {
 
-// One batch = up to kBatch chunks of one row's run in the slice: lane gl of the 16-lane group
+// One batch = up to kBatch chunks of one row's run in the slice: lane gl of the row's group
 // reads entries [pc, pc+EPL), pc = pcs + EPL*gl + kChunk*c.  A run longer than a batch is
 // continued by the next batch (same row, pcs advanced), so the row loop has a single shape
 // and the number of loads in flight is always known.
@@ -75,7 +76,7 @@ enum : int { kXDense = 0, kXNewest = 1, kXOnly = 2 };
 // newest row's entries that fall into it.  The switch between slices is then
 // three barriers and LDS traffic, with the first batch of ring loads of the
 // new slice issued before the last two.
-template <int FMT, int XM>
+template <int FMT, int XM, int GW>
 __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_t d, int32_t m,
                                              const StepState *__restrict__ step, int64_t row_stride,
                                              int64_t k, int32_t slice, int32_t nsl, int32_t cpx,
@@ -89,7 +90,8 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     const int32_t r_last = max(n_filled, 1) - 1;      // rows past the end repeat this one (row 0 of an empty window)
     using idx_t = typename Fmt<FMT>::idx_t;
     using val_t = typename Fmt<FMT>::val_t;
-    constexpr int EPL = Fmt<FMT>::EPL, kChunk = Fmt<FMT>::kChunk, kBatch = Fmt<FMT>::kBatch;
+    constexpr int EPL = Fmt<FMT>::EPL, kChunk = GW * EPL, kBatch = Fmt<FMT>::kBatch;
+    constexpr int kRowGroups = 1024 / GW;                // rows the workgroup works on at once
     extern __shared__ __align__(16) unsigned char smem[];
     // `slice` coordinates (a multiple of 64, at most kCandBlock) are live; the LDS layout is that
     // of the widest slice
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
     int32_t *np1 = np0 + kMaxSlicesPerWg;                          //   in each slice of this workgroup
 
     const int tid = threadIdx.x;
-    const int grp = tid >> 4, gl = tid & 15;
+    const int grp = tid / GW, gl = tid % GW;
     const int32_t per = (nsl + 7) >> 3;
     const int32_t xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
     const SliceList sl(xcd * per, min(nsl, (xcd + 1) * per), cu, cpx);
@@ -243,9 +245,9 @@ __global__ __launch_bounds__(1024) void k_sp(const float *__restrict__ x, int64_
 #pragma unroll
             for (int c = 0; c < kBatch; c++)
                 sp_accumulate<FMT>(b.iv[c], b.vv[c], b.pcs + gl * EPL + c * kChunk, b.p0, hi, mask, xc, aq, ag);
-            const double sum = row16_sum2_f64(aq, ag);             // lanes 0-7: q part, lanes 8-15: Gram part
-            if ((gl & 7) == 0 && b.r < n_filled)                   // row r belongs to this group only: no race
-                reinterpret_cast<double *>(racc)[2 * b.r + (gl >> 3)] += sum;
+            const double sum = row_sum2_f64<GW>(aq, ag);           // lower half of the group: q part, upper: Gram part
+            if ((gl & (GW / 2 - 1)) == 0 && b.r < n_filled)        // row r belongs to this group only: no race
+                reinterpret_cast<double *>(racc)[2 * b.r + gl / (GW / 2)] += sum;
         };
         while (__any(ba.r < n_filled)) {
             advance(ba, bb);
@@ -310,12 +312,19 @@ __global__ __launch_bounds__(1024) void k_sp_reduce(const double2 *__restrict__ 
 
 namespace {
 
+template <int FMT, int XM, int GW>
+void launch_sp_gw(const Geometry &g, const DevicePtrs &p, const float *x, hipStream_t stream)
+{
+    hipLaunchKernelGGL((k_sp<FMT, XM, GW>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, p.step,
+                       g.row_stride, g.k, g.slice, g.n_slices, g.sp_grid / 8,
+                       p.ring, p.offT, p.partial);
+}
+
 template <int FMT, int XM>
 void launch_sp_as(const Geometry &g, const DevicePtrs &p, const float *x, hipStream_t stream)
 {
-    hipLaunchKernelGGL((k_sp<FMT, XM>), dim3(g.sp_grid), dim3(1024), g.lds_sp, stream, x, g.d, g.m, p.step,
-                       g.row_stride, g.k, g.slice, g.n_slices, g.sp_grid / 8,
-                       p.ring, p.offT, p.partial);
+    if (g.row_lanes == 4) launch_sp_gw<FMT, XM, 4>(g, p, x, stream);
+    else launch_sp_gw<FMT, XM, 16>(g, p, x, stream);
 }
 
 template <int FMT>
@@ -329,8 +338,12 @@ void launch_sp_fmt(const Geometry &g, const DevicePtrs &p, const float *x, int32
 template <int FMT, int XM>
 hipError_t set_lds_sp(const Geometry &g)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<FMT, XM>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<FMT, XM, 16>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    if (rc == hipSuccess)
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_sp<FMT, XM, 4>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_sp);
+    return rc;
 }
 
 }  // namespace
