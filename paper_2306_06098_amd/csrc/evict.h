@@ -17,7 +17,8 @@ namespace efcp {
 // The recurrence is affine in R: R_{a+1} = (sigma_a/sigma_{a+1}) R_a + (...) W_a.  A block owns
 // 16 columns and splits the rows into 64 chunks of 16 ages: a thread loads its 16 entries of one
 // column once (all loads independent of every other chunk), runs them from R = 0, the chunk
-// results are chained through LDS with the closed-form factor sigma_start/sigma_end, and the
+// results are chained through LDS with the closed-form factor sigma_start/sigma_end (one thread per
+// column walks the chunks), and the
 // thread runs its 16 entries again, from registers, with the right starting value and stores
 // them.  Memory is thus waited for three times in all (first column, entries, nothing after the
 // stores), which keeps the kernel short also while a d-sized pass saturates the memory system
@@ -60,7 +61,7 @@ __device__ __forceinline__ void evict_block(int32_t blk, int32_t m, int32_t ldm,
         if (!(live && a_lo + u < n)) v[u] = 0.0;
 
     // thread a: p_a, then sigma by an exclusive scan of p^2 in age order
-    const double p = tid < n ? -wp / w00 : 0.0;
+    const double p = tid < n ? -wp * (1.0 / w00) : 0.0;
     const double p2 = p * p;
     double incl = p2;
 #pragma unroll
@@ -71,12 +72,14 @@ __device__ __forceinline__ void evict_block(int32_t blk, int32_t m, int32_t ldm,
     if (lane == 63) s_wave[wv] = incl;
     __syncthreads();
     double before = 1.0;                      // sigma_0 = 1
-    for (int i = 0; i < wv; i++) before += s_wave[i];
+#pragma unroll
+    for (int i = 0; i < 16; i++) before += i < wv ? s_wave[i] : 0.0;     // (all 16 reads at once)
     const double sigma = before + (incl - p2);
     const double nxt = sigma + p2;
+    const double rs = 1.0 / sqrt(sigma * nxt);    // 1/K_aa = sqrt(sigma/nxt) = sigma * rs
     s_p[tid] = p;
-    s_ik[tid] = sqrt(sigma / nxt);
-    s_g[tid] = p / sqrt(sigma * nxt);
+    s_ik[tid] = sigma * rs;
+    s_g[tid] = p * rs;
     s_sig[tid] = sigma;
     if (tid == 1023) s_sig[1024] = nxt;
     __syncthreads();
@@ -92,14 +95,21 @@ __device__ __forceinline__ void evict_block(int32_t blk, int32_t m, int32_t ldm,
     }
     s_B[ch][cl] = R;
     __syncthreads();
-    // chain the chunks before this one: R_in = sum_c B_c * sigma_end(c)/sigma_start(this)
-    // (fixed trip count: the LDS reads do not wait for one another)
-    R = 0.0;
-#pragma unroll 16
-    for (int c = 0; c < kEvictChunks; c++) {
-        const double t = fma(R, s_ratio[c], s_B[c][cl]);
-        R = c < ch ? t : R;
+    // chain the chunks: the value a chunk starts from is R_in(c+1) = R_in(c) * sigma_start(c)/sigma_end(c)
+    // + B_c, R_in(0) = 0.  One thread per column walks the 64 chunks and leaves R_in in place of B
+    // (every thread doing the walk for itself is 1 MB of LDS reads per workgroup, a quarter of the
+    // whole update's time).
+    if (tid < kEvictCols) {
+        double Rin = 0.0;
+#pragma unroll 8
+        for (int c = 0; c < kEvictChunks; c++) {
+            const double t = s_B[c][tid];
+            s_B[c][tid] = Rin;
+            Rin = fma(Rin, s_ratio[c], t);
+        }
     }
+    __syncthreads();
+    R = s_B[ch][cl];
 
     // sweep 2: the same entries with the right start, stored
 #pragma unroll
