@@ -9,7 +9,8 @@ against the CPU oracle and nothing else.
   e bit-exact, all of S and q to 1e-10, F^-1 g to 1e-3.  This is the regime the
   benchmark times (m = 1024, one eviction per step), including the update of
   the inverse factor over all sixteen 64-row chunks.
-* Windows of m in {65, 200, 1024} rows after many evictions: the rows are read
+* Windows of m in {65, 200, 1024} rows after many evictions (k = 64, and k = 3000 in slices of
+  1024 coordinates so that the window passes run with 16 lanes per row): the rows are read
   back from the library, loaded into a FRESH oracle in age order, and the
   oracle's own Gram matrix (all of it) and F^-1 x for a new x are compared with
   the library's.  Nothing on the reference side comes from the library except
@@ -73,12 +74,17 @@ def test_resnet20_shape_full_window_other_modes_vs_oracle(env, capsys, bf16):
     assert w["steps"] == m + 4
 
 
-@pytest.mark.parametrize("m,steps", [(65, 65 + 140), (200, 200 + 75), (1024, 1024 + 40)])
-def test_window_after_many_evictions_reloaded_into_a_fresh_oracle(env, m, steps):
+@pytest.mark.parametrize("m,steps,k,slice_width", [
+    (65, 65 + 140, 64, 0), (200, 200 + 75, 64, 0), (1024, 1024 + 40, 64, 0),
+    # 75 entries per row and slice: the window passes give a row 16 lanes (the cases above and the
+    # ResNet-20 shape, with a dozen entries per row and slice, run them with 4)
+    (1024, 1024 + 24, 3000, 1024),
+])
+def test_window_after_many_evictions_reloaded_into_a_fresh_oracle(env, m, steps, k, slice_width):
     torch, oracle_mod, binding = env
-    d, k, lam = 40_003, 64, 1e-4
+    d, lam = 40_003, 1e-4
     s = synth.GradientStream(d, 0.9, 21 + m)
-    ctx = binding.Efcp(d, m, k, lam)
+    ctx = binding.Efcp(d, m, k, lam, slice_width=slice_width)
     g = torch.empty(d, dtype=torch.float32, device="cuda:0")
     out = torch.empty_like(g)
     for t in range(steps):
