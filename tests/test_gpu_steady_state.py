@@ -58,10 +58,12 @@ def test_resnet20_shape_full_window_evicting_steps_vs_oracle(env, capsys):
     assert w["steps"] == wl.m + evicting
 
 
-@pytest.mark.parametrize("bf16", [False, True])
-def test_resnet20_shape_full_window_other_modes_vs_oracle(env, capsys, bf16):
+@pytest.mark.parametrize("bf16,slice_width", [(False, 0), (True, 0), (False, 8192), (True, 8192)])
+def test_resnet20_shape_full_window_other_modes_vs_oracle(env, capsys, bf16, slice_width):
     """Same regime, fewer coordinates (the oracle's sort dominates the fill): bfloat16 window,
-    and apply() on the full window after every evicting step."""
+    and apply() on the full window after every evicting step.  With the automatic slice width a
+    row has 5 entries per slice and the window passes give it 4 lanes; in slices of 8,192
+    coordinates it has 78 and gets 16."""
     torch, oracle_mod, binding = env
     d, m, k, lam = 70_001, 1024, 700, 1e-5
     s = synth.GradientStream(d, 0.9, 77)
@@ -70,7 +72,7 @@ def test_resnet20_shape_full_window_other_modes_vs_oracle(env, capsys, bf16):
         for _ in range(m + 4):
             yield s.next()
     w = run_parity(torch, oracle_mod, binding, d, m, k, lam, grads(), fill=m, fill_check_every=256,
-                   bf16=bf16, apply_every=1, say=_sayer(capsys))
+                   bf16=bf16, apply_every=1, say=_sayer(capsys), slice_width=slice_width)
     assert w["steps"] == m + 4
 
 
