@@ -40,17 +40,25 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
-// Sum over the 1024 threads of a block in a fixed order.  buf: 16 doubles.
-__device__ __forceinline__ double block_sum_f64_1024(double v, double *buf)
+// Two sums over the 1024 threads of a block at once, each in a fixed order.  buf: 32 doubles.
+__device__ __forceinline__ void block_sum2_f64_1024(double &a, double &b, double *buf)
 {
-    v = wave_sum_f64(v);
-    if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+    a = wave_sum_f64(a);
+    b = wave_sum_f64(b);
+    if ((threadIdx.x & 63) == 0) {
+        buf[threadIdx.x >> 6] = a;
+        buf[16 + (threadIdx.x >> 6)] = b;
+    }
     __syncthreads();
-    double r = 0.0;
+    double ra = 0.0, rb = 0.0;
 #pragma unroll
-    for (int i = 0; i < 16; i++) r += buf[i];
+    for (int i = 0; i < 16; i++) {
+        ra += buf[i];
+        rb += buf[16 + i];
+    }
     __syncthreads();
-    return r;
+    a = ra;
+    b = rb;
 }
 
 // ------------------------------------------------------------------
@@ -86,9 +94,17 @@ __global__ __launch_bounds__(256) void k_fwd(int32_t m, int32_t ldm, const StepS
 #pragma unroll
         for (int u = 0; u < kMaxM / 64; u++) v[u] = wr[min(lane + 64 * u, m - 1)];
     }
+    // ... and so is (q, s): unconditional loads (clamped), masked once the slot is known, so that
+    // the kernel waits for memory once
+    double2 t_sq[kMaxM / 256];
+#pragma unroll
+    for (int u = 0; u < kMaxM / 256; u++) t_sq[u] = sq[min((int)threadIdx.x + 256 * u, m - 1)];
     const int32_t slot = whole ? -1 : step_view(step, m, kAfter).slot;
-    for (int j = threadIdx.x; j < kMaxM; j += 256)
-        s_sq[j] = (j < m && j != slot) ? sq[j] : make_double2(0.0, 0.0);
+#pragma unroll
+    for (int u = 0; u < kMaxM / 256; u++) {
+        const int j = threadIdx.x + 256 * u;
+        s_sq[j] = (j < m && j != slot) ? t_sq[u] : make_double2(0.0, 0.0);
+    }
     __syncthreads();
     if (row >= m) return;
     double az = 0.0, aw = 0.0;
@@ -119,7 +135,8 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const Step
                                               uint32_t *__restrict__ status)
 {
     __shared__ double s_z[kMaxM], s_r[kMaxM];
-    __shared__ double buf[16];
+    __shared__ double2 s_sq[kMaxM];
+    __shared__ double buf[32];
     __shared__ double2 red[64][kBwdCols];
 
     const int tid = threadIdx.x;
@@ -131,16 +148,21 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const Step
     double wv[kMaxM / 64];
 #pragma unroll
     for (int u = 0; u < kMaxM / 64; u++) wv[u] = W[(int64_t)min(rg + 64 * u, m - 1) * ldm + colc];
+    // ... and with them everything else the block reads, whatever the slot turns out to be: the
+    // kernel waits for memory once
+    const double2 t_zw = zw[min(tid, m - 1)];
+    const double2 t_sq = sq[min(tid, m - 1)];
+    const double2 sqc = sq[colc];
     const int32_t slot = step_view(step, m, kAfter).slot;         // the slot written by this step
+    s_sq[tid] = t_sq;
     double z = 0.0, w = 0.0;
     if (tid < m && tid != slot) {
-        const double2 t = zw[tid];
-        z = t.x;
-        w = t.y;
+        z = t_zw.x;
+        w = t_zw.y;
     }
-    const double zz = block_sum_f64_1024(z * z, buf);
-    const double zwd = block_sum_f64_1024(z * w, buf);
-    const double2 sqn = sq[slot];                    // (q_n, s_nn)
+    double zz = z * z, zwd = z * w;
+    block_sum2_f64_1024(zz, zwd, buf);               // (its barrier also publishes s_sq)
+    const double2 sqn = s_sq[slot];                  // (q_n, s_nn)
     const double mlam = (double)m * lambda;
     double piv = sqn.y + mlam - zz;
     if (!(piv >= mlam)) {                            // the exact Schur complement is >= m*lambda
@@ -174,7 +196,6 @@ __global__ __launch_bounds__(1024) void k_bwd(int32_t m, int32_t ldm, const Step
             c += red[i][cl].x;
             y += red[i][cl].y;
         }
-        const double2 sqc = sq[col];
         double coef;
         if (col == slot) {
             coef = f / lambda;
