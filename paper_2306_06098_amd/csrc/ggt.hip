@@ -127,7 +127,11 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__
                                 const double t = (h >= 0.0 ? as : -as) / (fabs(h) + hy);
                                 c = rsqrt(1.0 + t * t);
                                 s = t * c;
-                                atomicAdd(n_rot, 1);
+                                // A sweep whose rotations all have |t| <= 2^-27 leaves off-diagonal entries
+                                // of relative size 2^-54 (each is annihilated once and then only moved by
+                                // other angles of that size times entries of that size): such a sweep is the
+                                // last one, and only larger rotations are counted.
+                                if (t * t > 0x1p-54) atomicAdd(n_rot, 1);
                             }
                         }
                     }
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__
         __syncthreads();
         if (tid == 0) *n_rot = 0;
         __syncthreads();
-        if (done) break;                      // uniform: a whole sweep without a rotation
+        if (done) break;                      // uniform: a whole sweep without a rotation that counts
     }
     if (tid < m) lam[tid] = tid < n ? A[tid * kGgtLd + tid] : 0.0;
     if (tid == 0) *n_stages = stage_out;
