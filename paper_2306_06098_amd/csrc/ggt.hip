@@ -47,12 +47,13 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__
                                                   double *__restrict__ S, const double2 *__restrict__ sq,
                                                   double *__restrict__ q_out, double *__restrict__ lam,
                                                   double2 *__restrict__ rot, int32_t *__restrict__ n_stages,
-                                                  int32_t max_sweeps)
+                                                  int32_t max_sweeps, double *__restrict__ vtq)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     double *A = reinterpret_cast<double *>(smem);                          // [kGgtMaxM][kGgtLd]
     double2 *cs = reinterpret_cast<double2 *>(A + kGgtMaxM * kGgtLd);      // [64]
     int32_t *n_rot = reinterpret_cast<int32_t *>(cs + 64);                 // [1] rotations of this sweep
+    double *yv = reinterpret_cast<double *>(n_rot + 4);                    // [kGgtMaxM + 2] V^T q as it forms (update)
 
     const StepView sv = step_view(step, m, kAfter);
     const int32_t n = sv.n_filled, slot = sv.slot;
@@ -73,6 +74,10 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__
         A[e] = (i < n && j < n) ? S[(int64_t)i * m + j] : 0.0;
     }
     if (tid == 0) *n_rot = 0;
+    // With update, q is known: every rotation is applied to it as it is found (by the thread that
+    // found it: the pairs of a stage are disjoint), which is V^T q for the coefficients at no cost;
+    // the replay kernel then only goes backwards through the log.
+    if (tid < kGgtMaxM + 2) yv[tid] = (update && tid < n) ? sq[tid].x : 0.0;
     __syncthreads();
 
     // The 2x2 blocks a thread updates are the same pairs of pairs (k1 <= k2) in every stage; found
@@ -138,6 +143,11 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__
                 }
                 cs[tid] = make_double2(c, s);
                 rot[(int64_t)stage_out * 64 + tid] = make_double2(c, s);
+                if (s != 0.0) {
+                    const double yp = yv[p], yq = yv[q];
+                    yv[p] = c * yp - s * yq;
+                    yv[q] = s * yp + c * yq;
+                }
             }
             __syncthreads();
             // A <- J^T A J, one 2x2 block per (row pair, column pair) and its mirror image; all
@@ -179,12 +189,16 @@ __global__ __launch_bounds__(1024) void k_ggt_eig(int32_t m, const StepState *__
         if (done) break;                      // uniform: a whole sweep without a rotation that counts
     }
     if (tid < m) lam[tid] = tid < n ? A[tid * kGgtLd + tid] : 0.0;
+    if (update && tid < m) vtq[tid] = yv[tid];
     if (tid == 0) *n_stages = stage_out;
 }
 
 // One wave.  y = V^T q by the logged rotations in order, z_i = y_i / (eps sigma_i (sigma_i + eps)),
 // coef = V z by the log backwards.  q is sq[].x; coef of slots >= n is 0.
+// have_y != 0: coef_out holds V^T q already (left there by k_ggt_eig in the same step), the forward
+// pass is skipped.
 __global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, const StepState *__restrict__ step, double eps,
+                                                 int32_t have_y,
                                                  const double2 *__restrict__ sq,
                                                  const double *__restrict__ lam,
                                                  const double2 *__restrict__ rot,
@@ -199,7 +213,7 @@ __global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, const StepState *__r
     double lmax = 0.0;
     for (int32_t i = lane; i < kGgtMaxM + 2; i += 64) {
         const double qi = i < n ? sq[i].x : 0.0;
-        y[i] = qi;
+        y[i] = (have_y && i < n) ? coef_out[i] : qi;
         if (i < m) q_out[i] = i < n ? qi : 0.0;
         if (i < n) lmax = fmax(lmax, lam[i]);
     }
@@ -207,20 +221,37 @@ __global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, const StepState *__r
     for (int o = 32; o > 0; o >>= 1) lmax = fmax(lmax, __shfl_xor(lmax, o, 64));
     __syncthreads();
 
-    int32_t r = 0;
-    double2 nxt = stages > 0 ? rot[lane] : make_double2(1.0, 0.0);
-    for (int32_t st = 0; st < stages; st++) {
-        const double2 cur = nxt;
-        if (st + 1 < stages) nxt = rot[(int64_t)(st + 1) * 64 + lane];
-        if (lane < half && cur.y != 0.0) {
-            int32_t p, q;
-            rr_pair(N, r, lane, p, q);
-            const double yp = y[p], yq = y[q];
-            y[p] = cur.x * yp - cur.y * yq;
-            y[q] = cur.y * yp + cur.x * yq;
+    // The log is read kLogAhead stages ahead of its use (a stage is one LDS round trip long, a
+    // load of the log many): loads unconditional and clamped, stages past the end are identities.
+    constexpr int kLogAhead = 8;
+    auto fetch = [&](int32_t st0, int32_t dir, double2 (&b)[kLogAhead]) {
+#pragma unroll
+        for (int u = 0; u < kLogAhead; u++) {
+            const int32_t st = st0 + dir * u;
+            const double2 t = rot[(int64_t)min(max(st, 0), max(stages - 1, 0)) * 64 + lane];
+            b[u] = (st >= 0 && st < stages) ? t : make_double2(1.0, 0.0);
         }
-        __syncthreads();
-        r = r + 1 == N - 1 ? 0 : r + 1;
+    };
+    double2 ahead[kLogAhead];
+    int32_t r = 0;
+    if (!have_y) fetch(0, 1, ahead);
+    for (int32_t st0 = 0; st0 < (have_y ? 0 : stages); st0 += kLogAhead) {
+        double2 cur[kLogAhead];
+#pragma unroll
+        for (int u = 0; u < kLogAhead; u++) cur[u] = ahead[u];
+        fetch(st0 + kLogAhead, 1, ahead);
+#pragma unroll
+        for (int u = 0; u < kLogAhead; u++) {
+            if (lane < half && cur[u].y != 0.0) {          // (an identity past the end moves nothing)
+                int32_t p, q;
+                rr_pair(N, r, lane, p, q);
+                const double yp = y[p], yq = y[q];
+                y[p] = cur[u].x * yp - cur[u].y * yq;
+                y[q] = cur[u].y * yp + cur[u].x * yq;
+            }
+            __syncthreads();
+            r = r + 1 == N - 1 ? 0 : r + 1;
+        }
     }
     const double cut = (double)n * 0x1p-52 * lmax;
     for (int32_t i = lane; i < n; i += 64) {
@@ -235,26 +266,31 @@ __global__ __launch_bounds__(64) void k_ggt_coef(int32_t m, const StepState *__r
     __syncthreads();
     // backwards: stage st used r = st mod (N-1)
     int32_t rb = stages > 0 ? (stages - 1) % (N - 1) : 0;
-    nxt = stages > 0 ? rot[(int64_t)(stages - 1) * 64 + lane] : make_double2(1.0, 0.0);
-    for (int32_t st = stages - 1; st >= 0; st--) {
-        const double2 cur = nxt;
-        if (st > 0) nxt = rot[(int64_t)(st - 1) * 64 + lane];
-        if (lane < half && cur.y != 0.0) {
-            int32_t p, q;
-            rr_pair(N, rb, lane, p, q);
-            const double zp = y[p], zq = y[q];
-            y[p] = cur.x * zp + cur.y * zq;
-            y[q] = -cur.y * zp + cur.x * zq;
+    fetch(stages - 1, -1, ahead);
+    for (int32_t st0 = stages - 1; st0 >= 0; st0 -= kLogAhead) {
+        double2 cur[kLogAhead];
+#pragma unroll
+        for (int u = 0; u < kLogAhead; u++) cur[u] = ahead[u];
+        fetch(st0 - kLogAhead, -1, ahead);
+#pragma unroll
+        for (int u = 0; u < kLogAhead; u++) {
+            if (lane < half && cur[u].y != 0.0) {
+                int32_t p, q;
+                rr_pair(N, rb, lane, p, q);
+                const double zp = y[p], zq = y[q];
+                y[p] = cur[u].x * zp + cur[u].y * zq;
+                y[q] = -cur[u].y * zp + cur[u].x * zq;
+            }
+            __syncthreads();
+            rb = rb == 0 ? N - 2 : rb - 1;
         }
-        __syncthreads();
-        rb = rb == 0 ? N - 2 : rb - 1;
     }
     for (int32_t i = lane; i < m; i += 64) coef_out[i] = i < n ? y[i] : 0.0;
 }
 
 size_t ggt_eig_lds_bytes()
 {
-    return (size_t)kGgtMaxM * kGgtLd * sizeof(double) + 64 * sizeof(double2) + 16;
+    return (size_t)kGgtMaxM * kGgtLd * sizeof(double) + 64 * sizeof(double2) + 16 + (kGgtMaxM + 2) * sizeof(double);
 }
 
 hipError_t configure_ggt()
@@ -267,8 +303,8 @@ hipError_t configure_ggt()
 hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, double eps, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, p.step, 1, p.S,
-                       p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps);
-    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, p.step, eps, p.sq, p.lam, p.rot,
+                       p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps, p.coef);
+    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, p.step, eps, 1, p.sq, p.lam, p.rot,
                        p.n_stages, p.q, p.coef);
     return hipGetLastError();
 }
@@ -277,14 +313,14 @@ hipError_t launch_ggt_step(const Geometry &g, const DevicePtrs &p, double eps, h
 hipError_t launch_ggt_refresh(const Geometry &g, const DevicePtrs &p, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_ggt_eig, dim3(1), dim3(1024), ggt_eig_lds_bytes(), stream, g.m, p.step, 0, p.S,
-                       p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps);
+                       p.sq, p.q, p.lam, p.rot, p.n_stages, kGgtMaxSweeps, p.coef);
     return hipGetLastError();
 }
 
 // Coefficients for another x on the window as it stands: the decomposition of the last step is reused.
 hipError_t launch_ggt_apply(const Geometry &g, const DevicePtrs &p, double eps, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, p.step, eps, p.sq, p.lam, p.rot,
+    hipLaunchKernelGGL(k_ggt_coef, dim3(1), dim3(64), 0, stream, g.m, p.step, eps, 0, p.sq, p.lam, p.rot,
                        p.n_stages, p.q, p.coef);
     return hipGetLastError();
 }
